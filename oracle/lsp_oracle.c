@@ -1,0 +1,406 @@
+/*
+ * CPU oracle for the LSP compress / decompress-apply path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, obviously-correct loops in fp64.  It shares no code, header, table or
+ * helper with the HIP library and must never be linked or called by the product path;
+ * only the tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ *
+ * What it computes (this repository's letters: G, W are m x n; r = subspace size;
+ * d = nonzeros per projector row; the paper calls the subspace size "d" and the
+ * nonzeros per row "r"):
+ *
+ *   compress          S = P^T G Q             -- Alg. 1, the "Compress on GPU and gradient
+ *                                                offload" step; Alg. 3, the step that forms
+ *                                                the projected gradient of a layer
+ *   decompress-apply  W <- W - P S Q^T        -- Alg. 1, "Decompress, apply deltas on GPU";
+ *                                                Alg. 3, the last step of the layer loop
+ *
+ * P (m x r) and Q (n x r) are (d,r)-sparse projectors in the sense of Def. 1: exactly d
+ * stored entries per row, kept in ELL layout as idx[row][k] (int32 column in [0,r)) and
+ * val[row][k] (fp32).  The dense view is  Phat[i][a] = sum over k with idx[i][k]==a of
+ * val[i][k]  (duplicate columns in one row add; val == 0 entries are padding).
+ * The learning-rate factor of Alg. 1 is taken to be folded into S by the CPU optimiser.
+ * The weight expression in Table 2 (P^T S Q) is dimensionally impossible for P in
+ * R^{m x r}; Eq. 1 and both algorithms use P S Q^T, which is what is computed here.
+ *
+ * Two forms are provided:
+ *   *_dense   the definition written out literally on densified projectors, O(m n r^2);
+ *             for tiny inputs only; it is what the working form is pinned against.
+ *   working   associativity only:  T = G Q, S = P^T T;   U = P S, W' = W - U Q^T.
+ *
+ * Storage types: 0 = fp32, 1 = fp16 (IEEE binary16), 2 = bf16.  Every stored value is
+ * widened exactly to fp64; results are produced in fp64 and, for W, additionally rounded
+ * ONCE (nearest, ties to even) from fp64 to the storage type.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORA_F32 = 0, ORA_F16 = 1, ORA_BF16 = 2 };
+
+/* ---------------------------------------------------------------- storage <-> fp64 */
+
+static double f16_bits_to_double(uint16_t h) {
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1F;
+    int f = h & 0x3FF;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -24);                 /* subnormal: f * 2^-10 * 2^-14 */
+    } else if (e == 31) {
+        v = f ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(f | 0x400), e - 25);    /* (1024+f) * 2^(e-15-10) */
+    }
+    return sign ? -v : v;
+}
+
+static double bf16_bits_to_double(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double load_elem(const void *base, int64_t k, int dtype) {
+    switch (dtype) {
+        case ORA_F32:  return (double)((const float *)base)[k];
+        case ORA_F16:  return f16_bits_to_double(((const uint16_t *)base)[k]);
+        default:       return bf16_bits_to_double(((const uint16_t *)base)[k]);
+    }
+}
+
+/* Round x (fp64) to a binary format with p significand bits (hidden bit included),
+ * minimum normal exponent emin, maximum exponent emax; nearest, ties to even; gradual
+ * underflow.  The result is returned as an fp64 that is exactly representable in the format
+ * (or +-inf on overflow).  rint() rounds ties to even in the default rounding mode. */
+static double round_to_format(double x, int p, int emin, int emax) {
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e = ilogb(x);
+    if (e < emin) e = emin;
+    double q = ldexp(1.0, e - (p - 1));            /* spacing of the format at this exponent */
+    double y = rint(x / q) * q;
+    double lim = ldexp(2.0 - ldexp(1.0, -(p - 1)), emax);   /* largest finite value */
+    if (fabs(y) > lim) return x > 0 ? INFINITY : -INFINITY;
+    return y;
+}
+
+static uint16_t double_to_f16_bits(double y) {     /* y must be exactly representable */
+    uint16_t sign = signbit(y) ? 0x8000 : 0;
+    double a = fabs(y);
+    if (isnan(y)) return 0x7E00;
+    if (isinf(y)) return sign | 0x7C00;
+    if (a == 0.0) return sign;
+    int e = ilogb(a);
+    if (e < -14) {
+        return sign | (uint16_t)llrint(ldexp(a, 24));
+    }
+    uint32_t mant = (uint32_t)llrint(ldexp(a, 10 - e));      /* in [1024, 2048) */
+    return sign | (uint16_t)(((e + 15) << 10) | (mant & 0x3FF));
+}
+
+static uint16_t double_to_bf16_bits(double y) {    /* y must be exactly representable */
+    float f = (float)y;                            /* exact: bf16 values are fp32 values */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if (isnan(y)) return 0x7FC0;
+    return (uint16_t)(u >> 16);
+}
+
+static void store_rounded(void *base, int64_t k, int dtype, double x) {
+    switch (dtype) {
+        case ORA_F32:
+            ((float *)base)[k] = (float)x;         /* one IEEE rounding fp64 -> fp32 (RNE) */
+            break;
+        case ORA_F16:
+            ((uint16_t *)base)[k] = double_to_f16_bits(round_to_format(x, 11, -14, 15));
+            break;
+        default:
+            ((uint16_t *)base)[k] = double_to_bf16_bits(round_to_format(x, 8, -126, 127));
+            break;
+    }
+}
+
+/* exposed so the tests can pin the rounding helpers against numpy's own conversions */
+double lsp_oracle_round_to_storage(double x, int dtype) {
+    if (dtype == ORA_F32) return (double)(float)x;
+    if (dtype == ORA_F16) return round_to_format(x, 11, -14, 15);
+    return round_to_format(x, 8, -126, 127);
+}
+double lsp_oracle_widen(const void *base, int64_t k, int dtype) { return load_elem(base, k, dtype); }
+
+/* ---------------------------------------------------------------- definition, literal */
+
+static double *densify(const int32_t *idx, const float *val, int64_t rows, int r, int d) {
+    double *D = (double *)calloc((size_t)rows * (size_t)r, sizeof(double));
+    if (!D) return NULL;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int k = 0; k < d; ++k)
+            D[i * r + idx[i * d + k]] += (double)val[i * d + k];
+    return D;
+}
+
+/* S[a][b] = sum_i sum_j Phat[i][a] * G[i][j] * Qhat[j][b]   (compress step, written out) */
+int lsp_oracle_compress_dense(const void *G, int dtype,
+                              const int32_t *P_idx, const float *P_val,
+                              const int32_t *Q_idx, const float *Q_val,
+                              int64_t m, int64_t n, int r, int d, double *S) {
+    double *Ph = densify(P_idx, P_val, m, r, d);
+    double *Qh = densify(Q_idx, Q_val, n, r, d);
+    if (!Ph || !Qh) { free(Ph); free(Qh); return -1; }
+    for (int a = 0; a < r; ++a)
+        for (int b = 0; b < r; ++b) {
+            double acc = 0.0;
+            for (int64_t i = 0; i < m; ++i)
+                for (int64_t j = 0; j < n; ++j)
+                    acc += Ph[i * r + a] * load_elem(G, i * n + j, dtype) * Qh[j * r + b];
+            S[(int64_t)a * r + b] = acc;
+        }
+    free(Ph); free(Qh);
+    return 0;
+}
+
+/* W'[i][j] = W[i][j] - sum_a sum_b Phat[i][a] * S[a][b] * Qhat[j][b]   (decompress-apply) */
+int lsp_oracle_decompress_apply_dense(const void *W, int dtype, const float *S,
+                                      const int32_t *P_idx, const float *P_val,
+                                      const int32_t *Q_idx, const float *Q_val,
+                                      int64_t m, int64_t n, int r, int d,
+                                      double *Wprime, void *W_out) {
+    double *Ph = densify(P_idx, P_val, m, r, d);
+    double *Qh = densify(Q_idx, Q_val, n, r, d);
+    if (!Ph || !Qh) { free(Ph); free(Qh); return -1; }
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double delta = 0.0;
+            for (int a = 0; a < r; ++a)
+                for (int b = 0; b < r; ++b)
+                    delta += Ph[i * r + a] * (double)S[(int64_t)a * r + b] * Qh[j * r + b];
+            double w = load_elem(W, i * n + j, dtype) - delta;
+            if (Wprime) Wprime[i * n + j] = w;
+            if (W_out) store_rounded(W_out, i * n + j, dtype, w);
+        }
+    free(Ph); free(Qh);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- working form */
+
+/* rows [i0, i1) of the compress sum, accumulated into S (which the caller zeroed).
+ * Trow is scratch of r doubles.   T[i][:] = G[i][:] Q ;   S += P[i][:]^T T[i][:] */
+static void compress_rows(const void *G, int dtype,
+                          const int32_t *P_idx, const float *P_val,
+                          const int32_t *Q_idx, const float *Q_val,
+                          int64_t i0, int64_t i1, int64_t n, int r, int d,
+                          double *Trow, double *S) {
+    for (int64_t i = i0; i < i1; ++i) {
+        for (int b = 0; b < r; ++b) Trow[b] = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+            double g = load_elem(G, i * n + j, dtype);
+            for (int k = 0; k < d; ++k)
+                Trow[Q_idx[j * d + k]] += g * (double)Q_val[j * d + k];
+        }
+        for (int k = 0; k < d; ++k) {
+            double pv = (double)P_val[i * d + k];
+            double *Srow = S + (int64_t)P_idx[i * d + k] * r;
+            for (int b = 0; b < r; ++b) Srow[b] += pv * Trow[b];
+        }
+    }
+}
+
+/* S (r x r, fp64, overwritten) = P^T G Q */
+int lsp_oracle_compress(const void *G, int dtype,
+                        const int32_t *P_idx, const float *P_val,
+                        const int32_t *Q_idx, const float *Q_val,
+                        int64_t m, int64_t n, int r, int d, double *S) {
+    double *Trow = (double *)malloc((size_t)r * sizeof(double));
+    if (!Trow) return -1;
+    memset(S, 0, (size_t)r * (size_t)r * sizeof(double));
+    compress_rows(G, dtype, P_idx, P_val, Q_idx, Q_val, 0, m, n, r, d, Trow, S);
+    free(Trow);
+    return 0;
+}
+
+/* rows [i0, i1):  U[i][:] = P[i][:] S ;  W'[i][j] = W[i][j] - sum_k U[i][Q_idx[j][k]] Q_val[j][k] */
+static void decompress_rows(const void *W, int dtype, const float *S,
+                            const int32_t *P_idx, const float *P_val,
+                            const int32_t *Q_idx, const float *Q_val,
+                            int64_t i0, int64_t i1, int64_t n, int r, int d,
+                            double *Urow, double *Wprime, void *W_out) {
+    for (int64_t i = i0; i < i1; ++i) {
+        for (int b = 0; b < r; ++b) Urow[b] = 0.0;
+        for (int k = 0; k < d; ++k) {
+            double pv = (double)P_val[i * d + k];
+            const float *Srow = S + (int64_t)P_idx[i * d + k] * r;
+            for (int b = 0; b < r; ++b) Urow[b] += pv * (double)Srow[b];
+        }
+        for (int64_t j = 0; j < n; ++j) {
+            double delta = 0.0;
+            for (int k = 0; k < d; ++k)
+                delta += Urow[Q_idx[j * d + k]] * (double)Q_val[j * d + k];
+            double w = load_elem(W, i * n + j, dtype) - delta;
+            if (Wprime) Wprime[i * n + j] = w;
+            if (W_out) store_rounded(W_out, i * n + j, dtype, w);
+        }
+    }
+}
+
+/* W' = W - P S Q^T.  Wprime (fp64, m x n) and/or W_out (storage type, m x n) may be NULL.
+ * W itself is not modified. */
+int lsp_oracle_decompress_apply(const void *W, int dtype, const float *S,
+                                const int32_t *P_idx, const float *P_val,
+                                const int32_t *Q_idx, const float *Q_val,
+                                int64_t m, int64_t n, int r, int d,
+                                double *Wprime, void *W_out) {
+    double *Urow = (double *)malloc((size_t)r * sizeof(double));
+    if (!Urow) return -1;
+    decompress_rows(W, dtype, S, P_idx, P_val, Q_idx, Q_val, 0, m, n, r, d, Urow, Wprime, W_out);
+    free(Urow);
+    return 0;
+}
+
+/* Selected rows only (for sampled checks at sizes where all m rows would take too long):
+ * out[t][j] = W'[rows[t]][j], fp64, nrows x n. */
+int lsp_oracle_decompress_rows(const void *W, int dtype, const float *S,
+                               const int32_t *P_idx, const float *P_val,
+                               const int32_t *Q_idx, const float *Q_val,
+                               int64_t m, int64_t n, int r, int d,
+                               const int64_t *rows, int64_t nrows, double *out) {
+    double *Urow = (double *)malloc((size_t)r * sizeof(double));
+    if (!Urow) return -1;
+    for (int64_t t = 0; t < nrows; ++t) {
+        int64_t i = rows[t];
+        if (i < 0 || i >= m) { free(Urow); return -2; }
+        for (int b = 0; b < r; ++b) Urow[b] = 0.0;
+        for (int k = 0; k < d; ++k) {
+            double pv = (double)P_val[i * d + k];
+            const float *Srow = S + (int64_t)P_idx[i * d + k] * r;
+            for (int b = 0; b < r; ++b) Urow[b] += pv * (double)Srow[b];
+        }
+        for (int64_t j = 0; j < n; ++j) {
+            double delta = 0.0;
+            for (int k = 0; k < d; ++k)
+                delta += Urow[Q_idx[j * d + k]] * (double)Q_val[j * d + k];
+            out[t * n + j] = load_elem(W, i * n + j, dtype) - delta;
+        }
+    }
+    free(Urow);
+    return 0;
+}
+
+/* Selected entries of S only:  out[t] = S[a_t][b_t], by the definition restricted to the
+ * rows of P that touch a_t and the rows of Q that touch b_t (no intermediate T). */
+int lsp_oracle_compress_entries(const void *G, int dtype,
+                                const int32_t *P_idx, const float *P_val,
+                                const int32_t *Q_idx, const float *Q_val,
+                                int64_t m, int64_t n, int r, int d,
+                                const int32_t *ea, const int32_t *eb, int64_t nent, double *out) {
+    (void)r;
+    for (int64_t t = 0; t < nent; ++t) {
+        int a = ea[t], b = eb[t];
+        double acc = 0.0;
+        for (int64_t i = 0; i < m; ++i) {
+            double pa = 0.0;
+            for (int k = 0; k < d; ++k)
+                if (P_idx[i * d + k] == a) pa += (double)P_val[i * d + k];
+            if (pa == 0.0) continue;
+            double rowsum = 0.0;
+            for (int64_t j = 0; j < n; ++j) {
+                double qb = 0.0;
+                for (int k = 0; k < d; ++k)
+                    if (Q_idx[j * d + k] == b) qb += (double)Q_val[j * d + k];
+                if (qb != 0.0) rowsum += load_elem(G, i * n + j, dtype) * qb;
+            }
+            acc += pa * rowsum;
+        }
+        out[t] = acc;
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------- same loops, rows split over threads
+ *
+ * Used only to time the oracle on all host cores.  The arithmetic is the working form above,
+ * unchanged: compress gives each thread a private S over a contiguous row range and adds the
+ * private copies at the end; decompress gives each thread a disjoint row range. */
+#include <pthread.h>
+
+typedef struct {
+    const void *X; int dtype; const float *S_in;
+    const int32_t *P_idx; const float *P_val; const int32_t *Q_idx; const float *Q_val;
+    int64_t i0, i1, n; int r, d;
+    double *S_priv; double *Wprime; void *W_out; int rc;
+} ora_job;
+
+static void *compress_worker(void *arg) {
+    ora_job *j = (ora_job *)arg;
+    double *Trow = (double *)malloc((size_t)j->r * sizeof(double));
+    if (!Trow) { j->rc = -1; return NULL; }
+    compress_rows(j->X, j->dtype, j->P_idx, j->P_val, j->Q_idx, j->Q_val,
+                  j->i0, j->i1, j->n, j->r, j->d, Trow, j->S_priv);
+    free(Trow);
+    j->rc = 0;
+    return NULL;
+}
+
+static void *decompress_worker(void *arg) {
+    ora_job *j = (ora_job *)arg;
+    double *Urow = (double *)malloc((size_t)j->r * sizeof(double));
+    if (!Urow) { j->rc = -1; return NULL; }
+    decompress_rows(j->X, j->dtype, j->S_in, j->P_idx, j->P_val, j->Q_idx, j->Q_val,
+                    j->i0, j->i1, j->n, j->r, j->d, Urow, j->Wprime, j->W_out);
+    free(Urow);
+    j->rc = 0;
+    return NULL;
+}
+
+int lsp_oracle_compress_mt(const void *G, int dtype,
+                           const int32_t *P_idx, const float *P_val,
+                           const int32_t *Q_idx, const float *Q_val,
+                           int64_t m, int64_t n, int r, int d, double *S, int nthreads) {
+    if (nthreads < 1) nthreads = 1;
+    if (nthreads > m) nthreads = (int)m;
+    size_t rr = (size_t)r * (size_t)r;
+    double *priv = (double *)calloc(rr * (size_t)nthreads, sizeof(double));
+    pthread_t *th = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)nthreads);
+    ora_job *jobs = (ora_job *)calloc((size_t)nthreads, sizeof(ora_job));
+    if (!priv || !th || !jobs) { free(priv); free(th); free(jobs); return -1; }
+    for (int t = 0; t < nthreads; ++t) {
+        ora_job *j = &jobs[t];
+        j->X = G; j->dtype = dtype; j->P_idx = P_idx; j->P_val = P_val; j->Q_idx = Q_idx; j->Q_val = Q_val;
+        j->i0 = m * t / nthreads; j->i1 = m * (t + 1) / nthreads; j->n = n; j->r = r; j->d = d;
+        j->S_priv = priv + rr * (size_t)t;
+        pthread_create(&th[t], NULL, compress_worker, j);
+    }
+    int rc = 0;
+    for (int t = 0; t < nthreads; ++t) { pthread_join(th[t], NULL); if (jobs[t].rc) rc = jobs[t].rc; }
+    memset(S, 0, rr * sizeof(double));
+    for (int t = 0; t < nthreads; ++t)
+        for (size_t k = 0; k < rr; ++k) S[k] += priv[rr * (size_t)t + k];
+    free(priv); free(th); free(jobs);
+    return rc;
+}
+
+int lsp_oracle_decompress_apply_mt(const void *W, int dtype, const float *S,
+                                   const int32_t *P_idx, const float *P_val,
+                                   const int32_t *Q_idx, const float *Q_val,
+                                   int64_t m, int64_t n, int r, int d,
+                                   double *Wprime, void *W_out, int nthreads) {
+    if (nthreads < 1) nthreads = 1;
+    if (nthreads > m) nthreads = (int)m;
+    pthread_t *th = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)nthreads);
+    ora_job *jobs = (ora_job *)calloc((size_t)nthreads, sizeof(ora_job));
+    if (!th || !jobs) { free(th); free(jobs); return -1; }
+    for (int t = 0; t < nthreads; ++t) {
+        ora_job *j = &jobs[t];
+        j->X = W; j->dtype = dtype; j->S_in = S;
+        j->P_idx = P_idx; j->P_val = P_val; j->Q_idx = Q_idx; j->Q_val = Q_val;
+        j->i0 = m * t / nthreads; j->i1 = m * (t + 1) / nthreads; j->n = n; j->r = r; j->d = d;
+        j->Wprime = Wprime; j->W_out = W_out;
+        pthread_create(&th[t], NULL, decompress_worker, j);
+    }
+    int rc = 0;
+    for (int t = 0; t < nthreads; ++t) { pthread_join(th[t], NULL); if (jobs[t].rc) rc = jobs[t].rc; }
+    free(th); free(jobs);
+    return rc;
+}

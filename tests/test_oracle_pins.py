@@ -1,0 +1,358 @@
+"""Pins for the CPU oracle (no GPU).  Each test fixes the oracle against something that is
+not the oracle: hand-worked numbers, the literal dense definition, independent few-line
+loops, algebraic identities, numpy's fp64 GEMM, numpy's own fp16 conversion.
+
+They are chosen so that a plausible mistake (dropped term, wrong sign, transposed or
+mis-paired projector, wrong index stride, double rounding) fails at least one of them.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import lsp_synth as syn
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _dense(idx, val, r):
+    rows, d = idx.shape
+    D = np.zeros((rows, r), dtype=np.float64)
+    for i in range(rows):
+        for k in range(d):
+            D[i, idx[i, k]] += float(val[i, k])
+    return D
+
+
+# ---------------------------------------------------------------- hand-worked example
+def _read_golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = np.array([float(v) for v in vals])
+    return out
+
+
+def test_hand_worked_example():
+    gold = _read_golden("hand_case_2x3.txt")
+    G = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.float32)
+    P_idx = np.array([[1], [0]], dtype=np.int32)
+    P_val = np.array([[2], [3]], dtype=np.float32)
+    Q_idx = np.array([[0], [1], [0]], dtype=np.int32)
+    Q_val = np.array([[1], [-1], [0.5]], dtype=np.float32)
+    for dense in (False, True):
+        S = oracle.compress(G, "f32", P_idx, P_val, Q_idx, Q_val, 2, dense=dense)
+        assert np.array_equal(S.ravel(), gold["S"])
+        S2 = np.array([[1, 0], [0, 2]], dtype=np.float32)
+        W0 = np.zeros((2, 3), dtype=np.float32)
+        Wp, Wr = oracle.decompress_apply(W0, "f32", S2, P_idx, P_val, Q_idx, Q_val, dense=dense)
+        assert np.array_equal(Wp.ravel(), gold["W"])
+        assert np.array_equal(Wr.ravel().astype(np.float64), gold["W"])
+
+
+def test_hand_worked_asymmetry_is_detected():
+    """The example is not symmetric under P<->Q or transposition, so a mis-paired operand
+    cannot give the same numbers (guards the fixture's power, on the CPU)."""
+    gold = _read_golden("hand_case_2x3.txt")
+    G = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.float64)
+    Ph = np.array([[0, 2], [3, 0]], dtype=np.float64)
+    Qh = np.array([[1, 0], [0, -1], [0.5, 0]], dtype=np.float64)
+    right = Ph.T @ G @ Qh
+    assert np.array_equal(right.ravel(), gold["S"])
+    assert not np.array_equal((Ph.T @ G @ Qh).T.ravel(), gold["S"])
+
+
+# ---------------------------------------------------------------- pin 1: literal definition
+@pytest.mark.parametrize("m,n,r,d,dist,dtype", [
+    (5, 7, 3, 2, "uniform", "f32"),
+    (12, 9, 6, 3, "uniform", "f32"),
+    (7, 12, 4, 4, "distinct", "f32"),      # d == r
+    (6, 6, 5, 3, "zipf", "f32"),           # duplicates certain
+    (9, 5, 6, 2, "uniform", "bf16"),
+    (8, 11, 4, 1, "uniform", "f16"),
+    (1, 1, 1, 1, "uniform", "f32"),
+])
+def test_working_form_equals_literal_definition(m, n, r, d, dist, dtype):
+    pb = syn.make_problem("t", m, n, r, d, dtype, seed=100 + m * n, g_std=1.0, w_std=1.0, s_std=1.0,
+                          index_dist=dist)
+    S_w = oracle.compress(pb.G, dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r)
+    S_d = oracle.compress(pb.G, dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r, dense=True)
+    np.testing.assert_allclose(S_w, S_d, rtol=0, atol=1e-12 * max(1.0, np.abs(S_d).max()))
+    Wp_w, Wr_w = oracle.decompress_apply(pb.W, dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    Wp_d, Wr_d = oracle.decompress_apply(pb.W, dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val,
+                                         dense=True)
+    np.testing.assert_allclose(Wp_w, Wp_d, rtol=0, atol=1e-12 * max(1.0, np.abs(Wp_d).max()))
+
+
+# ---------------------------------------------------------------- pin 6: numpy fp64 GEMM
+@pytest.mark.parametrize("maker", [syn.config1,
+                                   lambda: syn.make_problem("t", 96, 160, 32, 4, "bf16", 7),
+                                   lambda: syn.make_problem("t", 200, 72, 24, 3, "f16", 8,
+                                                            index_dist="zipf")])
+def test_against_numpy_gemm(maker):
+    pb = maker()
+    Ph, Qh = _dense(pb.P_idx, pb.P_val, pb.r), _dense(pb.Q_idx, pb.Q_val, pb.r)
+    G64 = syn.storage_to_f64(pb.G, pb.dtype)
+    W64 = syn.storage_to_f64(pb.W, pb.dtype)
+    S = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    ref = Ph.T @ G64 @ Qh
+    np.testing.assert_allclose(S, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+    Wp, Wr = oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    refW = W64 - Ph @ pb.S_in.astype(np.float64) @ Qh.T
+    np.testing.assert_allclose(Wp, refW, rtol=0, atol=1e-13)
+    # the rounded output is the fp64 value rounded once to the storage type
+    back = syn.storage_to_f64(Wr, pb.dtype)
+    assert np.all(np.abs(back - Wp) <= 0.5 * syn.ulp_of(Wp, pb.dtype) * (1 + 1e-12))
+
+
+# ---------------------------------------------------------------- pin 2: selection projectors
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_selection_projectors_give_block_sums(dtype):
+    rng = _rng(11)
+    m, n, r = 37, 53, 6
+    G = syn.integer_matrix(m, n, -8, 8, dtype, rng)
+    p = rng.integers(0, r, size=m).astype(np.int32)
+    q = rng.integers(0, r, size=n).astype(np.int32)
+    ones_m = np.ones((m, 1), dtype=np.float32)
+    ones_n = np.ones((n, 1), dtype=np.float32)
+    S = oracle.compress(G, dtype, p.reshape(m, 1), ones_m, q.reshape(n, 1), ones_n, r)
+    G64 = syn.storage_to_f64(G, dtype)
+    ref = np.zeros((r, r))
+    for i in range(m):                      # independent: plain block sums of G
+        for j in range(n):
+            ref[p[i], q[j]] += G64[i, j]
+    assert np.array_equal(S, ref)
+
+
+# ---------------------------------------------------------------- pin 3: linearity
+def test_linearity_exact_on_integers():
+    rng = _rng(12)
+    m, n, r, d = 40, 33, 8, 3
+    P_idx, P_val = syn.ell_projector(m, r, d, rng, "uniform", value_mode="smallint")
+    Q_idx, Q_val = syn.ell_projector(n, r, d, rng, "uniform", value_mode="smallint")
+    G1 = syn.integer_matrix(m, n, -8, 8, "f32", rng)
+    G2 = syn.integer_matrix(m, n, -8, 8, "f32", rng)
+    S1 = oracle.compress(G1, "f32", P_idx, P_val, Q_idx, Q_val, r)
+    S2 = oracle.compress(G2, "f32", P_idx, P_val, Q_idx, Q_val, r)
+    S12 = oracle.compress((2 * G1 - 4 * G2).astype(np.float32), "f32", P_idx, P_val, Q_idx, Q_val, r)
+    assert np.array_equal(S12, 2 * S1 - 4 * S2)
+    # decompress is affine in S: W - P(2A-4B)Q^T = W - 2(PAQ^T) + 4(PBQ^T)
+    A = rng.integers(-2, 3, size=(r, r)).astype(np.float32)
+    B = rng.integers(-2, 3, size=(r, r)).astype(np.float32)
+    Z = np.zeros((m, n), dtype=np.float32)
+    dA, _ = oracle.decompress_apply(Z, "f32", A, P_idx, P_val, Q_idx, Q_val)
+    dB, _ = oracle.decompress_apply(Z, "f32", B, P_idx, P_val, Q_idx, Q_val)
+    dAB, _ = oracle.decompress_apply(Z, "f32", 2 * A - 4 * B, P_idx, P_val, Q_idx, Q_val)
+    assert np.array_equal(dAB, 2 * dA - 4 * dB)
+
+
+# ---------------------------------------------------------------- pin 4: permutation round trip
+def test_permutation_round_trip():
+    rng = _rng(13)
+    m, n = 19, 23
+    G = rng.standard_normal((m, n)).astype(np.float32)
+    p_idx, p_val = syn.permutation_projector(m, rng)
+    # r is shared by P and Q, so use r = max(m, n) and an injective map for the shorter side
+    r = max(m, n)
+    q_idx, q_val = syn.permutation_projector(n, rng)
+    S = oracle.compress(G, "f32", p_idx, p_val, q_idx, q_val, r)
+    for i in range(m):
+        for j in range(n):
+            assert S[p_idx[i, 0], q_idx[j, 0]] == float(G[i, j])
+    assert np.count_nonzero(S) <= m * n
+    Wp, _ = oracle.decompress_apply(np.zeros((m, n), np.float32), "f32", S.astype(np.float32),
+                                    p_idx, p_val, q_idx, q_val)
+    assert np.array_equal(Wp, -G.astype(np.float64))      # bias b^{P,Q}(G) = P P^T G Q Q^T - G = 0
+
+
+# ---------------------------------------------------------------- pin 5: adjoint identity
+@pytest.mark.parametrize("dist", ["uniform", "zipf"])
+def test_adjoint_identity(dist):
+    pb = syn.make_problem("t", 45, 61, 12, 3, "f32", seed=14, g_std=1.0, s_std=1.0, index_dist=dist)
+    S = oracle.compress(pb.G, "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    Z = np.zeros((pb.m, pb.n), dtype=np.float32)
+    D, _ = oracle.decompress_apply(Z, "f32", pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    lhs = np.sum(S * pb.S_in.astype(np.float64))                  # <P^T G Q, S'>
+    rhs = np.sum(pb.G.astype(np.float64) * (-D))                  # <G, P S' Q^T>
+    assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), abs(rhs), 1.0)
+
+
+# ---------------------------------------------------------------- pin 7: zero / padding / duplicates
+def test_zero_padding_and_duplicates():
+    rng = _rng(15)
+    m, n, r, d = 14, 17, 5, 3
+    pb = syn.make_problem("t", m, n, r, d, "bf16", seed=16, g_std=1.0, w_std=1.0, s_std=1.0)
+    Zs = np.zeros((r, r), dtype=np.float32)
+    # G = 0 -> S = 0
+    S0 = oracle.compress(np.zeros((m, n), np.uint16), "bf16", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r)
+    assert not S0.any()
+    # S = 0 -> W unchanged bit for bit
+    Wp, Wr = oracle.decompress_apply(pb.W, "bf16", Zs, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    assert np.array_equal(Wr, pb.W)
+    # padding entries (val = 0, any index) change nothing
+    P_idx2 = np.concatenate([pb.P_idx, rng.integers(0, r, size=(m, 2)).astype(np.int32)], axis=1)
+    P_val2 = np.concatenate([pb.P_val, np.zeros((m, 2), np.float32)], axis=1)
+    Q_idx2 = np.concatenate([pb.Q_idx, rng.integers(0, r, size=(n, 2)).astype(np.int32)], axis=1)
+    Q_val2 = np.concatenate([pb.Q_val, np.zeros((n, 2), np.float32)], axis=1)
+    S_a = oracle.compress(pb.G, "bf16", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r)
+    S_b = oracle.compress(pb.G, "bf16", P_idx2, P_val2, Q_idx2, Q_val2, r)
+    np.testing.assert_allclose(S_a, S_b, rtol=0, atol=1e-13 * np.abs(S_a).max())
+    # a duplicated index pair (a, v1), (a, v2) equals a single (a, v1 + v2)
+    Pi = np.array([[2, 2]] * m, dtype=np.int32)
+    Pv = np.array([[0.5, 1.5]] * m, dtype=np.float32)
+    Qi = pb.Q_idx[:, :2].copy()
+    Qv = pb.Q_val[:, :2].copy()
+    S_dup = oracle.compress(pb.G, "bf16", Pi, Pv, Qi, Qv, r)
+    Pi_eq = np.array([[2, 0]] * m, dtype=np.int32)
+    Pv_eq = np.array([[2.0, 0.0]] * m, dtype=np.float32)
+    S_eq = oracle.compress(pb.G, "bf16", Pi_eq, Pv_eq, Qi, Qv, r)
+    np.testing.assert_allclose(S_dup, S_eq, rtol=0, atol=1e-13 * max(np.abs(S_eq).max(), 1e-300))
+
+
+# ---------------------------------------------------------------- pin 9: separability
+def test_rank_one_separability():
+    rng = _rng(17)
+    m, n, r, d = 50, 41, 9, 3
+    P_idx, P_val = syn.ell_projector(m, r, d, rng)
+    Q_idx, Q_val = syn.ell_projector(n, r, d, rng)
+    u = rng.standard_normal(m).astype(np.float32)
+    v = rng.standard_normal(n).astype(np.float32)
+    G = np.outer(u.astype(np.float64), v.astype(np.float64)).astype(np.float32)
+    G64 = G.astype(np.float64)
+    S = oracle.compress(G, "f32", P_idx, P_val, Q_idx, Q_val, r)
+    # two independent sparse mat-vecs on the fp32-rounded outer product's factors would differ by
+    # the rounding of G; use the rounded G's own row/column structure instead: S = Phat^T G Qhat
+    pu = np.zeros(r)
+    for i in range(m):
+        for k in range(d):
+            pu[P_idx[i, k]] += float(P_val[i, k]) * float(u[i])
+    qv = np.zeros(r)
+    for j in range(n):
+        for k in range(d):
+            qv[Q_idx[j, k]] += float(Q_val[j, k]) * float(v[j])
+    approx = np.outer(pu, qv)
+    # G was rounded to fp32 element-wise: relative perturbation <= 2^-24 per term
+    bound = 2.0 ** -23 * (np.abs(_dense(P_idx, P_val, r)).T @ np.abs(G64) @ np.abs(_dense(Q_idx, Q_val, r)))
+    assert np.all(np.abs(S - approx) <= bound + 1e-15)
+
+
+# ---------------------------------------------------------------- pin 8: generator scale (unbiasedness)
+def test_generator_unbiasedness_pins_variance_reading():
+    """E[Phat Phat^T] = I holds only if the values have variance 1/d (the reading of the
+    paper's N(0, 1/sqrt(d)) as a standard deviation).  Also pins mean(decompress(compress(G))) -> G."""
+    m, n, r, d = 12, 10, 24, 4
+    G = _rng(18).standard_normal((m, n)).astype(np.float32)
+    acc = np.zeros((m, m))
+    accG = np.zeros((m, n))
+    trials = 600
+    for t in range(trials):
+        rng = _rng(1000 + t)
+        P_idx, P_val = syn.ell_projector(m, r, d, rng, "distinct")
+        Q_idx, Q_val = syn.ell_projector(n, r, d, rng, "distinct")
+        Ph = _dense(P_idx, P_val, r)
+        acc += Ph @ Ph.T
+        S = oracle.compress(G, "f32", P_idx, P_val, Q_idx, Q_val, r)
+        D, _ = oracle.decompress_apply(np.zeros((m, n), np.float32), "f32", S.astype(np.float32),
+                                       P_idx, P_val, Q_idx, Q_val)
+        accG += -D
+    acc /= trials
+    accG /= trials
+    assert np.abs(np.diag(acc) - 1.0).max() < 0.15
+    off = acc - np.diag(np.diag(acc))
+    assert np.abs(off).max() < 0.15
+    # variance 1/d^2 or 1 (the other readings) would put the diagonal at 1/d or d: far outside
+    rel = np.linalg.norm(accG - G) / np.linalg.norm(G)
+    assert rel < 0.35
+
+
+# ---------------------------------------------------------------- storage conversions
+def test_widening_and_rounding_against_numpy():
+    rng = _rng(19)
+    # every fp16 bit pattern widens exactly as numpy widens it
+    bits = np.arange(0, 1 << 16, dtype=np.uint16)
+    h = bits.view(np.float16)
+    sample = rng.choice(bits.size, size=4000, replace=False)
+    for k in sample:
+        a = oracle.widen(h, int(k), "f16")
+        b = float(h[k])
+        assert (np.isnan(a) and np.isnan(b)) or a == b
+    # bf16 widening = bits << 16
+    bb = rng.integers(0, 1 << 16, size=2000).astype(np.uint16)
+    f = syn.bf16_bits_to_f32(bb)
+    for k in range(0, 2000, 7):
+        a = oracle.widen(bb, k, "bf16")
+        assert (np.isnan(a) and np.isnan(f[k])) or a == float(f[k])
+    # rounding fp64 -> fp16 equals numpy's direct float64 -> float16 conversion (single rounding)
+    xs = np.concatenate([rng.standard_normal(3000) * 10.0 ** rng.integers(-9, 5, size=3000),
+                         np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e6, 6e-8, 2.98e-8, 2.99e-8,
+                                   6.103515625e-05, 6.1e-05, 1.0 + 2 ** -11, 1.0 + 3 * 2 ** -11])])
+    for x in xs:
+        a = oracle.round_to_storage(float(x), "f16")
+        b = float(np.float64(x).astype(np.float16))
+        assert a == b, (x, a, b)
+    # rounding fp64 -> bf16: ties to even on hand-picked cases, and agreement with the
+    # integer bit trick on values that are exactly fp32
+    assert oracle.round_to_storage(1.0 + 2 ** -8, "bf16") == 1.0            # tie -> even (1.0)
+    assert oracle.round_to_storage(1.0 + 3 * 2 ** -8, "bf16") == 1.0 + 2 ** -6   # tie -> even
+    assert oracle.round_to_storage(1.0 + 2 ** -8 + 2 ** -30, "bf16") == 1.0 + 2 ** -7
+    x32 = (rng.standard_normal(3000) * 10.0 ** rng.integers(-6, 6, size=3000)).astype(np.float32)
+    via_bits = syn.bf16_bits_to_f32(syn.f32_to_bf16_bits(x32))
+    for k in range(x32.size):
+        assert oracle.round_to_storage(float(x32[k]), "bf16") == float(via_bits[k])
+    # double rounding trap: x just above a bf16 tie but rounding to the tie in fp32
+    x = 1.0 + 2 ** -8 + 2 ** -40
+    assert float(np.float32(x)) == 1.0 + 2 ** -8                 # fp32 lands on the tie
+    assert oracle.round_to_storage(x, "bf16") == 1.0 + 2 ** -7   # single rounding goes up
+
+
+# ---------------------------------------------------------------- helpers agree with the full forms
+def test_sampled_forms_match_full_forms():
+    pb = syn.make_problem("t", 64, 80, 16, 3, "bf16", seed=21)
+    S = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    ea = np.array([0, 3, 15, 7, 7], dtype=np.int32)
+    eb = np.array([0, 9, 15, 2, 7], dtype=np.int32)
+    ent = oracle.compress_entries(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, ea, eb)
+    np.testing.assert_allclose(ent, S[ea, eb], rtol=0, atol=1e-13 * np.abs(S).max())
+    Wp, _ = oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    rows = [0, 63, 17, 17]
+    sub = oracle.decompress_rows(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, rows)
+    assert np.array_equal(sub, Wp[rows])
+
+
+def test_threaded_driver_matches_single_thread():
+    pb = syn.make_problem("t", 130, 96, 32, 4, "f16", seed=22)
+    S1 = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    S4 = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, threads=4)
+    np.testing.assert_allclose(S4, S1, rtol=0, atol=1e-13 * np.abs(S1).max())
+    W1, R1 = oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    W4, R4 = oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val,
+                                     threads=4)
+    assert np.array_equal(W1, W4) and np.array_equal(R1, R4)
+
+
+# ---------------------------------------------------------------- the generators themselves
+def test_generators_are_deterministic_and_shaped():
+    a, b = syn.config1(), syn.config1()
+    for f in ("G", "W", "P_idx", "P_val", "Q_idx", "Q_val", "S_in"):
+        assert np.array_equal(getattr(a, f), getattr(b, f))
+    assert a.P_idx.shape == (256, 2) and a.Q_idx.shape == (256, 2)
+    assert all(len(set(row)) == 2 for row in a.P_idx.tolist())          # without replacement
+    assert a.P_idx.min() >= 0 and a.P_idx.max() < 16
+    # ELL storage is (m + n) d values plus as many indices: the GPU-memory row of Table 2
+    assert a.P_val.size + a.Q_val.size == (a.m + a.n) * a.d
+    z = syn.ell_projector(4000, 512, 8, _rng(5), "zipf")[0]
+    frac0 = np.mean(z == 0)
+    H = np.sum(np.arange(1, 513, dtype=np.float64) ** -1.1)
+    assert abs(frac0 - 1.0 / H) < 0.02                                   # hottest column ~ 1/H
+    pb = syn.make_problem("t", 200, 64, 8, 2, "f16", 3, heavy_row_frac=0.01)
+    rowmax = np.abs(pb.G.astype(np.float64)).max(axis=1)
+    assert np.sum(rowmax > 0.02) == 2                                    # ceil(1% of 200) heavy rows
