@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the LSP hot path on one MI355X.
+
+A step is one pass of the whole hot path over the 6.7B-style layer stack (BASELINE config 4):
+32 layers x {down 11008x4096, gate/up 4096x11008, o/v/k/q 4096x4096}, bf16, r = 512, d = 8,
+visited layer by layer in backward order on one stream; every matrix gets one
+lsp_compress_planned (S = P^T G Q) and one lsp_decompress_apply (W -= P S Q^T).  All inputs
+are resident in HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
+
+Prints ONE JSON line: throughput in algorithmic GB/s (bytes the method must move, see
+the design doc) with a roofline object for the dominant kernel and the CPU oracle timed on a bounded
+sample beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(m, n, r, d, sz):
+    comp = m * n * sz + (m + n) * d * 8 + r * r * 4
+    deco = 2 * m * n * sz + (m + n) * d * 8 + r * r * 4
+    return comp, deco
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32, help="layers of the stack (32 = the named workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path is single-GPU by construction (no collectives are built); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import lsp_synth as syn
+    import paper_2406_10181_amd as L
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+    r, d, dtype, code, sz = 512, 8, "bf16", syn.DTYPE_CODE["bf16"], 2
+
+    # ------------------------------------------------------------------ inputs, resident in HBM
+    t0 = time.time()
+    mats = []       # backward order: layer L-1 .. 0; within a layer: down, gate, up, o, v, k, q
+    ws_bytes = 0
+    gen = torch.Generator(device=dev)
+    for layer in range(args.layers - 1, -1, -1):
+        for which, (name, m, n) in enumerate(syn.LAYER_67B):
+            seed = 4000 + layer * 7 + which
+            gen.manual_seed(seed)
+            G = (torch.randn(m, n, device=dev, generator=gen, dtype=torch.float32) * 1e-3).to(torch.bfloat16)
+            W = (torch.randn(m, n, device=dev, generator=gen, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            S_upd = torch.randn(r, r, device=dev, generator=gen, dtype=torch.float32) * 1e-3
+            rng = np.random.default_rng(seed)
+            P_idx, P_val = syn.ell_projector(m, r, d, rng, "uniform")
+            Q_idx, Q_val = syn.ell_projector(n, r, d, rng, "uniform")
+            e = dict(name=f"L{layer}_{name}", m=m, n=n, G=G, W=W, S_upd=S_upd,
+                     S=torch.empty(r, r, device=dev, dtype=torch.float32),
+                     P_idx=torch.from_numpy(P_idx).to(dev), P_val=torch.from_numpy(P_val).to(dev),
+                     Q_idx=torch.from_numpy(Q_idx).to(dev), Q_val=torch.from_numpy(Q_val).to(dev))
+            pbytes = L.lsp_plan_bytes(m, n, r, d)
+            e["plan"] = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+            L.lsp_plan_build(e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], m, n, r, d, e["plan"], pbytes, stream)
+            ws_bytes = max(ws_bytes, L.lsp_compress_planned_workspace_bytes(m, n, r, d))
+            e["cb"], e["db"] = algorithmic_bytes(m, n, r, d, sz)
+            mats.append(e)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def compress_all(ms):
+        for e in ms:
+            L.lsp_compress_planned(e["G"], e["plan"], e["m"], e["n"], r, d, e["S"], code, ws, ws_bytes, stream)
+
+    def decompress_all(ms):
+        for e in ms:
+            L.lsp_decompress_apply(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"],
+                                   e["m"], e["n"], r, d, code, stream)
+
+    def step():
+        # layer by layer: the layer's compress calls, then its decompress-apply calls
+        for k in range(0, len(mats), 7):
+            compress_all(mats[k:k + 7])
+            decompress_all(mats[k:k + 7])
+
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps            # ms per repetition
+
+    for _ in range(args.warmup):
+        step()
+    ms_step = timed(step, args.steps)
+    # per-kernel passes (same buffers, still cold: 26 GB is swept between two visits of a buffer)
+    sub = max(3, min(args.steps, 10))
+    ms_comp = timed(lambda: compress_all(mats), sub)
+    ms_deco = timed(lambda: decompress_all(mats), sub)
+
+    cbytes = sum(e["cb"] for e in mats)
+    dbytes = sum(e["db"] for e in mats)
+    value = (cbytes + dbytes) / (ms_step * 1e-3) / 1e9
+    comp_gbs = cbytes / (ms_comp * 1e-3) / 1e9
+    deco_gbs = dbytes / (ms_deco * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_decompress_cfg4.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    nlaunch = len(mats)
+    out = {
+        "metric": "compress+decompress GB/s per layer and % of MI355X HBM peak",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg4: 6.7B-style stack, {args.layers} layers x 7 matrices, bf16 G/W, r=512, d=8, "
+                               "uniform projector columns, backward order on one stream",
+                   "storage": "bf16", "accumulate": "f32", "matrices": nlaunch,
+                   "algorithmic_GB_per_step": round((cbytes + dbytes) / 1e9, 3)},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "per_layer_us": round(ms_step * 1e3 / args.layers, 2),
+        "compress": {"GB/s": round(comp_gbs, 1), "pct_of_hbm_peak": round(100 * comp_gbs / HBM_PEAK_GBS, 2),
+                     "ms_per_pass": round(ms_comp, 4)},
+        "decompress_apply": {"GB/s": round(deco_gbs, 1), "pct_of_hbm_peak": round(100 * deco_gbs / HBM_PEAK_GBS, 2),
+                             "ms_per_pass": round(ms_deco, 4)},
+        "roofline": {"kernel": "k_decompress<bf16,d=8,r<=512>", "bound": "hbm",
+                     "achieved": round(deco_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(deco_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "launches": nlaunch, "avg_launch_us": round(ms_deco * 1e3 / nlaunch, 2),
+                     "algorithmic_bytes_per_launch_avg": int(dbytes / nlaunch)},
+        "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(syn, r, d)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(syn, r, d):
+    """The oracle, as it stands, on a bounded sample: one matrix of each distinct shape of a layer."""
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+    total_bytes, total_s = 0, 0.0
+    names = []
+    for which in (3, 1, 0):                      # o 4096x4096, gate 4096x11008, down 11008x4096
+        pb = syn.config4_matrix(31, which)
+        t = time.time()
+        S = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, threads=cores)
+        oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, threads=cores)
+        total_s += time.time() - t
+        total_bytes += pb.compress_bytes + pb.decompress_bytes
+        names.append(f"{pb.m}x{pb.n}")
+        del S
+    return {"value": round(total_bytes / total_s / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": "compress + decompress-apply of one matrix per distinct layer shape (" + ", ".join(names) +
+                      f"), bf16, r={r}, d={d}; fp64 plain loops, rows split over threads",
+            "seconds": round(total_s, 2)}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/*
+ * lsp.h -- C ABI of the MI355X (gfx950) library for the GPU hot path of LSP-Offload
+ * (arXiv 2406.10181): compressing a weight gradient through two learned sparse projectors
+ * and expanding the CPU-computed subspace update back onto the weight.
+ *
+ * Letters.  G and W are m x n, row-major, leading dimension n.  r is the subspace size
+ * (number of columns of P and Q; S is r x r).  d is the number of stored entries per
+ * projector row.  The paper names these the other way round: its "(d,r)-sparse projector"
+ * (Def. 1) has subspace size d and r nonzeros per row.
+ *
+ * Projectors.  P (m x r) and Q (n x r) are (d,r)-sparse in the sense of Def. 1 and are passed
+ * in ELL layout: idx[row][k] (int32, a column in [0, r)) and val[row][k] (fp32), k < d,
+ * row-major.  The dense meaning is  Phat[i][a] = sum of val[i][k] over k with idx[i][k] == a:
+ * duplicate columns within a row add up, and an entry with val == 0 is padding (its index
+ * must still be in range).  Indices are NOT range-checked by the compute calls; an index
+ * outside [0, r) is undefined behaviour.  lsp_validate_projector() checks them on request.
+ *
+ * Memory.  Every pointer named "device" is device memory of the current HIP device, owned by
+ * the caller for the whole call and until the enqueued work has finished.  The library never
+ * allocates, frees or copies device memory in the compute calls, never synchronises the
+ * stream, and keeps no state between calls.  Buffers must not alias one another.
+ * All base pointers must be aligned to 16 bytes.
+ *
+ * Execution.  Compute calls only enqueue kernels on `stream` (a hipStream_t passed as
+ * void*; NULL = the default stream) and return; work on one stream runs in call order
+ * (Alg. 3 issues these per layer, in backward order, asynchronously).
+ *
+ * Errors.  Every call returns LSP_OK (0) or a negative lsp_status.  On error nothing has
+ * been enqueued and no output has been touched.
+ */
+#ifndef LSP_H
+#define LSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LSP_F32  = 0,   /* IEEE binary32 */
+    LSP_F16  = 1,   /* IEEE binary16 */
+    LSP_BF16 = 2    /* bfloat16 */
+} lsp_dtype;
+
+typedef enum {
+    LSP_OK            =  0,
+    LSP_ERR_NULL      = -1,  /* a required pointer is NULL */
+    LSP_ERR_SHAPE     = -2,  /* m, n, r or d not positive, d > r, size overflow, r or d above the supported maximum */
+    LSP_ERR_DTYPE     = -3,  /* dtype is not one of lsp_dtype */
+    LSP_ERR_WORKSPACE = -4,  /* workspace / plan buffer missing, misaligned or too small */
+    LSP_ERR_LAUNCH    = -5,  /* the HIP runtime refused a launch or a copy (see lsp_last_hip_error) */
+    LSP_ERR_INDEX     = -6,  /* lsp_validate_projector found an index outside [0, r) */
+    LSP_ERR_ALIGN     = -7   /* a base pointer is not 16-byte aligned */
+} lsp_status;
+
+#define LSP_MAX_R 2048       /* largest supported subspace size (the paper's largest setting) */
+#define LSP_MAX_D 64         /* largest supported number of entries per projector row */
+
+/* ------------------------------------------------------------------------------------------
+ * Compress:  S := P^T G Q.
+ * The step "grad <- SendToCPU(P^T grad_W Q)" of Alg. 1 and the step that forms the projected
+ * gradient of layer l in Alg. 3.  S is OVERWRITTEN (not accumulated); gradient accumulation
+ * happens on G before the call.  G is widened exactly to fp32; all sums are fp32.
+ *
+ *   G          device, m*n elements of `dtype`, row-major
+ *   P_idx/val  device, [m][d]
+ *   Q_idx/val  device, [n][d]
+ *   S          device, r*r fp32, row-major, written
+ *   workspace  device scratch of at least lsp_compress_workspace_bytes(m,n,r,d) bytes,
+ *              16-byte aligned; contents are clobbered; may be reused by later calls on
+ *              the same stream
+ *
+ * This entry takes raw ELL projectors and needs no preparation: it evaluates the same sums
+ * in scatter form (LDS and global fp32 atomics), which is several times slower than the
+ * planned entry and not bit-reproducible from run to run (atomic order).  When the
+ * projectors stay fixed over many steps -- the paper refreshes them only every CheckFreq
+ * steps in MaybeUpdate, Alg. 1 -- build a plan once with lsp_plan_build and call
+ * lsp_compress_planned, which is the entry meant for the per-step loop.
+ */
+int lsp_compress(const void* G,
+                 const int32_t* P_idx, const float* P_val,
+                 const int32_t* Q_idx, const float* Q_val,
+                 int64_t m, int64_t n, int32_t r, int32_t d,
+                 float* S, lsp_dtype dtype,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of device scratch lsp_compress needs (0 on invalid shapes). */
+size_t lsp_compress_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+
+/* ------------------------------------------------------------------------------------------
+ * Projector plan: a device-resident, column-sorted copy of P and Q for one (m, n, r, d)
+ * problem, valid until the projector arrays change (every CheckFreq steps at most, Alg. 1).
+ * It lives entirely in a caller-owned device buffer of lsp_plan_bytes() bytes; there is no
+ * host handle.  Building a plan only sorts and packs the projector entries (no arithmetic on
+ * G, W or S).  lsp_plan_build is a set-up call, NOT part of the per-step path: it waits for
+ * `stream`, copies the four ELL arrays to the host, sorts there, uploads the plan and waits
+ * again (it allocates host memory; it returns LSP_ERR_INDEX if an index is outside [0, r)).
+ * lsp_plan_build_host does the same packing with every pointer in HOST memory and makes no HIP
+ * call; the resulting bytes can be copied to the device by the caller.
+ */
+size_t lsp_plan_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+
+int lsp_plan_build(const int32_t* P_idx, const float* P_val,
+                   const int32_t* Q_idx, const float* Q_val,
+                   int64_t m, int64_t n, int32_t r, int32_t d,
+                   void* plan, size_t plan_bytes, void* stream);
+
+int lsp_plan_build_host(const int32_t* P_idx, const float* P_val,
+                        const int32_t* Q_idx, const float* Q_val,
+                        int64_t m, int64_t n, int32_t r, int32_t d,
+                        void* plan_host, size_t plan_bytes);
+
+/* Same sums as lsp_compress, with the projectors given as a plan; gather form, no global
+ * atomics unless a row of P^T has more than 128 entries (heavily skewed projectors), and
+ * bit-reproducible from run to run whenever no list had to be cut (a column of Q with more
+ * than 64 entries inside one 1024-column chunk of G, or such a row of P^T).
+ * workspace: at least lsp_compress_planned_workspace_bytes(m,n,r,d) bytes. */
+int lsp_compress_planned(const void* G, const void* plan,
+                         int64_t m, int64_t n, int32_t r, int32_t d,
+                         float* S, lsp_dtype dtype,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+size_t lsp_compress_planned_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+
+/* ------------------------------------------------------------------------------------------
+ * Decompress and apply:  W := rn( W - P S Q^T ), in place.
+ * The step "W <- W - eta_t P Delta_W Q^T" of Alg. 1 and the last step of the layer loop of
+ * Alg. 3.  The learning rate is already folded into S by the CPU optimiser (P (eta S) Q^T =
+ * eta P S Q^T), so there is no scale argument.  Each W element is widened exactly to fp32,
+ * the update is accumulated in fp32, and the result is rounded once (nearest, ties to even)
+ * to `dtype`.  Needs no workspace and no plan (the ELL rows are read as they are).
+ *
+ *   W          device, m*n elements of `dtype`, row-major, read and written
+ *   S          device, r*r fp32, row-major, read
+ */
+int lsp_decompress_apply(void* W, const float* S,
+                         const int32_t* P_idx, const float* P_val,
+                         const int32_t* Q_idx, const float* Q_val,
+                         int64_t m, int64_t n, int32_t r, int32_t d,
+                         lsp_dtype dtype, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Utilities.
+ */
+
+/* Checks every idx[row][k] against [0, r).  Enqueues a kernel on `stream`, then WAITS for it
+ * (this call synchronises the stream).  Returns LSP_OK or LSP_ERR_INDEX.
+ * flag: device, one int32 of scratch. */
+int lsp_validate_projector(const int32_t* idx, int64_t rows, int32_t d, int32_t r,
+                           int32_t* flag, void* stream);
+
+const char* lsp_strerror(int code);      /* static string for an lsp_status */
+int         lsp_last_hip_error(void);    /* raw hipError_t of the last LSP_ERR_LAUNCH on this thread */
+int         lsp_version(void);           /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSP_H */

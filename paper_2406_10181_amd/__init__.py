@@ -1,0 +1,15 @@
+"""MI355X (gfx950) library for the GPU hot path of LSP-Offload: compress S = P^T G Q and
+decompress-and-apply W <- W - P S Q^T with (d,r)-sparse ELL projectors (Alg. 1 / Alg. 3, Def. 1).
+
+This package is a thin binding: it marshals torch device pointers into the C ABI declared in
+``include/lsp.h``.  Every step of the path runs in the HIP kernels of ``liblsp_hip.so``; there is
+no CPU fallback, and importing the binding fails loudly if the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    LspError, DTYPE_CODE, lib, lib_path,
+    lsp_compress, lsp_compress_workspace_bytes,
+    lsp_plan_bytes, lsp_plan_build, lsp_plan_build_host,
+    lsp_compress_planned, lsp_compress_planned_workspace_bytes,
+    lsp_decompress_apply, lsp_validate_projector, lsp_strerror, lsp_version,
+    torch_dtype_code,
+)

@@ -1,0 +1,161 @@
+"""ctypes binding with the same names as the C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "liblsp_hip.so")
+
+DTYPE_CODE = {"f32": 0, "f16": 1, "bf16": 2}
+
+
+class LspError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lsp_strerror(code)} (status {code}, hip error {lib().lsp_last_hip_error()})")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the in-tree HIP library.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+                "or python paper_2406_10181_amd/build.py)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+        L.lsp_compress.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, i32, vp, sz, vp]
+        L.lsp_compress.restype = ctypes.c_int
+        L.lsp_compress_workspace_bytes.argtypes = [i64, i64, i32, i32]
+        L.lsp_compress_workspace_bytes.restype = sz
+        L.lsp_plan_bytes.argtypes = [i64, i64, i32, i32]
+        L.lsp_plan_bytes.restype = sz
+        L.lsp_plan_build.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
+        L.lsp_plan_build.restype = ctypes.c_int
+        L.lsp_plan_build_host.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, sz]
+        L.lsp_plan_build_host.restype = ctypes.c_int
+        L.lsp_compress_planned.argtypes = [vp, vp, i64, i64, i32, i32, vp, i32, vp, sz, vp]
+        L.lsp_compress_planned.restype = ctypes.c_int
+        L.lsp_compress_planned_workspace_bytes.argtypes = [i64, i64, i32, i32]
+        L.lsp_compress_planned_workspace_bytes.restype = sz
+        L.lsp_decompress_apply.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, vp]
+        L.lsp_decompress_apply.restype = ctypes.c_int
+        L.lsp_validate_projector.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.lsp_validate_projector.restype = ctypes.c_int
+        L.lsp_strerror.argtypes = [ctypes.c_int]
+        L.lsp_strerror.restype = ctypes.c_char_p
+        L.lsp_last_hip_error.restype = ctypes.c_int
+        L.lsp_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(x) -> Optional[int]:
+    """Device (or host) address of a torch tensor / numpy array / raw int; None stays NULL."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):
+        return x.ctypes.data
+    raise TypeError(f"cannot take the address of {type(x)!r}")
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream          # torch.cuda.Stream
+
+
+def torch_dtype_code(t) -> int:
+    import torch
+    return {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}[t]
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise LspError(rc, where)
+
+
+def lsp_strerror(code: int) -> str:
+    return lib().lsp_strerror(code).decode()
+
+
+def lsp_version() -> int:
+    return lib().lsp_version()
+
+
+def lsp_compress_workspace_bytes(m, n, r, d) -> int:
+    return lib().lsp_compress_workspace_bytes(m, n, r, d)
+
+
+def lsp_compress_planned_workspace_bytes(m, n, r, d) -> int:
+    return lib().lsp_compress_planned_workspace_bytes(m, n, r, d)
+
+
+def lsp_plan_bytes(m, n, r, d) -> int:
+    return lib().lsp_plan_bytes(m, n, r, d)
+
+
+def lsp_compress(G, P_idx, P_val, Q_idx, Q_val, m, n, r, d, S, dtype: int, workspace, workspace_bytes, stream=None,
+                 check: bool = True) -> int:
+    rc = lib().lsp_compress(_ptr(G), _ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val), m, n, r, d, _ptr(S),
+                            dtype, _ptr(workspace), workspace_bytes, _stream(stream))
+    if check:
+        _check(rc, "lsp_compress")
+    return rc
+
+
+def lsp_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan, plan_bytes, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_plan_build(_ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val), m, n, r, d, _ptr(plan),
+                              plan_bytes, _stream(stream))
+    if check:
+        _check(rc, "lsp_plan_build")
+    return rc
+
+
+def lsp_plan_build_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan_host, plan_bytes, check: bool = True) -> int:
+    rc = lib().lsp_plan_build_host(_ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val), m, n, r, d,
+                                   _ptr(plan_host), plan_bytes)
+    if check:
+        _check(rc, "lsp_plan_build_host")
+    return rc
+
+
+def lsp_compress_planned(G, plan, m, n, r, d, S, dtype: int, workspace, workspace_bytes, stream=None,
+                         check: bool = True) -> int:
+    rc = lib().lsp_compress_planned(_ptr(G), _ptr(plan), m, n, r, d, _ptr(S), dtype, _ptr(workspace),
+                                    workspace_bytes, _stream(stream))
+    if check:
+        _check(rc, "lsp_compress_planned")
+    return rc
+
+
+def lsp_decompress_apply(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, dtype: int, stream=None,
+                         check: bool = True) -> int:
+    rc = lib().lsp_decompress_apply(_ptr(W), _ptr(S), _ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val),
+                                    m, n, r, d, dtype, _stream(stream))
+    if check:
+        _check(rc, "lsp_decompress_apply")
+    return rc
+
+
+def lsp_validate_projector(idx, rows, d, r, flag, stream=None, check: bool = False) -> int:
+    rc = lib().lsp_validate_projector(_ptr(idx), rows, d, r, _ptr(flag), _stream(stream))
+    if check:
+        _check(rc, "lsp_validate_projector")
+    return rc

@@ -1,0 +1,164 @@
+// extern "C" entry points: argument checks, workspace carving, kernel launches.
+#include <cstring>
+#include <vector>
+
+#include "lsp_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int fail_launch(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return LSP_ERR_LAUNCH;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int64_t m, int64_t n, int32_t r, int32_t d) {
+    if (m <= 0 || n <= 0 || r <= 0 || d <= 0) return LSP_ERR_SHAPE;
+    if (d > r || r > LSP_MAX_R || d > LSP_MAX_D) return LSP_ERR_SHAPE;
+    if (m > INT32_MAX || n > INT32_MAX) return LSP_ERR_SHAPE;
+    if (m > ((int64_t)1 << 40) / n) return LSP_ERR_SHAPE;
+    if (m * d > INT32_MAX || n * d > INT32_MAX) return LSP_ERR_SHAPE;   // plan offsets are 32-bit
+    return LSP_OK;
+}
+
+int check_dtype(lsp_dtype t) { return (t == LSP_F32 || t == LSP_F16 || t == LSP_BF16) ? LSP_OK : LSP_ERR_DTYPE; }
+
+size_t t_bytes(int64_t m, int32_t r) { return lsp::align_up((size_t)m * (size_t)r * sizeof(float), 256); }
+
+}  // namespace
+
+extern "C" {
+
+size_t lsp_compress_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
+    if (check_shape(m, n, r, d) != LSP_OK) return 0;
+    return t_bytes(m, r);
+}
+
+size_t lsp_compress_planned_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
+    if (check_shape(m, n, r, d) != LSP_OK) return 0;
+    return t_bytes(m, r);
+}
+
+size_t lsp_plan_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
+    if (check_shape(m, n, r, d) != LSP_OK) return 0;
+    return lsp::plan_bytes(m, n, r, d);
+}
+
+int lsp_compress(const void* G, const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                 int64_t m, int64_t n, int32_t r, int32_t d, float* S, lsp_dtype dtype,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (!G || !P_idx || !P_val || !Q_idx || !Q_val || !S) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    rc = check_dtype(dtype);
+    if (rc != LSP_OK) return rc;
+    if (!workspace || workspace_bytes < lsp_compress_workspace_bytes(m, n, r, d)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(G) || !aligned16(S) || !aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val))
+        return LSP_ERR_ALIGN;
+    hipError_t e = lsp::launch_compress_raw(G, P_idx, P_val, Q_idx, Q_val, m, n, r, d, S, dtype,
+                                            static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
+int lsp_plan_build(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                   int64_t m, int64_t n, int32_t r, int32_t d, void* plan, size_t plan_bytes, void* stream) {
+    if (!P_idx || !P_val || !Q_idx || !Q_val) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    const size_t need = lsp::plan_bytes(m, n, r, d);
+    if (!plan || plan_bytes < need || !aligned16(plan)) return LSP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Order after whatever produced the projector arrays on this stream, then bring them to the host.
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail_launch(e);
+    std::vector<int32_t> pi((size_t)m * d), qi((size_t)n * d);
+    std::vector<float> pv((size_t)m * d), qv((size_t)n * d);
+    if ((e = hipMemcpy(pi.data(), P_idx, pi.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
+    if ((e = hipMemcpy(pv.data(), P_val, pv.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
+    if ((e = hipMemcpy(qi.data(), Q_idx, qi.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
+    if ((e = hipMemcpy(qv.data(), Q_val, qv.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
+    for (int32_t v : pi) if (v < 0 || v >= r) return LSP_ERR_INDEX;
+    for (int32_t v : qi) if (v < 0 || v >= r) return LSP_ERR_INDEX;
+    std::vector<uint8_t> host(need);
+    lsp::build_plan_host(pi.data(), pv.data(), qi.data(), qv.data(), m, n, r, d, host.data());
+    if ((e = hipMemcpyAsync(plan, host.data(), need, hipMemcpyHostToDevice, st)) != hipSuccess) return fail_launch(e);
+    if ((e = hipStreamSynchronize(st)) != hipSuccess) return fail_launch(e);
+    return LSP_OK;
+}
+
+int lsp_plan_build_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                        int64_t m, int64_t n, int32_t r, int32_t d, void* plan_host, size_t plan_bytes) {
+    if (!P_idx || !P_val || !Q_idx || !Q_val) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    if (!plan_host || plan_bytes < lsp::plan_bytes(m, n, r, d)) return LSP_ERR_WORKSPACE;
+    for (int64_t k = 0; k < m * d; ++k) if (P_idx[k] < 0 || P_idx[k] >= r) return LSP_ERR_INDEX;
+    for (int64_t k = 0; k < n * d; ++k) if (Q_idx[k] < 0 || Q_idx[k] >= r) return LSP_ERR_INDEX;
+    lsp::build_plan_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, static_cast<uint8_t*>(plan_host));
+    return LSP_OK;
+}
+
+int lsp_compress_planned(const void* G, const void* plan, int64_t m, int64_t n, int32_t r, int32_t d,
+                         float* S, lsp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!G || !plan || !S) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    rc = check_dtype(dtype);
+    if (rc != LSP_OK) return rc;
+    if (!workspace || workspace_bytes < lsp_compress_planned_workspace_bytes(m, n, r, d)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(workspace) || !aligned16(plan)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(G) || !aligned16(S)) return LSP_ERR_ALIGN;
+    hipError_t e = lsp::launch_compress_planned(G, static_cast<const uint8_t*>(plan), m, n, r, d, S, dtype,
+                                                static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
+int lsp_decompress_apply(void* W, const float* S, const int32_t* P_idx, const float* P_val,
+                         const int32_t* Q_idx, const float* Q_val,
+                         int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype, void* stream) {
+    if (!W || !S || !P_idx || !P_val || !Q_idx || !Q_val) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    rc = check_dtype(dtype);
+    if (rc != LSP_OK) return rc;
+    if (!aligned16(W) || !aligned16(S) || !aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val))
+        return LSP_ERR_ALIGN;
+    hipError_t e = lsp::launch_decompress(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, dtype,
+                                          static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
+int lsp_validate_projector(const int32_t* idx, int64_t rows, int32_t d, int32_t r, int32_t* flag, void* stream) {
+    if (!idx || !flag) return LSP_ERR_NULL;
+    if (rows <= 0 || d <= 0 || r <= 0) return LSP_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = lsp::launch_validate(idx, rows * d, r, flag, st);
+    if (e != hipSuccess) return fail_launch(e);
+    int32_t host_flag = 0;
+    if ((e = hipMemcpyAsync(&host_flag, flag, sizeof(int32_t), hipMemcpyDeviceToHost, st)) != hipSuccess) return fail_launch(e);
+    if ((e = hipStreamSynchronize(st)) != hipSuccess) return fail_launch(e);
+    return host_flag ? LSP_ERR_INDEX : LSP_OK;
+}
+
+const char* lsp_strerror(int code) {
+    switch (code) {
+        case LSP_OK:            return "ok";
+        case LSP_ERR_NULL:      return "a required pointer is NULL";
+        case LSP_ERR_SHAPE:     return "invalid shape (m, n, r, d must be positive, d <= r, within supported maxima)";
+        case LSP_ERR_DTYPE:     return "unknown dtype";
+        case LSP_ERR_WORKSPACE: return "workspace or plan buffer missing, misaligned or too small";
+        case LSP_ERR_LAUNCH:    return "HIP runtime error (see lsp_last_hip_error)";
+        case LSP_ERR_INDEX:     return "projector index outside [0, r)";
+        case LSP_ERR_ALIGN:     return "a base pointer is not 16-byte aligned";
+        default:                return "unknown lsp_status";
+    }
+}
+
+int lsp_last_hip_error(void) { return g_last_hip_error; }
+int lsp_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,347 @@
+// Compress: S = P^T G Q  (Alg. 1, compress step; Alg. 3, projected gradient of a layer).
+//
+// Two kernels per call, both gather-form and free of global atomics in the common case:
+//   A  T = G Q     one workgroup per block of R rows of G; G is streamed once from HBM in
+//                  chunks of kChunk columns, widened to fp32 and staged in LDS transposed
+//                  ([column][4 rows], so one 128-bit LDS read serves four rows); each lane walks
+//                  the plan's list of (column, value) pairs of one subspace column b.
+//   B  S = P^T T   one workgroup per piece of a row of P^T; reads rows of T.
+// The path is bandwidth-bound (one pass over G); no matrix cores are involved because the
+// projectors are sparse (d entries per row, Def. 1) and the work is gather + fp32 FMA.
+#include "lsp_internal.h"
+
+namespace lsp {
+
+constexpr int kPlaneStride = kChunk * 16 + 16;   // bytes; last 16 bytes of a plane stay zero
+constexpr int kThreadsA = 256;
+constexpr int kWavesA = kThreadsA / kWave;
+
+// ----------------------------------------------------------------------------------------------
+// eight consecutive elements of one row, as loaded
+template <typename D> struct Oct;
+template <> struct Oct<F32>  { float4 lo, hi; };
+template <> struct Oct<F16>  { uint4 v; };
+template <> struct Oct<BF16> { uint4 v; };
+
+template <typename D> __device__ __forceinline__ Oct<D> oct_zero();
+template <> __device__ __forceinline__ Oct<F32> oct_zero<F32>() { return {make_float4(0, 0, 0, 0), make_float4(0, 0, 0, 0)}; }
+template <> __device__ __forceinline__ Oct<F16> oct_zero<F16>() { return {make_uint4(0, 0, 0, 0)}; }
+template <> __device__ __forceinline__ Oct<BF16> oct_zero<BF16>() { return {make_uint4(0, 0, 0, 0)}; }
+
+template <typename D> __device__ __forceinline__ Oct<D> oct_load(const typename D::elem* p);
+template <> __device__ __forceinline__ Oct<F32> oct_load<F32>(const float* p) {
+    const float4* q = reinterpret_cast<const float4*>(p);
+    return {q[0], q[1]};
+}
+template <> __device__ __forceinline__ Oct<F16> oct_load<F16>(const uint16_t* p) { return {*reinterpret_cast<const uint4*>(p)}; }
+template <> __device__ __forceinline__ Oct<BF16> oct_load<BF16>(const uint16_t* p) { return {*reinterpret_cast<const uint4*>(p)}; }
+
+// element-wise, bounds-checked variant for ragged or unaligned rows
+template <typename D> __device__ __forceinline__ void oct_gather(const typename D::elem* row, int64_t col0, int64_t n, float out[8]) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) out[q] = (col0 + q < n) ? widen<D>(row[col0 + q]) : 0.0f;
+}
+
+template <typename D> __device__ __forceinline__ void oct_widen(const Oct<D>& o, float out[8]);
+template <> __device__ __forceinline__ void oct_widen<F32>(const Oct<F32>& o, float out[8]) {
+    out[0] = o.lo.x; out[1] = o.lo.y; out[2] = o.lo.z; out[3] = o.lo.w;
+    out[4] = o.hi.x; out[5] = o.hi.y; out[6] = o.hi.z; out[7] = o.hi.w;
+}
+template <> __device__ __forceinline__ void oct_widen<BF16>(const Oct<BF16>& o, float out[8]) {
+    const uint32_t w[4] = {o.v.x, o.v.y, o.v.z, o.v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        out[2 * q]     = __uint_as_float(w[q] << 16);
+        out[2 * q + 1] = __uint_as_float(w[q] & 0xFFFF0000u);
+    }
+}
+template <> __device__ __forceinline__ void oct_widen<F16>(const Oct<F16>& o, float out[8]) {
+    const uint32_t w[4] = {o.v.x, o.v.y, o.v.z, o.v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        out[2 * q]     = widen<F16>((uint16_t)(w[q] & 0xFFFFu));
+        out[2 * q + 1] = widen<F16>((uint16_t)(w[q] >> 16));
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Kernel A.  RG = number of 4-row planes per workgroup (rows per workgroup R = 4 RG).
+// LDS: RG planes of kPlaneStride bytes (staged chunk of G, fp32), then T tile [R][r] fp32.
+// VEC: rows are 8-element aligned (n % 8 == 0), vector loads; otherwise element-wise loads.
+template <typename D, int RG, bool VEC>
+__global__ __launch_bounds__(kThreadsA) void k_compress_gq(const typename D::elem* __restrict__ G,
+                                                          const uint8_t* __restrict__ plan,
+                                                          float* __restrict__ T, float* __restrict__ S,
+                                                          int m, int n, int r) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    constexpr int R = 4 * RG;
+    constexpr int UNITS = RG * (kChunk / 8);                 // (plane, column octet) units per chunk
+    constexpr int UPT = (UNITS + kThreadsA - 1) / kThreadsA; // units per thread
+    float* Tl = reinterpret_cast<float*>(smem + RG * kPlaneStride);
+
+    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    const ChunkInfo* chunks = reinterpret_cast<const ChunkInfo*>(plan + H->off_q_chunk);
+    const RoundInfo* rounds = reinterpret_cast<const RoundInfo*>(plan + H->off_q_round);
+    const uint16_t* cols = reinterpret_cast<const uint16_t*>(plan + H->off_q_cols);
+    const uint2* qent = reinterpret_cast<const uint2*>(plan + H->off_q_ent);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t i0 = (int64_t)blockIdx.x * R;
+    const int nchunks = H->nchunks;
+
+    // S must start at zero only when some row of P^T was cut into pieces (kernel B then adds).
+    if (H->p_any_split) {
+        const int64_t total = (int64_t)r * r;
+        for (int64_t k = (int64_t)blockIdx.x * kThreadsA + tid; k < total; k += (int64_t)gridDim.x * kThreadsA) S[k] = 0.0f;
+    }
+    for (int k = tid; k < R * r; k += kThreadsA) Tl[k] = 0.0f;
+    if (tid < RG) *reinterpret_cast<float4*>(smem + tid * kPlaneStride + kChunk * 16) = make_float4(0, 0, 0, 0);
+
+    Oct<D> pre[UPT][4];
+    float  preg[VEC ? 1 : UPT][VEC ? 1 : 4][VEC ? 1 : 8];
+
+    auto fetch = [&](int c) {
+#pragma unroll
+        for (int u = 0; u < UPT; ++u) {
+            const int unit = tid + u * kThreadsA;
+            const int plane = unit / (kChunk / 8), oct = unit % (kChunk / 8);
+            const int64_t col0 = (int64_t)c * kChunk + (int64_t)oct * 8;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int64_t row = i0 + plane * 4 + t;
+                const bool ok = (UNITS % kThreadsA == 0 || unit < UNITS) && row < m && col0 < n;
+                if constexpr (VEC) {
+                    pre[u][t] = ok ? oct_load<D>(G + row * (int64_t)n + col0) : oct_zero<D>();
+                } else {
+                    if (ok) oct_gather<D>(G + row * (int64_t)n, col0, n, preg[u][t]);
+                    else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) preg[u][t][q] = 0.0f;
+                    }
+                }
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int u = 0; u < UPT; ++u) {
+            const int unit = tid + u * kThreadsA;
+            if (UNITS % kThreadsA != 0 && unit >= UNITS) continue;
+            const int plane = unit / (kChunk / 8), oct = unit % (kChunk / 8);
+            float f[4][8];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if constexpr (VEC) oct_widen<D>(pre[u][t], f[t]);
+                else {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) f[t][q] = preg[u][t][q];
+                }
+            }
+            uint8_t* base = smem + plane * kPlaneStride + oct * 16;
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                *reinterpret_cast<float4*>(base + q * (kChunk / 8) * 16) = make_float4(f[0][q], f[1][q], f[2][q], f[3][q]);
+        }
+    };
+
+    fetch(0);
+    for (int c = 0; c < nchunks; ++c) {
+        __syncthreads();               // everyone is done reading the previous chunk (and Tl is zeroed)
+        stage();
+        __syncthreads();
+        if (c + 1 < nchunks) fetch(c + 1);
+
+        const int first = chunks[c].first_round, nr = chunks[c].nrounds;
+        for (int k = 0;; ++k) {
+            // rounds are sorted by length; deal them to the waves in serpentine order
+            const int rho = (k & 1) ? k * kWavesA + (kWavesA - 1 - wave) : k * kWavesA + wave;
+            if (rho >= nr) break;
+            const RoundInfo ri = rounds[first + rho];
+            const uint32_t b = cols[(size_t)(first + rho) * kWave + lane];
+            const uint2* ep = qent + ri.ent_offset + lane;
+            float acc[RG][4];
+#pragma unroll
+            for (int g = 0; g < RG; ++g) acc[g][0] = acc[g][1] = acc[g][2] = acc[g][3] = 0.0f;
+#pragma unroll 2
+            for (int e = 0; e < ri.len; ++e) {
+                const uint2 en = ep[(size_t)e * kWave];
+                const float v = __uint_as_float(en.y);
+#pragma unroll
+                for (int g = 0; g < RG; ++g) {
+                    const float4 x = *reinterpret_cast<const float4*>(smem + en.x + g * kPlaneStride);
+                    acc[g][0] = fmaf(v, x.x, acc[g][0]);
+                    acc[g][1] = fmaf(v, x.y, acc[g][1]);
+                    acc[g][2] = fmaf(v, x.z, acc[g][2]);
+                    acc[g][3] = fmaf(v, x.w, acc[g][3]);
+                }
+            }
+            if (b != kNoColumn) {
+#pragma unroll
+                for (int g = 0; g < RG; ++g)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) atomicAdd(&Tl[(g * 4 + t) * r + b], acc[g][t]);
+            }
+        }
+    }
+    __syncthreads();
+    for (int k = tid; k < R * r; k += kThreadsA) {
+        const int t = k / r;
+        if (i0 + t < m) T[(i0 + t) * (int64_t)r + (k - t * r)] = Tl[k];
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Kernel B.  One workgroup per piece of a row of P^T:  S[a][:] (+)= sum_e v_e T[i_e][:].
+template <bool VEC4>
+__global__ __launch_bounds__(128) void k_compress_pt(const uint8_t* __restrict__ plan, const float* __restrict__ T,
+                                                    float* __restrict__ S, int r) {
+    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    if ((int)blockIdx.x >= H->p_nitems) return;
+    const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[blockIdx.x];
+    const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
+    if constexpr (VEC4) {
+        for (int b0 = threadIdx.x * 4; b0 < r; b0 += 128 * 4) {
+            float4 acc = make_float4(0, 0, 0, 0);
+#pragma unroll 8
+            for (int e = 0; e < it.len; ++e) {
+                const uint2 en = ent[e];
+                const float v = __uint_as_float(en.y);
+                const float4 x = *reinterpret_cast<const float4*>(T + (int64_t)en.x * r + b0);
+                acc.x = fmaf(v, x.x, acc.x); acc.y = fmaf(v, x.y, acc.y);
+                acc.z = fmaf(v, x.z, acc.z); acc.w = fmaf(v, x.w, acc.w);
+            }
+            float* dst = S + (int64_t)it.a * r + b0;
+            if (it.atomic) {
+                atomicAdd(dst + 0, acc.x); atomicAdd(dst + 1, acc.y); atomicAdd(dst + 2, acc.z); atomicAdd(dst + 3, acc.w);
+            } else {
+                *reinterpret_cast<float4*>(dst) = acc;
+            }
+        }
+    } else {
+        for (int b = threadIdx.x; b < r; b += 128) {
+            float acc = 0.0f;
+            for (int e = 0; e < it.len; ++e) {
+                const uint2 en = ent[e];
+                acc = fmaf(__uint_as_float(en.y), T[(int64_t)en.x * r + b], acc);
+            }
+            float* dst = S + (int64_t)it.a * r + b;
+            if (it.atomic) atomicAdd(dst, acc); else *dst = acc;
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Plan-free variant used by the raw-ELL entry: same mathematics in scatter form.
+//   T tile in LDS, every (row, column j, entry k) adds G[i][j] * Q_val[j][k] to T[i][Q_idx[j][k]];
+//   then S[P_idx[i][k]][:] += P_val[i][k] * T[i][:] with global atomics (S zeroed first).
+constexpr int kRawRows = 16;
+template <typename D>
+__global__ __launch_bounds__(256) void k_raw_gq(const typename D::elem* __restrict__ G,
+                                               const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
+                                               float* __restrict__ T, int m, int n, int r, int d) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    float* Tl = reinterpret_cast<float*>(smem);
+    const int64_t i0 = (int64_t)blockIdx.x * kRawRows;
+    for (int k = threadIdx.x; k < kRawRows * r; k += 256) Tl[k] = 0.0f;
+    __syncthreads();
+    for (int64_t j = threadIdx.x; j < n; j += 256) {
+        float g[kRawRows];
+#pragma unroll
+        for (int t = 0; t < kRawRows; ++t) g[t] = (i0 + t < m) ? widen<D>(G[(i0 + t) * (int64_t)n + j]) : 0.0f;
+        for (int k = 0; k < d; ++k) {
+            const int b = Q_idx[j * d + k];
+            const float v = Q_val[j * d + k];
+#pragma unroll
+            for (int t = 0; t < kRawRows; ++t) atomicAdd(&Tl[t * r + b], g[t] * v);
+        }
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < kRawRows * r; k += 256) {
+        const int t = k / r;
+        if (i0 + t < m) T[(i0 + t) * (int64_t)r + (k - t * r)] = Tl[k];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_fill_zero(float* __restrict__ p, int64_t count) {
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < count; k += (int64_t)gridDim.x * 256) p[k] = 0.0f;
+}
+
+__global__ __launch_bounds__(256) void k_raw_pt(const float* __restrict__ T, const int32_t* __restrict__ P_idx,
+                                               const float* __restrict__ P_val, float* __restrict__ S, int r, int d) {
+    const int64_t i = blockIdx.x;
+    for (int k = 0; k < d; ++k) {
+        const int a = P_idx[i * d + k];
+        const float v = P_val[i * d + k];
+        for (int b = threadIdx.x; b < r; b += 256) atomicAdd(&S[(int64_t)a * r + b], v * T[i * r + b]);
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+template <typename D, int RG>
+static hipError_t launch_gq(const void* G, const uint8_t* plan, float* T, float* S, int64_t m, int64_t n, int32_t r, hipStream_t st) {
+    const size_t lds = (size_t)RG * kPlaneStride + (size_t)RG * 4 * r * sizeof(float);
+    const unsigned grid = (unsigned)((m + RG * 4 - 1) / (RG * 4));
+    const bool vec = (n % 8) == 0;
+    auto kern = vec ? k_compress_gq<D, RG, true> : k_compress_gq<D, RG, false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsA), lds, st,
+                       reinterpret_cast<const typename D::elem*>(G), plan, T, S, (int)m, (int)n, (int)r);
+    return hipGetLastError();
+}
+
+template <typename D>
+static hipError_t launch_gq_rg(const void* G, const uint8_t* plan, float* T, float* S, int64_t m, int64_t n, int32_t r, hipStream_t st) {
+    if (r <= 1024) return launch_gq<D, 4>(G, plan, T, S, m, n, r, st);
+    return launch_gq<D, 2>(G, plan, T, S, m, n, r, st);
+}
+
+hipError_t launch_compress_planned(const void* G, const uint8_t* plan, int64_t m, int64_t n, int32_t r, int32_t d,
+                                   float* S, lsp_dtype dtype, float* T, hipStream_t st) {
+    hipError_t e;
+    switch (dtype) {
+        case LSP_F32:  e = launch_gq_rg<F32>(G, plan, T, S, m, n, r, st); break;
+        case LSP_F16:  e = launch_gq_rg<F16>(G, plan, T, S, m, n, r, st); break;
+        default:       e = launch_gq_rg<BF16>(G, plan, T, S, m, n, r, st); break;
+    }
+    if (e != hipSuccess) return e;
+    const unsigned items = (unsigned)plan_max_items(m, r, d);
+    if (r % 4 == 0) hipLaunchKernelGGL(k_compress_pt<true>, dim3(items), dim3(128), 0, st, plan, T, S, (int)r);
+    else            hipLaunchKernelGGL(k_compress_pt<false>, dim3(items), dim3(128), 0, st, plan, T, S, (int)r);
+    return hipGetLastError();
+}
+
+template <typename D>
+static hipError_t launch_raw_gq(const void* G, const int32_t* Q_idx, const float* Q_val, float* T,
+                                int64_t m, int64_t n, int32_t r, int32_t d, hipStream_t st) {
+    const size_t lds = (size_t)kRawRows * r * sizeof(float);
+    auto kern = k_raw_gq<D>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((m + kRawRows - 1) / kRawRows)), dim3(256), lds, st,
+                       reinterpret_cast<const typename D::elem*>(G), Q_idx, Q_val, T, (int)m, (int)n, (int)r, (int)d);
+    return hipGetLastError();
+}
+
+hipError_t launch_compress_raw(const void* G, const int32_t* P_idx, const float* P_val,
+                               const int32_t* Q_idx, const float* Q_val,
+                               int64_t m, int64_t n, int32_t r, int32_t d,
+                               float* S, lsp_dtype dtype, float* T, hipStream_t st) {
+    hipError_t e;
+    switch (dtype) {
+        case LSP_F32:  e = launch_raw_gq<F32>(G, Q_idx, Q_val, T, m, n, r, d, st); break;
+        case LSP_F16:  e = launch_raw_gq<F16>(G, Q_idx, Q_val, T, m, n, r, d, st); break;
+        default:       e = launch_raw_gq<BF16>(G, Q_idx, Q_val, T, m, n, r, d, st); break;
+    }
+    if (e != hipSuccess) return e;
+    const int64_t rr = (int64_t)r * r;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((rr + 255) / 256 > 1024 ? 1024 : (rr + 255) / 256)), dim3(256), 0, st, S, rr);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_raw_pt, dim3((unsigned)m), dim3(256), 0, st, T, P_idx, P_val, S, (int)r, (int)d);
+    return hipGetLastError();
+}
+
+}  // namespace lsp

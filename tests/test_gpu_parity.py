@@ -1,0 +1,185 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
+element on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import lsp_synth as syn
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+THREADS = 16
+
+
+def _dp(pb):
+    from gpu_util import DeviceProblem
+    return DeviceProblem(pb)
+
+
+def _full_check(pb, tight=5e-5, raw=True):
+    import gpu_util as gu
+    print(f"[case] {pb.name} m={pb.m} n={pb.n} r={pb.r} d={pb.d} {pb.dtype}", flush=True)
+    dp = _dp(pb)
+    S_o = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, threads=THREADS)
+    S_p = dp.compress_planned()
+    e1 = gu.check_compress(S_p, S_o, pb.name + " planned", tight)
+    if raw:
+        S_r = dp.compress_raw()
+        gu.check_compress(S_r, S_o, pb.name + " raw", tight)
+    Wp, Wr = oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val,
+                                     threads=THREADS)
+    W_g = dp.decompress(pb.S_in)
+    mism = gu.check_decompress(W_g, pb.W, Wp, Wr, pb.dtype, pb.name)
+    assert mism < 0.02, f"{pb.name}: {mism:.4f} of W differs from the singly rounded oracle"
+    print(f"[ok]   {pb.name} compress rel err {e1:.2e}, W mismatch fraction {mism:.2e}", flush=True)
+    return dp
+
+
+# ------------------------------------------------------------------ BASELINE configurations
+def test_config1_fp32_small():
+    dp = _full_check(syn.config1(), tight=2e-6)
+    # round trip: decompress the compressed gradient (what MaybeUpdate's bias test composes)
+    import gpu_util as gu
+    pb = dp.pb
+    S_g = dp.compress_planned()
+    Wp, Wr = oracle.decompress_apply(pb.W, pb.dtype, S_g, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    gu.check_decompress(dp.decompress(S_g), pb.W, Wp, Wr, pb.dtype, "cfg1 round trip")
+
+
+def test_config2_fp16_attention():
+    _full_check(syn.config2())
+
+
+def test_config3_fp16_mlp_heavy_rows():
+    for pb in syn.config3():
+        _full_check(pb)
+
+
+@pytest.mark.parametrize("which", [0, 1, 3])      # down 11008x4096, gate 4096x11008, o 4096x4096
+def test_config4_bf16_layer_shapes(which):
+    _full_check(syn.config4_matrix(31, which), raw=(which == 3))
+
+
+@pytest.mark.parametrize("r,d", [(256, 16), (512, 8), (1024, 2), (1024, 16)])
+def test_config5_bf16_zipf_wide(r, d):
+    # skewed columns: lists are cut into pieces and summed with atomics; accumulation error grows
+    # with the number of terms per entry (up to ~2.6e5), still far below the bar
+    _full_check(syn.config5_point(r, d, index=r + d), tight=2e-4, raw=False)
+
+
+# ------------------------------------------------------------------ bit-exact index handling
+@pytest.mark.parametrize("m,n,r,d,dtype,dist", [
+    (256, 2048, 64, 4, "bf16", "uniform"),
+    (100, 3000, 16, 2, "f16", "distinct"),       # ragged rows, three chunks
+    (64, 1040, 8, 8, "bf16", "zipf"),            # cut lists, atomic pieces
+    (48, 1000, 20, 3, "f32", "uniform"),         # generic decompress kernel (d = 3)
+    (37, 53, 6, 1, "f32", "uniform"),            # selection-like, everything ragged
+])
+def test_integer_inputs_bit_exact(m, n, r, d, dtype, dist):
+    pb = syn.make_integer_problem("int", m, n, r, d, dtype, seed=900 + m, index_dist=dist)
+    print(f"[case] integer m={m} n={n} r={r} d={d} {dtype} {dist}", flush=True)
+    dp = _dp(pb)
+    S_o = oracle.compress(pb.G, dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r)
+    assert np.abs(S_o).max() < 2 ** 24                       # exactly representable in fp32
+    assert np.array_equal(dp.compress_planned().astype(np.float64), S_o)
+    assert np.array_equal(dp.compress_raw().astype(np.float64), S_o)
+    Wp, Wr = oracle.decompress_apply(pb.W, dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val)
+    W_g = dp.decompress(pb.S_in)
+    if dtype == "f32":
+        assert np.array_equal(W_g, Wr)
+    else:
+        # the fp32 update is exact on integers, so the single rounding to 16 bits must agree bit for bit
+        assert np.array_equal(W_g.view(np.uint16), Wr.view(np.uint16))
+
+
+def test_selection_projectors_block_sums_bit_exact():
+    rng = np.random.default_rng(5)
+    m, n, r = 300, 2500, 32
+    G = syn.integer_matrix(m, n, -8, 8, "bf16", rng)
+    p = rng.integers(0, r, size=(m, 1)).astype(np.int32)
+    q = rng.integers(0, r, size=(n, 1)).astype(np.int32)
+    pb = syn.Problem("sel", m, n, r, 1, "bf16", G, G.copy(), p, np.ones((m, 1), np.float32), q,
+                     np.ones((n, 1), np.float32), np.zeros((r, r), np.float32))
+    G64 = syn.storage_to_f64(G, "bf16")
+    ref = np.zeros((r, r))
+    np.add.at(ref, (p[:, 0][:, None], q[:, 0][None, :]), G64)       # plain block sums of G
+    dp = _dp(pb)
+    assert np.array_equal(dp.compress_planned().astype(np.float64), ref)
+    assert np.array_equal(dp.compress_raw().astype(np.float64), ref)
+
+
+# ------------------------------------------------------------------ edge shapes
+@pytest.mark.parametrize("m,n,r,d,dtype", [
+    (1, 1, 1, 1, "f32"),
+    (1, 8, 4, 2, "bf16"),
+    (17, 9, 5, 5, "f16"),            # d == r, nothing aligned
+    (16, 1024, 16, 2, "bf16"),       # exactly one tile, one chunk
+    (15, 1025, 12, 4, "bf16"),       # one row short, one column over a chunk
+    (130, 4100, 256, 4, "f16"),
+    (40, 2048, 2048, 8, "bf16"),     # largest subspace (two-plane kernels)
+    (33, 520, 1030, 2, "bf16"),      # r not a multiple of 4 above 1024
+    (24, 64, 1000, 16, "f32"),
+])
+def test_edge_shapes(m, n, r, d, dtype):
+    pb = syn.make_problem(f"edge_{m}x{n}_r{r}_d{d}", m, n, r, d, dtype, seed=300 + m + n, g_std=0.5,
+                          index_dist="uniform" if d < r else "distinct")
+    _full_check(pb)
+
+
+def test_zero_and_identity_cases():
+    pb = syn.make_problem("zero", 64, 2048, 128, 4, "bf16", seed=42)
+    dp = _dp(pb)
+    # S = 0 leaves W unchanged bit for bit
+    W_g = dp.decompress(np.zeros((pb.r, pb.r), np.float32))
+    assert np.array_equal(W_g, pb.W)
+    # G = 0 gives S = 0 exactly (and S is overwritten, not accumulated: it was NaN-filled)
+    dp.G.zero_()
+    assert not dp.compress_planned().any()
+    assert not dp.compress_raw().any()
+
+
+def test_planned_path_is_reproducible_and_plan_reusable():
+    pb = syn.config2()
+    dp = _dp(pb)
+    a = dp.compress_planned()
+    b = dp.compress_planned()
+    assert np.array_equal(a, b)                      # no atomics on this path for uniform projectors
+    # a second gradient through the same plan (projectors fixed between refreshes)
+    G2 = syn.gaussian_matrix(pb.m, pb.n, 1e-3, pb.dtype, np.random.default_rng(99))
+    import gpu_util as gu
+    dp.G.copy_(gu.to_device(G2, pb.dtype))
+    S2 = dp.compress_planned()
+    S2_o = oracle.compress(G2, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, threads=THREADS)
+    gu.check_compress(S2, S2_o, "cfg2 second gradient")
+
+
+def test_fp16_subnormals_are_not_flushed():
+    m, n, r, d = 32, 1024, 16, 2
+    rng = np.random.default_rng(7)
+    # gradients entirely below the fp16 minimum normal (6.1e-5): flushing them would give S = 0
+    G = (rng.integers(1, 1023, size=(m, n)).astype(np.uint16)).view(np.float16)
+    P_idx, P_val = syn.ell_projector(m, r, d, rng, value_mode="smallint")
+    Q_idx, Q_val = syn.ell_projector(n, r, d, rng, value_mode="smallint")
+    pb = syn.Problem("sub", m, n, r, d, "f16", G, G.copy(), P_idx, P_val, Q_idx, Q_val,
+                     np.zeros((r, r), np.float32))
+    S_o = oracle.compress(G, "f16", P_idx, P_val, Q_idx, Q_val, r)
+    assert np.abs(S_o).max() > 0
+    import gpu_util as gu
+    dp = _dp(pb)
+    gu.check_compress(dp.compress_planned(), S_o, "fp16 subnormal", tight=1e-6)
+    gu.check_compress(dp.compress_raw(), S_o, "fp16 subnormal raw", tight=1e-6)
+
+
+def test_validate_projector_and_plan_index_error():
+    import torch
+    import paper_2406_10181_amd as L
+    pb = syn.make_problem("val", 64, 64, 16, 2, "f32", seed=1)
+    dp = _dp(pb)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert L.lsp_validate_projector(dp.Q_idx, 64, 2, 16, flag) == 0
+    bad = dp.Q_idx.clone()
+    bad[5, 1] = 16
+    assert L.lsp_validate_projector(bad, 64, 2, 16, flag) == -6
+    plan = torch.empty(L.lsp_plan_bytes(64, 64, 16, 2), dtype=torch.uint8, device="cuda")
+    rc = L.lsp_plan_build(dp.P_idx, dp.P_val, bad, dp.Q_val, 64, 64, 16, 2, plan, plan.numel(), check=False)
+    assert rc == -6
