@@ -8,6 +8,8 @@
 //   B  S = P^T T   one workgroup per piece of a row of P^T; reads rows of T.
 // The path is bandwidth-bound (one pass over G); no matrix cores are involved because the
 // projectors are sparse (d entries per row, Def. 1) and the work is gather + fp32 FMA.
+#include <cstdlib>
+
 #include "lsp_internal.h"
 
 namespace lsp {
@@ -15,6 +17,8 @@ namespace lsp {
 constexpr int kPlaneStride = kChunk * 16 + 16;   // bytes; last 16 bytes of a plane stay zero
 constexpr int kThreadsA = 256;
 constexpr int kWavesA = kThreadsA / kWave;
+constexpr int kBatch = 8;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ----------------------------------------------------------------------------------------------
 // eight consecutive elements of one row, as loaded
@@ -164,63 +168,102 @@ __global__ __launch_bounds__(kThreadsA) void k_compress_gq(const typename D::ele
             float acc[RG][4];
 #pragma unroll
             for (int g = 0; g < RG; ++g) acc[g][0] = acc[g][1] = acc[g][2] = acc[g][3] = 0.0f;
-#pragma unroll 2
-            for (int e = 0; e < ri.len; ++e) {
-                const uint2 en = ep[(size_t)e * kWave];
+            auto consume = [&](const uint2 en) {
                 const float v = __uint_as_float(en.y);
 #pragma unroll
                 for (int g = 0; g < RG; ++g) {
-                    const float4 x = *reinterpret_cast<const float4*>(smem + en.x + g * kPlaneStride);
+                    const f32x4 x = *reinterpret_cast<const f32x4*>(smem + en.x + g * kPlaneStride);
                     acc[g][0] = fmaf(v, x.x, acc[g][0]);
                     acc[g][1] = fmaf(v, x.y, acc[g][1]);
                     acc[g][2] = fmaf(v, x.z, acc[g][2]);
                     acc[g][3] = fmaf(v, x.w, acc[g][3]);
                 }
+            };
+            int e = 0;
+            for (; e + kBatch <= ri.len; e += kBatch) {      // kBatch entry loads in flight at once
+                uint2 en[kBatch];
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q) en[q] = ep[(size_t)(e + q) * kWave];
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q) consume(en[q]);
             }
+            for (; e < ri.len; ++e) consume(ep[(size_t)e * kWave]);
             if (b != kNoColumn) {
+                const uint32_t bb = b & 0x7FFFu;
+                if (b & kSharedColumn) {
+                    // this column's list was cut into pieces that other lanes add to as well
 #pragma unroll
-                for (int g = 0; g < RG; ++g)
+                    for (int g = 0; g < RG; ++g)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) atomicAdd(&Tl[(g * 4 + t) * r + b], acc[g][t]);
+                        for (int t = 0; t < 4; ++t) atomicAdd(&Tl[(g * r + bb) * 4 + t], acc[g][t]);
+                } else {
+                    // the whole (chunk, column) list belongs to this lane: plain read-modify-write
+                    f32x4* Tl4 = reinterpret_cast<f32x4*>(Tl);
+#pragma unroll
+                    for (int g = 0; g < RG; ++g) {
+                        f32x4 x = Tl4[g * r + bb];
+                        x.x += acc[g][0]; x.y += acc[g][1]; x.z += acc[g][2]; x.w += acc[g][3];
+                        Tl4[g * r + bb] = x;
+                    }
+                }
             }
         }
     }
     __syncthreads();
     for (int k = tid; k < R * r; k += kThreadsA) {
-        const int t = k / r;
-        if (i0 + t < m) T[(i0 + t) * (int64_t)r + (k - t * r)] = Tl[k];
+        const int t = k / r, b = k - t * r;                  // T tile is [plane][b][4 rows] in LDS
+        if (i0 + t < m) T[(i0 + t) * (int64_t)r + b] = Tl[((t >> 2) * r + b) * 4 + (t & 3)];
     }
 }
 
 // ----------------------------------------------------------------------------------------------
-// Kernel B.  One workgroup per piece of a row of P^T:  S[a][:] (+)= sum_e v_e T[i_e][:].
+// Kernel B.  S[a][stripe] (+)= sum_e v_e T[i_e][stripe] for one piece of a row of P^T and one
+// stripe of 256 columns.  A workgroup is 4 waves; wave w takes entries w, w+4, ... of the piece, so
+// an entry (row of T, value) is uniform over the wave (scalar loads) and the 64 lanes read 1 KB of
+// that row of T in one 128-bit load each; the four partial sums meet in LDS.
+constexpr int kThreadsB = 256;
+constexpr int kStripeQuads = 64;                              // column quads (float4) per stripe
 template <bool VEC4>
-__global__ __launch_bounds__(128) void k_compress_pt(const uint8_t* __restrict__ plan, const float* __restrict__ T,
-                                                    float* __restrict__ S, int r) {
+__global__ __launch_bounds__(kThreadsB) void k_compress_pt(const uint8_t* __restrict__ plan, const float* __restrict__ T,
+                                                          float* __restrict__ S, int r, int nstripes) {
+    __shared__ f32x4 part[3][kStripeQuads];
     const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
-    if ((int)blockIdx.x >= H->p_nitems) return;
-    const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[blockIdx.x];
+    const int stripe = blockIdx.x % nstripes, item = blockIdx.x / nstripes;
+    if (item >= H->p_nitems) return;
+    const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[item];
     const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
     if constexpr (VEC4) {
-        for (int b0 = threadIdx.x * 4; b0 < r; b0 += 128 * 4) {
-            float4 acc = make_float4(0, 0, 0, 0);
+        const int nb4 = r >> 2;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+        const int b4 = stripe * kStripeQuads + lane;
+        const bool live = b4 < nb4;
+        const float* Tcol = T + (live ? b4 * 4 : 0);
+        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 8
-            for (int e = 0; e < it.len; ++e) {
-                const uint2 en = ent[e];
-                const float v = __uint_as_float(en.y);
-                const float4 x = *reinterpret_cast<const float4*>(T + (int64_t)en.x * r + b0);
-                acc.x = fmaf(v, x.x, acc.x); acc.y = fmaf(v, x.y, acc.y);
-                acc.z = fmaf(v, x.z, acc.z); acc.w = fmaf(v, x.w, acc.w);
+        for (int e = wave; e < it.len; e += 4) {
+            const uint2 en = ent[e];                          // uniform over the wave
+            const float v = __uint_as_float(en.y);
+            const f32x4 x = *reinterpret_cast<const f32x4*>(Tcol + (int64_t)en.x * r);
+            acc.x = fmaf(v, x.x, acc.x); acc.y = fmaf(v, x.y, acc.y);
+            acc.z = fmaf(v, x.z, acc.z); acc.w = fmaf(v, x.w, acc.w);
+        }
+        if (wave > 0) part[wave - 1][lane] = acc;
+        __syncthreads();
+        if (wave == 0 && live) {
+#pragma unroll
+            for (int g = 0; g < 3; ++g) {
+                const f32x4 p = part[g][lane];
+                acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w;
             }
-            float* dst = S + (int64_t)it.a * r + b0;
+            float* dst = S + (int64_t)it.a * r + b4 * 4;
             if (it.atomic) {
                 atomicAdd(dst + 0, acc.x); atomicAdd(dst + 1, acc.y); atomicAdd(dst + 2, acc.z); atomicAdd(dst + 3, acc.w);
             } else {
-                *reinterpret_cast<float4*>(dst) = acc;
+                *reinterpret_cast<f32x4*>(dst) = acc;
             }
         }
     } else {
-        for (int b = threadIdx.x; b < r; b += 128) {
+        for (int b = stripe * kStripeQuads * 4 + threadIdx.x; b < min(r, (stripe + 1) * kStripeQuads * 4); b += kThreadsB) {
             float acc = 0.0f;
             for (int e = 0; e < it.len; ++e) {
                 const uint2 en = ent[e];
@@ -294,7 +337,9 @@ static hipError_t launch_gq(const void* G, const uint8_t* plan, float* T, float*
 
 template <typename D>
 static hipError_t launch_gq_rg(const void* G, const uint8_t* plan, float* T, float* S, int64_t m, int64_t n, int32_t r, hipStream_t st) {
-    if (r <= 1024) return launch_gq<D, 4>(G, plan, T, S, m, n, r, st);
+    int rg = (r <= 1024 && (m + 15) / 16 >= 3 * 256) ? 4 : 2;
+    if (const char* e = getenv("LSP_DEV_RGC")) rg = (atoi(e) == 4 && r <= 1024) ? 4 : 2;
+    if (rg == 4) return launch_gq<D, 4>(G, plan, T, S, m, n, r, st);
     return launch_gq<D, 2>(G, plan, T, S, m, n, r, st);
 }
 
@@ -307,9 +352,10 @@ hipError_t launch_compress_planned(const void* G, const uint8_t* plan, int64_t m
         default:       e = launch_gq_rg<BF16>(G, plan, T, S, m, n, r, st); break;
     }
     if (e != hipSuccess) return e;
-    const unsigned items = (unsigned)plan_max_items(m, r, d);
-    if (r % 4 == 0) hipLaunchKernelGGL(k_compress_pt<true>, dim3(items), dim3(128), 0, st, plan, T, S, (int)r);
-    else            hipLaunchKernelGGL(k_compress_pt<false>, dim3(items), dim3(128), 0, st, plan, T, S, (int)r);
+    const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
+    const unsigned items = (unsigned)plan_max_items(m, r, d) * (unsigned)nstripes;
+    if (r % 4 == 0) hipLaunchKernelGGL(k_compress_pt<true>, dim3(items), dim3(kThreadsB), 0, st, plan, T, S, (int)r, nstripes);
+    else            hipLaunchKernelGGL(k_compress_pt<false>, dim3(items), dim3(kThreadsB), 0, st, plan, T, S, (int)r, nstripes);
     return hipGetLastError();
 }
 

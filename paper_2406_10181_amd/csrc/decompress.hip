@@ -6,43 +6,56 @@
 //            their rows of Q in registers, and for each 4-row plane gathers U with one 128-bit
 //            LDS read per pair; W is read, updated in fp32 and rounded once.
 // Bandwidth-bound (read + write of W); no matrix cores (sparse gather + fp32 FMA).
+#include <cstdlib>
+
 #include "lsp_internal.h"
 
 namespace lsp {
 
-constexpr int kThreadsD = 256;
+constexpr int kThreadsD = 256;   // generic kernel
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <typename D, int CPT> struct Vec;     // CPT consecutive elements of W
-template <> struct Vec<F32, 4>  { float4 v; };
-template <> struct Vec<F16, 4>  { uint2 v; };
-template <> struct Vec<BF16, 4> { uint2 v; };
+template <> struct Vec<F32, 4>  { f32x4 v; };
+template <> struct Vec<F32, 2>  { float x, y; };
+template <> struct Vec<F16, 4>  { uint32_t x, y; };
+template <> struct Vec<BF16, 4> { uint32_t x, y; };
+template <> struct Vec<F16, 2>  { uint32_t x; };
+template <> struct Vec<BF16, 2> { uint32_t x; };
 
-template <typename D> __device__ __forceinline__ void vec_widen(const Vec<D, 4>& x, float out[4]);
-template <> __device__ __forceinline__ void vec_widen<F32>(const Vec<F32, 4>& x, float out[4]) {
-    out[0] = x.v.x; out[1] = x.v.y; out[2] = x.v.z; out[3] = x.v.w;
+template <typename D> __device__ __forceinline__ void pair_widen(uint32_t p, float& lo, float& hi);
+template <> __device__ __forceinline__ void pair_widen<F16>(uint32_t p, float& lo, float& hi) {
+    lo = widen<F16>((uint16_t)(p & 0xFFFFu)); hi = widen<F16>((uint16_t)(p >> 16));
 }
-template <> __device__ __forceinline__ void vec_widen<F16>(const Vec<F16, 4>& x, float out[4]) {
-    out[0] = widen<F16>((uint16_t)(x.v.x & 0xFFFFu)); out[1] = widen<F16>((uint16_t)(x.v.x >> 16));
-    out[2] = widen<F16>((uint16_t)(x.v.y & 0xFFFFu)); out[3] = widen<F16>((uint16_t)(x.v.y >> 16));
+template <> __device__ __forceinline__ void pair_widen<BF16>(uint32_t p, float& lo, float& hi) {
+    lo = __uint_as_float(p << 16); hi = __uint_as_float(p & 0xFFFF0000u);
 }
-template <> __device__ __forceinline__ void vec_widen<BF16>(const Vec<BF16, 4>& x, float out[4]) {
-    out[0] = __uint_as_float(x.v.x << 16); out[1] = __uint_as_float(x.v.x & 0xFFFF0000u);
-    out[2] = __uint_as_float(x.v.y << 16); out[3] = __uint_as_float(x.v.y & 0xFFFF0000u);
-}
-template <typename D> __device__ __forceinline__ Vec<D, 4> vec_narrow(const float in[4]);
-template <> __device__ __forceinline__ Vec<F32, 4> vec_narrow<F32>(const float in[4]) {
-    return {make_float4(in[0], in[1], in[2], in[3])};
-}
-template <> __device__ __forceinline__ Vec<F16, 4> vec_narrow<F16>(const float in[4]) {
-    return {make_uint2((uint32_t)narrow<F16>(in[0]) | ((uint32_t)narrow<F16>(in[1]) << 16),
-                       (uint32_t)narrow<F16>(in[2]) | ((uint32_t)narrow<F16>(in[3]) << 16))};
-}
-template <> __device__ __forceinline__ Vec<BF16, 4> vec_narrow<BF16>(const float in[4]) {
-    return {make_uint2((uint32_t)narrow<BF16>(in[0]) | ((uint32_t)narrow<BF16>(in[1]) << 16),
-                       (uint32_t)narrow<BF16>(in[2]) | ((uint32_t)narrow<BF16>(in[3]) << 16))};
+template <typename D> __device__ __forceinline__ uint32_t pair_narrow(float lo, float hi) {
+    return (uint32_t)narrow<D>(lo) | ((uint32_t)narrow<D>(hi) << 16);
 }
 
-// phase 1, shared by both kernels:  Us[plane][b] (float4 = 4 rows) = sum_k P_val[i][k] S[P_idx[i][k]][b]
+template <typename D, int CPT> __device__ __forceinline__ void vec_widen(const Vec<D, CPT>& x, float* out) {
+    if constexpr (D::size == 4) {
+        if constexpr (CPT == 4) { out[0] = x.v.x; out[1] = x.v.y; out[2] = x.v.z; out[3] = x.v.w; }
+        else { out[0] = x.x; out[1] = x.y; }
+    } else {
+        pair_widen<D>(x.x, out[0], out[1]);
+        if constexpr (CPT == 4) pair_widen<D>(x.y, out[2], out[3]);
+    }
+}
+template <typename D, int CPT> __device__ __forceinline__ Vec<D, CPT> vec_narrow(const float* in) {
+    Vec<D, CPT> o;
+    if constexpr (D::size == 4) {
+        if constexpr (CPT == 4) { o.v.x = in[0]; o.v.y = in[1]; o.v.z = in[2]; o.v.w = in[3]; }
+        else { o.x = in[0]; o.y = in[1]; }
+    } else {
+        o.x = pair_narrow<D>(in[0], in[1]);
+        if constexpr (CPT == 4) o.y = pair_narrow<D>(in[2], in[3]);
+    }
+    return o;
+}
+
+// phase 1 (generic kernel):  Us[plane][b] (float4 = 4 rows) = sum_k P_val[i][k] S[P_idx[i][k]][b]
 // `plane` is the distance between planes in float4 units (>= r).
 template <int RG>
 __device__ __forceinline__ void build_u_tile(float4* Us, const float* __restrict__ S,
@@ -68,35 +81,94 @@ __device__ __forceinline__ void build_u_tile(float4* Us, const float* __restrict
     }
 }
 
-// Fast kernel: DD = compile-time d, 4 columns per thread, n % 4 == 0.  PS = bytes between the
-// 4-row planes of U in LDS, a compile-time constant >= 16 r so that the plane offset folds into the
-// immediate offset of the LDS read and a gather costs no address arithmetic.
-template <typename D, int RG, int DD, int PS>
-__global__ __launch_bounds__(kThreadsD) void k_decompress(typename D::elem* __restrict__ W, const float* __restrict__ S,
-                                                         const int32_t* __restrict__ P_idx, const float* __restrict__ P_val,
-                                                         const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
-                                                         int m, int n, int r) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    float4* Us = reinterpret_cast<float4*>(smem);
+// phase 1 (fast kernel, r % 4 == 0): the R*DD (row of S, value) pairs of the tile go to LDS first,
+// then every work item (row t of the tile, 4 consecutive columns b) issues its DD 128-bit loads of
+// S back to back, so the whole gather costs two memory round trips.
+template <int RG, int DD, int PS, int NT>
+__device__ __forceinline__ void build_u_tile_fast(uint8_t* smem, int2* pent, const float* __restrict__ S,
+                                                  const int32_t* __restrict__ P_idx, const float* __restrict__ P_val,
+                                                  int64_t i0, int m, int r) {
     constexpr int R = 4 * RG;
-    constexpr int CPT = 4;
+    for (int q = threadIdx.x; q < R * DD; q += NT) {
+        const int64_t i = i0 + q / DD;
+        int2 e = make_int2(0, 0);                                   // rows past m: value 0, row 0 of S
+        if (i < m) e = make_int2(P_idx[i * DD + q % DD], __float_as_int(P_val[i * DD + q % DD]));
+        pent[q] = e;
+    }
+    __syncthreads();
+    const int r4 = r >> 2;
+    for (int q = threadIdx.x; q < r4 * R; q += NT) {
+        const int row = q / r4, b4 = q - row * r4;                  // row of the tile, column quad
+        f32x4 x[DD];
+#pragma unroll
+        for (int k = 0; k < DD; ++k)
+            x[k] = *reinterpret_cast<const f32x4*>(S + (int64_t)pent[row * DD + k].x * r + b4 * 4);
+        f32x4 u = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int k = 0; k < DD; ++k) {
+            const float v = __int_as_float(pent[row * DD + k].y);
+            u.x = fmaf(v, x[k].x, u.x); u.y = fmaf(v, x[k].y, u.y);
+            u.z = fmaf(v, x[k].z, u.z); u.w = fmaf(v, x[k].w, u.w);
+        }
+        // Us[plane][b] is a float4 over the plane's 4 rows: element (b, t) lives at float index 4 b + t
+        float* dst = reinterpret_cast<float*>(smem + (row >> 2) * PS) + (b4 * 4) * 4 + (row & 3);
+        dst[0] = u.x; dst[4] = u.y; dst[8] = u.z; dst[12] = u.w;
+    }
+}
+
+// Fast kernel: DD = compile-time d, CPT columns per thread, n % CPT == 0, r % 4 == 0.  PS = bytes
+// between the 4-row planes of U in LDS, a compile-time constant >= 16 r so that the plane offset
+// folds into the immediate offset of the LDS read and a gather costs no address arithmetic.
+// All loads of a pass (the thread's rows of Q and its R x CPT patch of W) are issued before the
+// gathers start, so one pass costs one HBM round trip; many waves per CU overlap the passes.
+template <typename D, int RG, int DD, int PS, int NT, int CPT>
+__global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict__ W, const float* __restrict__ S,
+                                                  const int32_t* __restrict__ P_idx, const float* __restrict__ P_val,
+                                                  const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
+                                                  int m, int n, int r, int devmode) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    constexpr int R = 4 * RG;
+    constexpr int NE = CPT * DD;                                    // entries owned by a thread in one pass
+    static_assert(NE % 4 == 0, "entries are loaded 4 at a time");
     const int64_t i0 = (int64_t)blockIdx.x * R;
-    build_u_tile<RG>(Us, S, P_idx, P_val, i0, m, r, DD, PS / 16);
+    int2* pent = reinterpret_cast<int2*>(smem + RG * PS);
+    const f32x4* Us4 = reinterpret_cast<const f32x4*>(smem);
+
+    // one pass = this thread's CPT columns: their rows of Q (NE pairs, flat index c * DD + k) and
+    // the R x CPT patch of W
+    struct Pass { int4 qi[NE / 4]; f32x4 qv[NE / 4]; Vec<D, CPT> wv[R]; };
+    auto load_pass = [&](int64_t j0, Pass& p) {
+        const int4* qip = reinterpret_cast<const int4*>(Q_idx + j0 * DD);
+        const f32x4* qvp = reinterpret_cast<const f32x4*>(Q_val + j0 * DD);
+#pragma unroll
+        for (int k = 0; k < NE / 4; ++k) {
+            if (devmode & 4) { p.qi[k] = make_int4(k, k + 1, k + 2, k + 3); p.qv[k] = f32x4{1.f, 2.f, 3.f, 4.f}; }
+            else { p.qi[k] = qip[k]; p.qv[k] = qvp[k]; }
+        }
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const int64_t i = i0 + t < m ? i0 + t : m - 1;         // rows past m: any valid row, never stored
+            p.wv[t] = *reinterpret_cast<const Vec<D, CPT>*>(W + i * (int64_t)n + j0);
+        }
+    };
+    auto idx_of = [](const Pass& p, int e) -> uint32_t {
+        const int4 q = p.qi[e >> 2];
+        return (uint32_t)((e & 3) == 0 ? q.x : (e & 3) == 1 ? q.y : (e & 3) == 2 ? q.z : q.w);
+    };
+    auto val_of = [](const Pass& p, int e) -> float {
+        const f32x4 q = p.qv[e >> 2];
+        return (e & 3) == 0 ? q.x : (e & 3) == 1 ? q.y : (e & 3) == 2 ? q.z : q.w;
+    };
+
+    const int64_t step = (int64_t)NT * CPT;
+    int64_t j0 = (int64_t)threadIdx.x * CPT;
+    Pass cur, nxt;
+    if (j0 < n) load_pass(j0, cur);                                 // in flight while the U tile is built
+    if (!(devmode & 2)) build_u_tile_fast<RG, DD, PS, NT>(smem, pent, S, P_idx, P_val, i0, m, r);
     __syncthreads();
 
-    for (int64_t j0 = (int64_t)threadIdx.x * CPT; j0 < n; j0 += (int64_t)kThreadsD * CPT) {
-        // the CPT rows of Q owned by this thread: DD (column, value) pairs each
-        uint32_t off[CPT][DD];
-        float val[CPT][DD];
-        const int32_t* qi = Q_idx + j0 * DD;
-        const float* qv = Q_val + j0 * DD;
-#pragma unroll
-        for (int c = 0; c < CPT; ++c)
-#pragma unroll
-            for (int k = 0; k < DD; ++k) {
-                off[c][k] = (uint32_t)qi[c * DD + k] * 16u;
-                val[c][k] = qv[c * DD + k];
-            }
+    for (; j0 < n; j0 += step) {
+        if (j0 + step < n) load_pass(j0 + step, nxt);               // next pass in flight during this one
 #pragma unroll
         for (int g = 0; g < RG; ++g) {
             float acc[4][CPT];
@@ -104,29 +176,31 @@ __global__ __launch_bounds__(kThreadsD) void k_decompress(typename D::elem* __re
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int c = 0; c < CPT; ++c) acc[t][c] = 0.0f;
+            if (!(devmode & 1))
 #pragma unroll
             for (int c = 0; c < CPT; ++c)
 #pragma unroll
                 for (int k = 0; k < DD; ++k) {
-                    const float4 u = *reinterpret_cast<const float4*>(smem + off[c][k] + g * PS);
-                    acc[0][c] = fmaf(val[c][k], u.x, acc[0][c]);
-                    acc[1][c] = fmaf(val[c][k], u.y, acc[1][c]);
-                    acc[2][c] = fmaf(val[c][k], u.z, acc[2][c]);
-                    acc[3][c] = fmaf(val[c][k], u.w, acc[3][c]);
+                    const f32x4 u = Us4[idx_of(cur, c * DD + k) + g * (PS / 16)];
+                    const float v = val_of(cur, c * DD + k);
+                    acc[0][c] = fmaf(v, u.x, acc[0][c]);
+                    acc[1][c] = fmaf(v, u.y, acc[1][c]);
+                    acc[2][c] = fmaf(v, u.z, acc[2][c]);
+                    acc[3][c] = fmaf(v, u.w, acc[3][c]);
                 }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int64_t i = i0 + g * 4 + t;
                 if (i < m) {
-                    Vec<D, CPT>* p = reinterpret_cast<Vec<D, CPT>*>(W + i * (int64_t)n + j0);
-                    float w[4];
-                    vec_widen<D>(*p, w);
+                    float w[CPT];
+                    vec_widen<D, CPT>(cur.wv[g * 4 + t], w);
 #pragma unroll
                     for (int c = 0; c < CPT; ++c) w[c] -= acc[t][c];
-                    *p = vec_narrow<D>(w);
+                    *reinterpret_cast<Vec<D, CPT>*>(W + i * (int64_t)n + j0) = vec_narrow<D, CPT>(w);
                 }
             }
         }
+        cur = nxt;
     }
 }
 
@@ -169,22 +243,22 @@ __global__ __launch_bounds__(kThreadsD) void k_decompress_any(typename D::elem* 
     }
 }
 
-template <typename D, int RG, int PS>
+template <typename D, int RG, int PS, int NT, int CPT>
 static hipError_t launch_d(void* W, const float* S, const int32_t* P_idx, const float* P_val,
                            const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
                            hipStream_t st) {
     using E = typename D::elem;
     const unsigned grid = (unsigned)((m + RG * 4 - 1) / (RG * 4));
-    const bool fast = (n % 4) == 0 && (d == 2 || d == 4 || d == 8 || d == 16);
+    const bool fast = (n % 4) == 0 && (r % 4) == 0 && (d == 2 || d == 4 || d == 8 || d == 16);   // CPT * d % 4 == 0 holds
     hipError_t e;
 #define LSP_LAUNCH_FAST(DDV)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_decompress<D, RG, DDV, PS>;                                                              \
-        const size_t lds = (size_t)RG * PS;                                                                    \
+        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT>;                                                          \
+        const size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                              \
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         if (e != hipSuccess) return e;                                                                         \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsD), lds, st, reinterpret_cast<E*>(W), S, P_idx, P_val, \
-                           Q_idx, Q_val, (int)m, (int)n, (int)r);                                              \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, reinterpret_cast<E*>(W), S, P_idx, P_val,      \
+                           Q_idx, Q_val, (int)m, (int)n, (int)r, getenv("LSP_DEV_MODE") ? atoi(getenv("LSP_DEV_MODE")) : 0); \
     } while (0)
     if (fast && d == 2) LSP_LAUNCH_FAST(2);
     else if (fast && d == 4) LSP_LAUNCH_FAST(4);
@@ -202,23 +276,54 @@ static hipError_t launch_d(void* W, const float* S, const int32_t* P_idx, const 
     return hipGetLastError();
 }
 
-template <typename D>
+// rows per workgroup: 16 (four planes) when that still leaves at least three workgroups per CU, else 8
+static int pick_planes(int64_t m, int32_t r) {
+    if (r > 1024) return 2;
+    if (const char* e = getenv("LSP_DEV_RGD")) return atoi(e) == 2 ? 2 : 4;
+    (void)m;
+    return 4;
+}
+
+template <typename D, int NT, int CPT>
 static hipError_t launch_d_rg(void* W, const float* S, const int32_t* P_idx, const float* P_val,
                               const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
                               hipStream_t st) {
-    if (r <= 256)  return launch_d<D, 4, 4096>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-    if (r <= 512)  return launch_d<D, 4, 8192>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-    if (r <= 1024) return launch_d<D, 4, 16384>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-    return launch_d<D, 2, 32768>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+    const int rg = pick_planes(m, r);
+#define LSP_D_CASE(RGV, PSV) return launch_d<D, RGV, PSV, NT, CPT>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st)
+    if (rg == 4) {
+        if (r <= 256) LSP_D_CASE(4, 4096);
+        if (r <= 512) LSP_D_CASE(4, 8192);
+        LSP_D_CASE(4, 16384);
+    }
+    if (r <= 256) LSP_D_CASE(2, 4096);
+    if (r <= 512) LSP_D_CASE(2, 8192);
+    if (r <= 1024) LSP_D_CASE(2, 16384);
+    LSP_D_CASE(2, 32768);
+#undef LSP_D_CASE
+}
+
+template <typename D>
+static hipError_t launch_d_nt(void* W, const float* S, const int32_t* P_idx, const float* P_val,
+                              const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
+                              hipStream_t st) {
+    int nt = 512, cpt = 2;
+    if (const char* e = getenv("LSP_DEV_NTD")) nt = atoi(e);
+    if (const char* e = getenv("LSP_DEV_CPT")) cpt = atoi(e);
+#define LSP_D_ARGS W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st
+    if (cpt == 4) return launch_d_rg<D, 256, 4>(LSP_D_ARGS);
+    if (nt == 1024) return launch_d_rg<D, 1024, 2>(LSP_D_ARGS);
+    if (nt == 512) return launch_d_rg<D, 512, 2>(LSP_D_ARGS);
+    return launch_d_rg<D, 256, 2>(LSP_D_ARGS);
+#undef LSP_D_ARGS
 }
 
 hipError_t launch_decompress(void* W, const float* S, const int32_t* P_idx, const float* P_val,
                              const int32_t* Q_idx, const float* Q_val,
                              int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
     switch (dtype) {
-        case LSP_F32:  return launch_d_rg<F32>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-        case LSP_F16:  return launch_d_rg<F16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-        default:       return launch_d_rg<BF16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+        case LSP_F32:  return launch_d_nt<F32>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+        case LSP_F16:  return launch_d_nt<F16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+        default:       return launch_d_nt<BF16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
     }
 }
 

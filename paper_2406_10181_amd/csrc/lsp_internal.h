@@ -16,7 +16,8 @@ constexpr int kChunk      = 1024;  // columns of G staged in LDS at a time
 constexpr int kWave       = 64;    // gfx950 wavefront
 constexpr int kListMax    = 64;    // a (chunk, column) list longer than this is cut into pieces
 constexpr int kRowPiece   = 128;   // a row list of P^T longer than this is cut into pieces
-constexpr uint32_t kNoColumn = 0xFFFFu;
+constexpr uint32_t kNoColumn = 0xFFFFu;      // lane has no piece in this round
+constexpr uint32_t kSharedColumn = 0x8000u;  // flag on a piece's column: the list was cut, several lanes add to it
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

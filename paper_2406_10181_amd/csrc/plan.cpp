@@ -70,7 +70,7 @@ void build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_
     uint2*     qent   = reinterpret_cast<uint2*>(out + L.off_q_ent);
 
     // ---- Q: per chunk of kChunk columns of G, the entries grouped by subspace column b ----------
-    struct Piece { int32_t b; int32_t start; int32_t len; };
+    struct Piece { int32_t b; int32_t start; int32_t len; int32_t shared; };
     std::vector<int32_t> cnt((size_t)r + 1), cur((size_t)r);
     std::vector<uint2> sorted;                 // entries of one chunk ordered by (b, j, k)
     std::vector<Piece> pieces;
@@ -94,7 +94,8 @@ void build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_
         pieces.clear();
         for (int b = 0; b < r; ++b)
             for (int32_t s = cnt[(size_t)b]; s < cnt[(size_t)b + 1]; s += kListMax)
-                pieces.push_back(Piece{b, s, std::min<int32_t>(kListMax, cnt[(size_t)b + 1] - s)});
+                pieces.push_back(Piece{b, s, std::min<int32_t>(kListMax, cnt[(size_t)b + 1] - s),
+                                       cnt[(size_t)b + 1] - cnt[(size_t)b] > kListMax});
         std::stable_sort(pieces.begin(), pieces.end(),
                          [](const Piece& x, const Piece& y) { return x.len > y.len; });
         chunks[c].first_round = total_rounds;
@@ -108,7 +109,8 @@ void build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_
             for (int lane = 0; lane < kWave; ++lane) {
                 const bool have = p0 + (size_t)lane < pieces.size();
                 cols[(size_t)total_rounds * kWave + (size_t)lane] =
-                    have ? (uint16_t)pieces[p0 + (size_t)lane].b : (uint16_t)kNoColumn;
+                    have ? (uint16_t)(pieces[p0 + (size_t)lane].b | (pieces[p0 + (size_t)lane].shared ? kSharedColumn : 0u))
+                         : (uint16_t)kNoColumn;
                 for (int e = 0; e < len; ++e) {
                     uint2 v{pad_offset, 0u};
                     if (have && e < pieces[p0 + (size_t)lane].len)

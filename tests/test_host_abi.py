@@ -102,6 +102,8 @@ def _replay_plan(buf, pb):
             used_slots += ln * 64
             for lane in range(64):
                 b = int(cols[rho, lane])
+                if b != 0xFFFF:
+                    b &= 0x7FFF                       # bit 15 marks a piece of a cut list
                 for e in range(ln):
                     off, vb = int(ent[e, lane, 0]), ent[e, lane, 1:2]
                     v = float(vb.view(np.float32)[0])
