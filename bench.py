@@ -164,13 +164,13 @@ def main():
 
 
 def cpu_baseline(syn, r, d):
-    """The oracle, as it stands, on a bounded sample: one matrix of each distinct shape of a layer."""
+    """The oracle, as it stands, on a bounded sample: the seven matrices of one layer."""
     import oracle
     cores = len(os.sched_getaffinity(0))
     cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
     total_bytes, total_s = 0, 0.0
     names = []
-    for which in (3, 1, 0):                      # o 4096x4096, gate 4096x11008, down 11008x4096
+    for which in range(7):                       # the 7 matrices of layer 31, backward order
         pb = syn.config4_matrix(31, which)
         t = time.time()
         S = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, threads=cores)
@@ -180,8 +180,8 @@ def cpu_baseline(syn, r, d):
         names.append(f"{pb.m}x{pb.n}")
         del S
     return {"value": round(total_bytes / total_s / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": "compress + decompress-apply of one matrix per distinct layer shape (" + ", ".join(names) +
-                      f"), bf16, r={r}, d={d}; fp64 plain loops, rows split over threads",
+            "sample": "compress + decompress-apply of the 7 matrices of one layer (" + ", ".join(names) +
+                      f"), 1/32 of a step, bf16, r={r}, d={d}; fp64 plain loops, rows split over threads",
             "seconds": round(total_s, 2)}
 
 

@@ -160,15 +160,27 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
         return (e & 3) == 0 ? q.x : (e & 3) == 1 ? q.y : (e & 3) == 2 ? q.z : q.w;
     };
 
+    // Passes are visited in an order rotated by the workgroup's position inside its XCD
+    // (workgroups are dealt to the 8 XCDs round-robin): all workgroups read the same Q arrays, and
+    // without the rotation they would all ask the same few L2 channels for the same lines at once.
     const int64_t step = (int64_t)NT * CPT;
-    int64_t j0 = (int64_t)threadIdx.x * CPT;
+    const int npass = (int)((n + step - 1) / step);
+    const int rot = (devmode & 8) ? 0 : (int)((blockIdx.x / 8) % npass);
+    auto pass_col = [&](int p) -> int64_t {
+        int q = p + rot;
+        if (q >= npass) q -= npass;
+        return (int64_t)q * step + (int64_t)threadIdx.x * CPT;
+    };
     Pass cur, nxt;
+    int64_t j0 = pass_col(0);
     if (j0 < n) load_pass(j0, cur);                                 // in flight while the U tile is built
     if (!(devmode & 2)) build_u_tile_fast<RG, DD, PS, NT>(smem, pent, S, P_idx, P_val, i0, m, r);
     __syncthreads();
 
-    for (; j0 < n; j0 += step) {
-        if (j0 + step < n) load_pass(j0 + step, nxt);               // next pass in flight during this one
+    for (int p = 0; p < npass; ++p) {
+        const int64_t j1 = p + 1 < npass ? pass_col(p + 1) : n;
+        if (j1 < n) load_pass(j1, nxt);                             // next pass in flight during this one
+        if (j0 < n)
 #pragma unroll
         for (int g = 0; g < RG; ++g) {
             float acc[4][CPT];
@@ -201,6 +213,7 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
             }
         }
         cur = nxt;
+        j0 = j1;
     }
 }
 
