@@ -52,7 +52,8 @@ typedef enum {
     LSP_ERR_WORKSPACE = -4,  /* workspace / plan buffer missing, misaligned or too small */
     LSP_ERR_LAUNCH    = -5,  /* the HIP runtime refused a launch or a copy (see lsp_last_hip_error) */
     LSP_ERR_INDEX     = -6,  /* lsp_validate_projector found an index outside [0, r) */
-    LSP_ERR_ALIGN     = -7   /* a base pointer is not 16-byte aligned */
+    LSP_ERR_ALIGN     = -7,  /* a base pointer is not 16-byte aligned */
+    LSP_ERR_SKEW      = -8   /* lsp_plan_build: the columns of Q are used too unevenly for a plan; use lsp_compress */
 } lsp_status;
 
 #define LSP_MAX_R 2048       /* largest supported subspace size (the paper's largest setting) */
@@ -114,8 +115,9 @@ int lsp_plan_build_host(const int32_t* P_idx, const float* P_val,
 
 /* Same sums as lsp_compress, with the projectors given as a plan; gather form, no global
  * atomics unless a row of P^T has more than 128 entries (heavily skewed projectors), and
- * bit-reproducible from run to run whenever no list had to be cut (a column of Q with more
- * than 64 entries inside one 1024-column chunk of G, or such a row of P^T).
+ * bit-reproducible from run to run whenever no list had to be cut (a column of Q used more than
+ * about twice as often as the average inside one 2048-column chunk of G, or a row of P^T with more
+ * than 128 entries).
  * workspace: at least lsp_compress_planned_workspace_bytes(m,n,r,d) bytes. */
 int lsp_compress_planned(const void* G, const void* plan,
                          int64_t m, int64_t n, int32_t r, int32_t d,

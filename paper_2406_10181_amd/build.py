@@ -20,18 +20,18 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = True, save_temps: bool = False) -> str:
+def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, defines=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     for s in SOURCES:
         cmd += ["-x", "hip", os.path.join(CSRC, s)]
-    cmd += ["-o", LIB]
+    cmd += [f"-D{x}" for x in defines] + ["-o", out]
     if save_temps:
         cmd += ["-save-temps=obj"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd, cwd=PKG)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -84,7 +84,8 @@ int lsp_plan_build(const int32_t* P_idx, const float* P_val, const int32_t* Q_id
     for (int32_t v : pi) if (v < 0 || v >= r) return LSP_ERR_INDEX;
     for (int32_t v : qi) if (v < 0 || v >= r) return LSP_ERR_INDEX;
     std::vector<uint8_t> host(need);
-    lsp::build_plan_host(pi.data(), pv.data(), qi.data(), qv.data(), m, n, r, d, host.data());
+    rc = lsp::build_plan_host(pi.data(), pv.data(), qi.data(), qv.data(), m, n, r, d, host.data());
+    if (rc != LSP_OK) return rc;
     if ((e = hipMemcpyAsync(plan, host.data(), need, hipMemcpyHostToDevice, st)) != hipSuccess) return fail_launch(e);
     if ((e = hipStreamSynchronize(st)) != hipSuccess) return fail_launch(e);
     return LSP_OK;
@@ -98,8 +99,7 @@ int lsp_plan_build_host(const int32_t* P_idx, const float* P_val, const int32_t*
     if (!plan_host || plan_bytes < lsp::plan_bytes(m, n, r, d)) return LSP_ERR_WORKSPACE;
     for (int64_t k = 0; k < m * d; ++k) if (P_idx[k] < 0 || P_idx[k] >= r) return LSP_ERR_INDEX;
     for (int64_t k = 0; k < n * d; ++k) if (Q_idx[k] < 0 || Q_idx[k] >= r) return LSP_ERR_INDEX;
-    lsp::build_plan_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, static_cast<uint8_t*>(plan_host));
-    return LSP_OK;
+    return lsp::build_plan_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, static_cast<uint8_t*>(plan_host));
 }
 
 int lsp_compress_planned(const void* G, const void* plan, int64_t m, int64_t n, int32_t r, int32_t d,
@@ -154,6 +154,7 @@ const char* lsp_strerror(int code) {
         case LSP_ERR_LAUNCH:    return "HIP runtime error (see lsp_last_hip_error)";
         case LSP_ERR_INDEX:     return "projector index outside [0, r)";
         case LSP_ERR_ALIGN:     return "a base pointer is not 16-byte aligned";
+        case LSP_ERR_SKEW:      return "projector columns used too unevenly for a plan (use lsp_compress)";
         default:                return "unknown lsp_status";
     }
 }

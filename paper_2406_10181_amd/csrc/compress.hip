@@ -1,10 +1,10 @@
 // Compress: S = P^T G Q  (Alg. 1, compress step; Alg. 3, projected gradient of a layer).
 //
 // Two kernels per call, both gather-form and free of global atomics in the common case:
-//   A  T = G Q     one workgroup per block of R rows of G; G is streamed once from HBM in
+//   A  T = G Q     one workgroup per block of 16 rows of G; G is streamed once from HBM in
 //                  chunks of kChunk columns, widened to fp32 and staged in LDS transposed
-//                  ([column][4 rows], so one 128-bit LDS read serves four rows); each lane walks
-//                  the plan's list of (column, value) pairs of one subspace column b.
+//                  ([column][4 rows], so one 128-bit LDS read serves four rows); each lane owns one
+//                  column b of T and walks the plan's list of (column of G, value) pairs of b.
 //   B  S = P^T T   one workgroup per piece of a row of P^T; reads rows of T.
 // The path is bandwidth-bound (one pass over G); no matrix cores are involved because the
 // projectors are sparse (d entries per row, Def. 1) and the work is gather + fp32 FMA.
@@ -15,10 +15,14 @@
 namespace lsp {
 
 constexpr int kPlaneStride = kChunk * 16 + 16;   // bytes; last 16 bytes of a plane stay zero
-constexpr int kThreadsA = 256;
-constexpr int kWavesA = kThreadsA / kWave;
-constexpr int kBatch = 8;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+#ifndef LSP_ABL
+#define LSP_ABL 0          // development ablations, compile-time only; 0 in every shipped build
+#endif
+#define LSP_ABL_NOCONSUME ((LSP_ABL & 1) != 0)
+#define LSP_ABL_NOSTREAM  ((LSP_ABL & 2) != 0)
+#define LSP_ABL_NOSTAGE   ((LSP_ABL & 4) != 0)
+#define LSP_ABL_NOTWRITE  ((LSP_ABL & 8) != 0)
 
 // ----------------------------------------------------------------------------------------------
 // eight consecutive elements of one row, as loaded
@@ -35,10 +39,10 @@ template <> __device__ __forceinline__ Oct<BF16> oct_zero<BF16>() { return {make
 template <typename D> __device__ __forceinline__ Oct<D> oct_load(const typename D::elem* p);
 template <> __device__ __forceinline__ Oct<F32> oct_load<F32>(const float* p) {
     const float4* q = reinterpret_cast<const float4*>(p);
-    return {q[0], q[1]};
+    return {stream_load(q), stream_load(q + 1)};
 }
-template <> __device__ __forceinline__ Oct<F16> oct_load<F16>(const uint16_t* p) { return {*reinterpret_cast<const uint4*>(p)}; }
-template <> __device__ __forceinline__ Oct<BF16> oct_load<BF16>(const uint16_t* p) { return {*reinterpret_cast<const uint4*>(p)}; }
+template <> __device__ __forceinline__ Oct<F16> oct_load<F16>(const uint16_t* p) { return {stream_load(reinterpret_cast<const uint4*>(p))}; }
+template <> __device__ __forceinline__ Oct<BF16> oct_load<BF16>(const uint16_t* p) { return {stream_load(reinterpret_cast<const uint4*>(p))}; }
 
 // element-wise, bounds-checked variant for ragged or unaligned rows
 template <typename D> __device__ __forceinline__ void oct_gather(const typename D::elem* row, int64_t col0, int64_t n, float out[8]) {
@@ -69,39 +73,43 @@ template <> __device__ __forceinline__ void oct_widen<F16>(const Oct<F16>& o, fl
 }
 
 // ----------------------------------------------------------------------------------------------
-// Kernel A.  RG = number of 4-row planes per workgroup (rows per workgroup R = 4 RG).
-// LDS: RG planes of kPlaneStride bytes (staged chunk of G, fp32), then T tile [R][r] fp32.
+// Kernel A.  One workgroup = 16 rows of G (4 planes of 4 rows), 512 threads, one lane per
+// (virtual) column of T; the lane keeps its 16 partial sums per owned column in registers for the
+// whole kernel, so there is no flush and no atomic in the main loop.
+// LDS: 4 planes of kPlaneStride bytes (staged chunk of G, fp32); at the very end the same memory
+// holds the T tile [16][r] for a coalesced write.
+// Each wave reads one linear stream of plan rows (64 x (LDS offset, value)), always one batch of 8
+// rows ahead in registers; segment lengths come from a small table (scalar loads).
 // VEC: rows are 8-element aligned (n % 8 == 0), vector loads; otherwise element-wise loads.
-template <typename D, int RG, bool VEC>
-__global__ __launch_bounds__(kThreadsA) void k_compress_gq(const typename D::elem* __restrict__ G,
-                                                          const uint8_t* __restrict__ plan,
-                                                          float* __restrict__ T, float* __restrict__ S,
-                                                          int m, int n, int r) {
+constexpr int kPlanes = 4;
+template <typename D, bool VEC>
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::elem* __restrict__ G,
+                                                           const uint8_t* __restrict__ plan,
+                                                           float* __restrict__ T, float* __restrict__ S,
+                                                           int m, int n, int r) {
     extern __shared__ __align__(16) uint8_t smem[];
-    constexpr int R = 4 * RG;
-    constexpr int UNITS = RG * (kChunk / 8);                 // (plane, column octet) units per chunk
-    constexpr int UPT = (UNITS + kThreadsA - 1) / kThreadsA; // units per thread
-    float* Tl = reinterpret_cast<float*>(smem + RG * kPlaneStride);
+    constexpr int R = 4 * kPlanes;
+    constexpr int UNITS = kPlanes * (kChunk / 8);             // (plane, column octet) units per chunk
+    constexpr int UPT = UNITS / kThreadsGQ;                   // units per thread
+    static_assert(UNITS % kThreadsGQ == 0, "staging assumes whole units per thread");
 
     const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
-    const ChunkInfo* chunks = reinterpret_cast<const ChunkInfo*>(plan + H->off_q_chunk);
-    const RoundInfo* rounds = reinterpret_cast<const RoundInfo*>(plan + H->off_q_round);
-    const uint16_t* cols = reinterpret_cast<const uint16_t*>(plan + H->off_q_cols);
-    const uint2* qent = reinterpret_cast<const uint2*>(plan + H->off_q_ent);
-
+    if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t i0 = (int64_t)blockIdx.x * R;
     const int nchunks = H->nchunks;
+    const int nslots = H->nslots;
+    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg);
+    const uint2* rp = reinterpret_cast<const uint2*>(plan + H->off_q_rows) + (size_t)H->q_stream_row[wave] * kWave + lane;
 
     // S must start at zero only when some row of P^T was cut into pieces (kernel B then adds).
     if (H->p_any_split) {
         const int64_t total = (int64_t)r * r;
-        for (int64_t k = (int64_t)blockIdx.x * kThreadsA + tid; k < total; k += (int64_t)gridDim.x * kThreadsA) S[k] = 0.0f;
+        for (int64_t k = (int64_t)blockIdx.x * kThreadsGQ + tid; k < total; k += (int64_t)gridDim.x * kThreadsGQ) S[k] = 0.0f;
     }
-    for (int k = tid; k < R * r; k += kThreadsA) Tl[k] = 0.0f;
-    if (tid < RG) *reinterpret_cast<float4*>(smem + tid * kPlaneStride + kChunk * 16) = make_float4(0, 0, 0, 0);
+    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     Oct<D> pre[UPT][4];
     float  preg[VEC ? 1 : UPT][VEC ? 1 : 4][VEC ? 1 : 8];
@@ -109,13 +117,13 @@ __global__ __launch_bounds__(kThreadsA) void k_compress_gq(const typename D::ele
     auto fetch = [&](int c) {
 #pragma unroll
         for (int u = 0; u < UPT; ++u) {
-            const int unit = tid + u * kThreadsA;
+            const int unit = tid + u * kThreadsGQ;
             const int plane = unit / (kChunk / 8), oct = unit % (kChunk / 8);
             const int64_t col0 = (int64_t)c * kChunk + (int64_t)oct * 8;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int64_t row = i0 + plane * 4 + t;
-                const bool ok = (UNITS % kThreadsA == 0 || unit < UNITS) && row < m && col0 < n;
+                const bool ok = row < m && col0 < n;
                 if constexpr (VEC) {
                     pre[u][t] = ok ? oct_load<D>(G + row * (int64_t)n + col0) : oct_zero<D>();
                 } else {
@@ -131,8 +139,7 @@ __global__ __launch_bounds__(kThreadsA) void k_compress_gq(const typename D::ele
     auto stage = [&]() {
 #pragma unroll
         for (int u = 0; u < UPT; ++u) {
-            const int unit = tid + u * kThreadsA;
-            if (UNITS % kThreadsA != 0 && unit >= UNITS) continue;
+            const int unit = tid + u * kThreadsGQ;
             const int plane = unit / (kChunk / 8), oct = unit % (kChunk / 8);
             float f[4][8];
 #pragma unroll
@@ -146,73 +153,85 @@ __global__ __launch_bounds__(kThreadsA) void k_compress_gq(const typename D::ele
             uint8_t* base = smem + plane * kPlaneStride + oct * 16;
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                *reinterpret_cast<float4*>(base + q * (kChunk / 8) * 16) = make_float4(f[0][q], f[1][q], f[2][q], f[3][q]);
+                *reinterpret_cast<f32x4*>(base + q * (kChunk / 8) * 16) = f32x4{f[0][q], f[1][q], f[2][q], f[3][q]};
         }
     };
 
-    fetch(0);
-    for (int c = 0; c < nchunks; ++c) {
-        __syncthreads();               // everyone is done reading the previous chunk (and Tl is zeroed)
-        stage();
-        __syncthreads();
-        if (c + 1 < nchunks) fetch(c + 1);
+    float acc[kMaxSlots][kPlanes][4];
+#pragma unroll
+    for (int s = 0; s < kMaxSlots; ++s)
+#pragma unroll
+        for (int g = 0; g < kPlanes; ++g) acc[s][g][0] = acc[s][g][1] = acc[s][g][2] = acc[s][g][3] = 0.0f;
 
-        const int first = chunks[c].first_round, nr = chunks[c].nrounds;
-        for (int k = 0;; ++k) {
-            // rounds are sorted by length; deal them to the waves in serpentine order
-            const int rho = (k & 1) ? k * kWavesA + (kWavesA - 1 - wave) : k * kWavesA + wave;
-            if (rho >= nr) break;
-            const RoundInfo ri = rounds[first + rho];
-            const uint32_t b = cols[(size_t)(first + rho) * kWave + lane];
-            const uint2* ep = qent + ri.ent_offset + lane;
-            float acc[RG][4];
+    uint2 cur[kSegBatch], nxt[kSegBatch];
 #pragma unroll
-            for (int g = 0; g < RG; ++g) acc[g][0] = acc[g][1] = acc[g][2] = acc[g][3] = 0.0f;
-            auto consume = [&](const uint2 en) {
-                const float v = __uint_as_float(en.y);
+    for (int q = 0; q < kSegBatch; ++q) cur[q] = rp[(size_t)q * kWave];
+    if (!LSP_ABL_NOSTAGE) fetch(0);
+
+    for (int c = 0; c < nchunks; ++c) {
+        __syncthreads();                     // everyone is done reading the previous chunk
+        if (!LSP_ABL_NOSTAGE) stage();
+        __syncthreads();
+        if (c + 1 < nchunks && !LSP_ABL_NOSTAGE) fetch(c + 1);
 #pragma unroll
-                for (int g = 0; g < RG; ++g) {
-                    const f32x4 x = *reinterpret_cast<const f32x4*>(smem + en.x + g * kPlaneStride);
-                    acc[g][0] = fmaf(v, x.x, acc[g][0]);
-                    acc[g][1] = fmaf(v, x.y, acc[g][1]);
-                    acc[g][2] = fmaf(v, x.z, acc[g][2]);
-                    acc[g][3] = fmaf(v, x.w, acc[g][3]);
-                }
-            };
-            int e = 0;
-            for (; e + kBatch <= ri.len; e += kBatch) {      // kBatch entry loads in flight at once
-                uint2 en[kBatch];
+        for (int s = 0; s < kMaxSlots; ++s) {
+            if (s < nslots) {
+                const int nb = (int)(seg[(c * nslots + s) * kWavesGQ + wave] / kSegBatch);
+                for (int b = 0; b < nb; ++b) {
 #pragma unroll
-                for (int q = 0; q < kBatch; ++q) en[q] = ep[(size_t)(e + q) * kWave];
+                    for (int q = 0; q < kSegBatch; ++q) nxt[q] = LSP_ABL_NOSTREAM ? cur[q] : rp[(size_t)(kSegBatch + q) * kWave];   // one batch ahead
+                    if (!LSP_ABL_NOCONSUME)
 #pragma unroll
-                for (int q = 0; q < kBatch; ++q) consume(en[q]);
-            }
-            for (; e < ri.len; ++e) consume(ep[(size_t)e * kWave]);
-            if (b != kNoColumn) {
-                const uint32_t bb = b & 0x7FFFu;
-                if (b & kSharedColumn) {
-                    // this column's list was cut into pieces that other lanes add to as well
+                    for (int q = 0; q < kSegBatch; ++q) {
+                        const float v = __uint_as_float(cur[q].y);
 #pragma unroll
-                    for (int g = 0; g < RG; ++g)
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) atomicAdd(&Tl[(g * r + bb) * 4 + t], acc[g][t]);
-                } else {
-                    // the whole (chunk, column) list belongs to this lane: plain read-modify-write
-                    f32x4* Tl4 = reinterpret_cast<f32x4*>(Tl);
-#pragma unroll
-                    for (int g = 0; g < RG; ++g) {
-                        f32x4 x = Tl4[g * r + bb];
-                        x.x += acc[g][0]; x.y += acc[g][1]; x.z += acc[g][2]; x.w += acc[g][3];
-                        Tl4[g * r + bb] = x;
+                        for (int g = 0; g < kPlanes; ++g) {
+                            const f32x4 x = *reinterpret_cast<const f32x4*>(smem + cur[q].x + g * kPlaneStride);
+                            acc[s][g][0] = fmaf(v, x.x, acc[s][g][0]);
+                            acc[s][g][1] = fmaf(v, x.y, acc[s][g][1]);
+                            acc[s][g][2] = fmaf(v, x.z, acc[s][g][2]);
+                            acc[s][g][3] = fmaf(v, x.w, acc[s][g][3]);
+                        }
                     }
+#pragma unroll
+                    for (int q = 0; q < kSegBatch; ++q) cur[q] = nxt[q];
+                    rp += (size_t)kSegBatch * kWave;
+                }
+            }
+        }
+    }
+
+    if (LSP_ABL_NOTWRITE) { if (acc[0][0][0] == 123.0f) T[tid] = acc[1][1][1] + acc[2][2][2] + acc[3][3][3]; return; }
+    // T tile through LDS: owners of a shared column add, all others store
+    __syncthreads();
+    float* Tl = reinterpret_cast<float*>(smem);
+    for (int k = tid; k < R * r; k += kThreadsGQ) Tl[k] = 0.0f;
+    __syncthreads();
+    const uint16_t* vcol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol);
+#pragma unroll
+    for (int s = 0; s < kMaxSlots; ++s) {
+        if (s < nslots) {
+            const uint32_t col = vcol[s * kThreadsGQ + tid];
+            if (col != kNoColumn) {
+                const uint32_t bb = col & 0x7FFFu;
+                if (col & kSharedColumn) {
+#pragma unroll
+                    for (int g = 0; g < kPlanes; ++g)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) atomicAdd(&Tl[(g * 4 + t) * r + bb], acc[s][g][t]);
+                } else {
+#pragma unroll
+                    for (int g = 0; g < kPlanes; ++g)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) Tl[(g * 4 + t) * r + bb] = acc[s][g][t];
                 }
             }
         }
     }
     __syncthreads();
-    for (int k = tid; k < R * r; k += kThreadsA) {
-        const int t = k / r, b = k - t * r;                  // T tile is [plane][b][4 rows] in LDS
-        if (i0 + t < m) T[(i0 + t) * (int64_t)r + b] = Tl[((t >> 2) * r + b) * 4 + (t & 3)];
+    for (int k = tid; k < R * r; k += kThreadsGQ) {
+        const int t = k / r;
+        if (i0 + t < m) T[(i0 + t) * (int64_t)r + (k - t * r)] = Tl[k];
     }
 }
 
@@ -322,34 +341,26 @@ __global__ __launch_bounds__(256) void k_raw_pt(const float* __restrict__ T, con
 }
 
 // ----------------------------------------------------------------------------------------------
-template <typename D, int RG>
+template <typename D>
 static hipError_t launch_gq(const void* G, const uint8_t* plan, float* T, float* S, int64_t m, int64_t n, int32_t r, hipStream_t st) {
-    const size_t lds = (size_t)RG * kPlaneStride + (size_t)RG * 4 * r * sizeof(float);
-    const unsigned grid = (unsigned)((m + RG * 4 - 1) / (RG * 4));
+    const size_t lds = (size_t)kPlanes * kPlaneStride;       // >= 64 r bytes for every supported r
+    const unsigned grid = (unsigned)((m + kPlanes * 4 - 1) / (kPlanes * 4));
     const bool vec = (n % 8) == 0;
-    auto kern = vec ? k_compress_gq<D, RG, true> : k_compress_gq<D, RG, false>;
+    auto kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsA), lds, st,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsGQ), lds, st,
                        reinterpret_cast<const typename D::elem*>(G), plan, T, S, (int)m, (int)n, (int)r);
     return hipGetLastError();
-}
-
-template <typename D>
-static hipError_t launch_gq_rg(const void* G, const uint8_t* plan, float* T, float* S, int64_t m, int64_t n, int32_t r, hipStream_t st) {
-    int rg = (r <= 1024 && (m + 15) / 16 >= 3 * 256) ? 4 : 2;
-    if (const char* e = getenv("LSP_DEV_RGC")) rg = (atoi(e) == 4 && r <= 1024) ? 4 : 2;
-    if (rg == 4) return launch_gq<D, 4>(G, plan, T, S, m, n, r, st);
-    return launch_gq<D, 2>(G, plan, T, S, m, n, r, st);
 }
 
 hipError_t launch_compress_planned(const void* G, const uint8_t* plan, int64_t m, int64_t n, int32_t r, int32_t d,
                                    float* S, lsp_dtype dtype, float* T, hipStream_t st) {
     hipError_t e;
     switch (dtype) {
-        case LSP_F32:  e = launch_gq_rg<F32>(G, plan, T, S, m, n, r, st); break;
-        case LSP_F16:  e = launch_gq_rg<F16>(G, plan, T, S, m, n, r, st); break;
-        default:       e = launch_gq_rg<BF16>(G, plan, T, S, m, n, r, st); break;
+        case LSP_F32:  e = launch_gq<F32>(G, plan, T, S, m, n, r, st); break;
+        case LSP_F16:  e = launch_gq<F16>(G, plan, T, S, m, n, r, st); break;
+        default:       e = launch_gq<BF16>(G, plan, T, S, m, n, r, st); break;
     }
     if (e != hipSuccess) return e;
     const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);

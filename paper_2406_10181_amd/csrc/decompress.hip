@@ -148,7 +148,7 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
 #pragma unroll
         for (int t = 0; t < R; ++t) {
             const int64_t i = i0 + t < m ? i0 + t : m - 1;         // rows past m: any valid row, never stored
-            p.wv[t] = *reinterpret_cast<const Vec<D, CPT>*>(W + i * (int64_t)n + j0);
+            p.wv[t] = stream_load(reinterpret_cast<const Vec<D, CPT>*>(W + i * (int64_t)n + j0));
         }
     };
     auto idx_of = [](const Pass& p, int e) -> uint32_t {
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
                     vec_widen<D, CPT>(cur.wv[g * 4 + t], w);
 #pragma unroll
                     for (int c = 0; c < CPT; ++c) w[c] -= acc[t][c];
-                    *reinterpret_cast<Vec<D, CPT>*>(W + i * (int64_t)n + j0) = vec_narrow<D, CPT>(w);
+                    stream_store(reinterpret_cast<Vec<D, CPT>*>(W + i * (int64_t)n + j0), vec_narrow<D, CPT>(w));
                 }
             }
         }

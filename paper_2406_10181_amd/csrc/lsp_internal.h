@@ -12,12 +12,16 @@ namespace lsp {
 // ------------------------------------------------------------------------------------------
 // Tiling constants of the compress kernels (the plan layout depends on them).
 // ------------------------------------------------------------------------------------------
-constexpr int kChunk      = 1024;  // columns of G staged in LDS at a time
+constexpr int kChunk      = 2048;  // columns of G staged in LDS at a time
 constexpr int kWave       = 64;    // gfx950 wavefront
-constexpr int kListMax    = 64;    // a (chunk, column) list longer than this is cut into pieces
+constexpr int kThreadsGQ  = 512;   // threads of the T = G Q kernel: one lane per (virtual) column of T
+constexpr int kWavesGQ    = kThreadsGQ / kWave;
+constexpr int kMaxSlots   = 4;     // a lane owns at most this many virtual columns
+constexpr int kSegBatch   = 8;     // segment lengths are multiples of this many rows
+constexpr int kStreamSlack = 2 * kSegBatch;   // readable padding rows after the last segment
 constexpr int kRowPiece   = 128;   // a row list of P^T longer than this is cut into pieces
-constexpr uint32_t kNoColumn = 0xFFFFu;      // lane has no piece in this round
-constexpr uint32_t kSharedColumn = 0x8000u;  // flag on a piece's column: the list was cut, several lanes add to it
+constexpr uint32_t kNoColumn = 0xFFFFu;      // virtual column slot without a column
+constexpr uint32_t kSharedColumn = 0x8000u;  // flag: the column is owned by several lanes
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -31,42 +35,55 @@ __host__ __device__ static inline uint32_t chunk_col_offset(uint32_t j) {
 // ------------------------------------------------------------------------------------------
 // Plan: column-sorted projector copies, laid out for the compress kernels.
 // All offsets are bytes from the start of the plan buffer and multiples of 16.
+//
+// Q part.  Every column b of T = G Q is owned by one lane of the 512-thread workgroup, for all
+// chunks, so the lane can keep its partial sums in registers.  A column whose list of (column j of
+// G, value) pairs is longer than list_cap inside some chunk gets several owners ("virtual
+// columns"), each taking an equal share of the list in every chunk; the owners' sums are added at
+// the end.  Virtual column v sits in slot v / 512, lane v % 512.  For each (chunk, slot, wave) the
+// 64 lists are padded to a common length (a multiple of kSegBatch) with pairs that point at an
+// always-zero LDS unit, and stored lane-interleaved: one row = 64 x (LDS offset, value bits).
+// The rows of one wave are contiguous over all chunks and slots (chunk-major), so a wave reads
+// one linear stream.
 // ------------------------------------------------------------------------------------------
 struct PlanHeader {            // first 256 bytes of the plan buffer
     uint32_t magic;            // kPlanMagic
     int32_t  m, n, r, d;
     int32_t  nchunks;          // ceil(n / kChunk)
-    int32_t  q_total_rounds;   // rounds over all chunks
+    int32_t  nslots;           // virtual columns per lane (1 .. kMaxSlots)
+    int32_t  nvcols;           // virtual columns in use
+    int32_t  q_total_rows;     // rows of all wave streams, slack included
     int32_t  p_nitems;         // pieces of rows of P^T
     int32_t  p_any_split;      // 1 if some row of P^T was cut (S must start at zero)
-    uint32_t pad[7];
+    int32_t  list_cap;         // longest list a lane walks in one chunk
+    uint32_t q_stream_row[kWavesGQ];   // first row of each wave's stream
+    uint32_t pad[4];
     // section offsets
-    uint64_t off_q_chunk;      // ChunkInfo[nchunks]
-    uint64_t off_q_round;      // RoundInfo[q_total_rounds]
-    uint64_t off_q_cols;       // uint16[q_total_rounds][64]   column b of each lane's piece
-    uint64_t off_q_ent;        // uint2[slots]                  (LDS offset, value bits)
+    uint64_t off_q_seg;        // uint32[nchunks][nslots][kWavesGQ]  rows of each segment
+    uint64_t off_q_vcol;       // uint16[nslots * 512]               column b (| kSharedColumn) or kNoColumn
+    uint64_t off_q_rows;       // uint2[q_total_rows][64]
     uint64_t off_p_item;       // RowItem[p_nitems]
-    uint64_t off_p_ent;        // uint2[m*d]                    (row i, value bits)
+    uint64_t off_p_ent;        // uint2[m*d]                         (row i, value bits)
     uint64_t total_bytes;
-    uint64_t pad2[9];
+    uint64_t pad2[6];
 };
 static_assert(sizeof(PlanHeader) == 192, "PlanHeader layout");
-constexpr uint32_t kPlanMagic = 0x4C535031u;   // "LSP1"
+constexpr uint32_t kPlanMagic = 0x4C535034u;   // "LSP4"
 constexpr size_t   kPlanHeaderBytes = 256;
 
-struct ChunkInfo { int32_t first_round; int32_t nrounds; };
-struct RoundInfo { uint32_t ent_offset; int32_t len; };         // ent_offset in entries
 struct RowItem   { int32_t a; int32_t start; int32_t len; int32_t atomic; };
 
 // Upper bounds (depend on shapes only) used to size the plan buffer.
-size_t plan_max_rounds(int64_t n, int32_t r, int32_t d);
-size_t plan_max_slots(int64_t n, int32_t r, int32_t d);
+int    plan_list_cap(int32_t r, int32_t d);
+size_t plan_max_rows(int64_t n, int32_t r, int32_t d);
 size_t plan_max_items(int64_t m, int32_t r, int32_t d);
 size_t plan_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
 
 // Host-side builder: fills `host_plan` (plan_bytes() bytes) from host copies of the ELL arrays.
-void build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
-                     int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* host_plan);
+// Returns LSP_OK, or LSP_ERR_SKEW when the columns of Q are so unevenly used that more than
+// kMaxSlots * 512 virtual columns would be needed.
+int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                    int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* host_plan);
 
 // ------------------------------------------------------------------------------------------
 // Kernel launchers (each returns hipSuccess or the launch error).
@@ -90,6 +107,26 @@ struct F16 { using elem = uint16_t; static constexpr int size = 2; };
 struct BF16{ using elem = uint16_t; static constexpr int size = 2; };
 
 #if defined(__HIPCC__)
+// Streaming accesses to the big matrices (each byte of G and W is touched once per call): marked
+// non-temporal so that they do not evict the small, heavily re-read operands (S, the projector
+// arrays, the plan) from the XCD's L2.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <typename V> __device__ __forceinline__ V stream_load(const V* p) {
+    static_assert(sizeof(V) == 4 || sizeof(V) == 8 || sizeof(V) == 16, "4, 8 or 16 bytes");
+    V out;
+    if constexpr (sizeof(V) == 4) { uint32_t t = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p)); __builtin_memcpy(&out, &t, 4); }
+    else if constexpr (sizeof(V) == 8) { u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p)); __builtin_memcpy(&out, &t, 8); }
+    else { u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); __builtin_memcpy(&out, &t, 16); }
+    return out;
+}
+template <typename V> __device__ __forceinline__ void stream_store(V* p, const V& v) {
+    static_assert(sizeof(V) == 4 || sizeof(V) == 8 || sizeof(V) == 16, "4, 8 or 16 bytes");
+    if constexpr (sizeof(V) == 4) { uint32_t t; __builtin_memcpy(&t, &v, 4); __builtin_nontemporal_store(t, reinterpret_cast<uint32_t*>(p)); }
+    else if constexpr (sizeof(V) == 8) { u32x2 t; __builtin_memcpy(&t, &v, 8); __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p)); }
+    else { u32x4 t; __builtin_memcpy(&t, &v, 16); __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p)); }
+}
+
 template <typename D> __device__ __forceinline__ float widen(typename D::elem x);
 template <> __device__ __forceinline__ float widen<F32>(float x) { return x; }
 template <> __device__ __forceinline__ float widen<F16>(uint16_t x) {

@@ -13,18 +13,17 @@
 
 namespace lsp {
 
-size_t plan_max_rounds(int64_t n, int32_t r, int32_t d) {
-    const int64_t nchunks = (n + kChunk - 1) / kChunk;
-    const int64_t items_per_chunk = (int64_t)r + ((int64_t)kChunk * d + kListMax - 1) / kListMax + 1;
-    return (size_t)(nchunks * ((items_per_chunk + kWave - 1) / kWave + 1));
+// Longest list one lane may have to walk in one chunk: twice the mean list of a uniformly used
+// column (so uniformly drawn projectors are never split), at least 16.
+int plan_list_cap(int32_t r, int32_t d) {
+    const int64_t mean = ((int64_t)kChunk * d + r - 1) / r;
+    return (int)std::max<int64_t>(16, 2 * mean + 8);
 }
 
-size_t plan_max_slots(int64_t n, int32_t r, int32_t d) {
-    (void)r;
+size_t plan_max_rows(int64_t n, int32_t r, int32_t d) {
     const int64_t nchunks = (n + kChunk - 1) / kChunk;
-    // Pieces are sorted by length inside a chunk, so the padded size of all rounds after the first
-    // is bounded by the entries themselves; the first round adds at most 64 * kListMax.
-    return (size_t)(n * d + nchunks * (int64_t)kWave * (kListMax + 1));
+    const int64_t seg = align_up((size_t)plan_list_cap(r, d), kSegBatch);
+    return (size_t)(nchunks * kMaxSlots * kWavesGQ * seg + kWavesGQ * kStreamSlack);
 }
 
 size_t plan_max_items(int64_t m, int32_t r, int32_t d) {
@@ -32,19 +31,16 @@ size_t plan_max_items(int64_t m, int32_t r, int32_t d) {
 }
 
 namespace {
-struct Layout {
-    size_t off_q_chunk, off_q_round, off_q_cols, off_q_ent, off_p_item, off_p_ent, total;
-};
+struct Layout { size_t off_q_seg, off_q_vcol, off_q_rows, off_p_item, off_p_ent, total; };
 Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
     Layout L;
     const size_t nchunks = (size_t)((n + kChunk - 1) / kChunk);
     size_t o = kPlanHeaderBytes;
-    L.off_q_chunk = o; o = align_up(o + nchunks * sizeof(ChunkInfo), 256);
-    L.off_q_round = o; o = align_up(o + plan_max_rounds(n, r, d) * sizeof(RoundInfo), 256);
-    L.off_q_cols  = o; o = align_up(o + plan_max_rounds(n, r, d) * kWave * sizeof(uint16_t), 256);
-    L.off_q_ent   = o; o = align_up(o + plan_max_slots(n, r, d) * sizeof(uint2), 256);
-    L.off_p_item  = o; o = align_up(o + plan_max_items(m, r, d) * sizeof(RowItem), 256);
-    L.off_p_ent   = o; o = align_up(o + (size_t)(m * d) * sizeof(uint2), 256);
+    L.off_q_seg  = o; o = align_up(o + nchunks * kMaxSlots * kWavesGQ * sizeof(uint32_t), 256);
+    L.off_q_vcol = o; o = align_up(o + (size_t)kMaxSlots * kThreadsGQ * sizeof(uint16_t), 256);
+    L.off_q_rows = o; o = align_up(o + plan_max_rows(n, r, d) * kWave * sizeof(uint2), 256);
+    L.off_p_item = o; o = align_up(o + plan_max_items(m, r, d) * sizeof(RowItem), 256);
+    L.off_p_ent  = o; o = align_up(o + (size_t)(m * d) * sizeof(uint2), 256);
     L.total = o;
     return L;
 }
@@ -53,81 +49,106 @@ uint32_t float_bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
 
 size_t plan_bytes(int64_t m, int64_t n, int32_t r, int32_t d) { return plan_layout(m, n, r, d).total; }
 
-void build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
-                     int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* out) {
+int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                    int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* out) {
     const Layout L = plan_layout(m, n, r, d);
-    std::memset(out, 0, L.total);
-    PlanHeader* H = reinterpret_cast<PlanHeader*>(out);
     const int nchunks = (int)((n + kChunk - 1) / kChunk);
-    H->magic = kPlanMagic; H->m = (int32_t)m; H->n = (int32_t)n; H->r = r; H->d = d; H->nchunks = nchunks;
-    H->off_q_chunk = L.off_q_chunk; H->off_q_round = L.off_q_round; H->off_q_cols = L.off_q_cols;
-    H->off_q_ent = L.off_q_ent; H->off_p_item = L.off_p_item; H->off_p_ent = L.off_p_ent;
-    H->total_bytes = L.total;
+    const int cap = plan_list_cap(r, d);
 
-    ChunkInfo* chunks = reinterpret_cast<ChunkInfo*>(out + L.off_q_chunk);
-    RoundInfo* rounds = reinterpret_cast<RoundInfo*>(out + L.off_q_round);
-    uint16_t*  cols   = reinterpret_cast<uint16_t*>(out + L.off_q_cols);
-    uint2*     qent   = reinterpret_cast<uint2*>(out + L.off_q_ent);
-
-    // ---- Q: per chunk of kChunk columns of G, the entries grouped by subspace column b ----------
-    struct Piece { int32_t b; int32_t start; int32_t len; int32_t shared; };
-    std::vector<int32_t> cnt((size_t)r + 1), cur((size_t)r);
-    std::vector<uint2> sorted;                 // entries of one chunk ordered by (b, j, k)
-    std::vector<Piece> pieces;
-    int total_rounds = 0;
-    size_t slot = 0;
-    const uint32_t pad_offset = (uint32_t)kChunk * 16u;     // the always-zero unit of each plane
+    // ---- Q: lists of (column j of G, value) per (chunk, subspace column b) -----------------------
+    // start[c][b] .. start[c][b+1] index into sorted[c], ordered by (b, j, k)
+    std::vector<std::vector<int32_t>> start((size_t)nchunks, std::vector<int32_t>((size_t)r + 1, 0));
+    std::vector<std::vector<uint2>> sorted((size_t)nchunks);
+    std::vector<int32_t> cur((size_t)r);
     for (int c = 0; c < nchunks; ++c) {
         const int64_t j0 = (int64_t)c * kChunk, j1 = std::min<int64_t>(n, j0 + kChunk);
-        std::fill(cnt.begin(), cnt.end(), 0);
+        auto& st = start[(size_t)c];
         for (int64_t j = j0; j < j1; ++j)
-            for (int k = 0; k < d; ++k) cnt[(size_t)Q_idx[j * d + k] + 1]++;
-        for (int b = 0; b < r; ++b) cnt[(size_t)b + 1] += cnt[(size_t)b];
-        sorted.assign((size_t)cnt[(size_t)r], uint2{0, 0});
-        for (int b = 0; b < r; ++b) cur[(size_t)b] = cnt[(size_t)b];
+            for (int k = 0; k < d; ++k) st[(size_t)Q_idx[j * d + k] + 1]++;
+        for (int b = 0; b < r; ++b) st[(size_t)b + 1] += st[(size_t)b];
+        sorted[(size_t)c].assign((size_t)st[(size_t)r], uint2{0, 0});
+        for (int b = 0; b < r; ++b) cur[(size_t)b] = st[(size_t)b];
         for (int64_t j = j0; j < j1; ++j)
             for (int k = 0; k < d; ++k) {
                 const int32_t b = Q_idx[j * d + k];
-                sorted[(size_t)cur[(size_t)b]++] = uint2{chunk_col_offset((uint32_t)(j - j0)),
-                                                         float_bits(Q_val[j * d + k])};
+                sorted[(size_t)c][(size_t)cur[(size_t)b]++] =
+                    uint2{chunk_col_offset((uint32_t)(j - j0)), float_bits(Q_val[j * d + k])};
             }
-        pieces.clear();
-        for (int b = 0; b < r; ++b)
-            for (int32_t s = cnt[(size_t)b]; s < cnt[(size_t)b + 1]; s += kListMax)
-                pieces.push_back(Piece{b, s, std::min<int32_t>(kListMax, cnt[(size_t)b + 1] - s),
-                                       cnt[(size_t)b + 1] - cnt[(size_t)b] > kListMax});
-        std::stable_sort(pieces.begin(), pieces.end(),
-                         [](const Piece& x, const Piece& y) { return x.len > y.len; });
-        chunks[c].first_round = total_rounds;
-        const int nr = (int)((pieces.size() + kWave - 1) / kWave);
-        chunks[c].nrounds = nr;
-        for (int rho = 0; rho < nr; ++rho) {
-            const size_t p0 = (size_t)rho * kWave;
-            const int len = pieces[p0].len;
-            RoundInfo& ri = rounds[total_rounds];
-            ri.ent_offset = (uint32_t)slot; ri.len = len;
-            for (int lane = 0; lane < kWave; ++lane) {
-                const bool have = p0 + (size_t)lane < pieces.size();
-                cols[(size_t)total_rounds * kWave + (size_t)lane] =
-                    have ? (uint16_t)(pieces[p0 + (size_t)lane].b | (pieces[p0 + (size_t)lane].shared ? kSharedColumn : 0u))
-                         : (uint16_t)kNoColumn;
-                for (int e = 0; e < len; ++e) {
-                    uint2 v{pad_offset, 0u};
-                    if (have && e < pieces[p0 + (size_t)lane].len)
-                        v = sorted[(size_t)pieces[p0 + (size_t)lane].start + (size_t)e];
-                    qent[slot + (size_t)e * kWave + (size_t)lane] = v;
-                }
-            }
-            slot += (size_t)len * kWave;
-            ++total_rounds;
-        }
     }
-    H->q_total_rounds = total_rounds;
+    // owners per column: enough that no owner's share exceeds `cap` in any chunk
+    std::vector<int32_t> owners((size_t)r, 1), first_v((size_t)r + 1, 0);
+    for (int b = 0; b < r; ++b) {
+        int32_t longest = 0;
+        for (int c = 0; c < nchunks; ++c)
+            longest = std::max(longest, start[(size_t)c][(size_t)b + 1] - start[(size_t)c][(size_t)b]);
+        owners[(size_t)b] = std::max(1, (longest + cap - 1) / cap);
+        first_v[(size_t)b + 1] = first_v[(size_t)b] + owners[(size_t)b];
+    }
+    const int V = first_v[(size_t)r];
+    if (V > kMaxSlots * kThreadsGQ) return LSP_ERR_SKEW;
+    const int nslots = std::max(1, (V + kThreadsGQ - 1) / kThreadsGQ);
+
+    std::memset(out, 0, L.total);
+    PlanHeader* H = reinterpret_cast<PlanHeader*>(out);
+    H->magic = kPlanMagic; H->m = (int32_t)m; H->n = (int32_t)n; H->r = r; H->d = d; H->nchunks = nchunks;
+    H->nslots = nslots; H->nvcols = V; H->list_cap = cap;
+    H->off_q_seg = L.off_q_seg; H->off_q_vcol = L.off_q_vcol; H->off_q_rows = L.off_q_rows;
+    H->off_p_item = L.off_p_item; H->off_p_ent = L.off_p_ent; H->total_bytes = L.total;
+
+    uint32_t* seg  = reinterpret_cast<uint32_t*>(out + L.off_q_seg);
+    uint16_t* vcol = reinterpret_cast<uint16_t*>(out + L.off_q_vcol);
+    uint2*    rows = reinterpret_cast<uint2*>(out + L.off_q_rows);
+    std::vector<int32_t> v_col((size_t)nslots * kThreadsGQ, -1), v_own((size_t)nslots * kThreadsGQ, 0);
+    for (int b = 0; b < r; ++b)
+        for (int o = 0; o < owners[(size_t)b]; ++o) {
+            const int v = first_v[(size_t)b] + o;
+            v_col[(size_t)v] = b; v_own[(size_t)v] = o;
+        }
+    for (size_t v = 0; v < v_col.size(); ++v)
+        vcol[v] = v_col[v] < 0 ? (uint16_t)kNoColumn
+                               : (uint16_t)((uint32_t)v_col[v] | (owners[(size_t)v_col[v]] > 1 ? kSharedColumn : 0u));
+
+    // share of owner o of column b in chunk c: [lo, hi) inside the chunk's sorted list of b
+    auto share = [&](int c, int b, int o, int32_t& lo, int32_t& hi) {
+        const int32_t s0 = start[(size_t)c][(size_t)b], len = start[(size_t)c][(size_t)b + 1] - s0;
+        const int k = owners[(size_t)b];
+        lo = s0 + (int32_t)((int64_t)len * o / k);
+        hi = s0 + (int32_t)((int64_t)len * (o + 1) / k);
+    };
+    const uint2 pad_pair{(uint32_t)kChunk * 16u, 0u};       // the always-zero unit of each plane
+    size_t row = 0;
+    for (int w = 0; w < kWavesGQ; ++w) {
+        H->q_stream_row[w] = (uint32_t)row;
+        for (int c = 0; c < nchunks; ++c)
+            for (int s = 0; s < nslots; ++s) {
+                int32_t longest = 0;
+                for (int lane = 0; lane < kWave; ++lane) {
+                    const size_t v = (size_t)s * kThreadsGQ + (size_t)w * kWave + (size_t)lane;
+                    if (v_col[v] < 0) continue;
+                    int32_t lo, hi; share(c, v_col[v], v_own[v], lo, hi);
+                    longest = std::max(longest, hi - lo);
+                }
+                const int32_t len = (int32_t)align_up((size_t)longest, kSegBatch);
+                seg[((size_t)c * nslots + (size_t)s) * kWavesGQ + (size_t)w] = (uint32_t)len;
+                for (int lane = 0; lane < kWave; ++lane) {
+                    const size_t v = (size_t)s * kThreadsGQ + (size_t)w * kWave + (size_t)lane;
+                    int32_t lo = 0, hi = 0;
+                    if (v_col[v] >= 0) share(c, v_col[v], v_own[v], lo, hi);
+                    for (int32_t e = 0; e < len; ++e)
+                        rows[(row + (size_t)e) * kWave + (size_t)lane] =
+                            e < hi - lo ? sorted[(size_t)c][(size_t)(lo + e)] : pad_pair;
+                }
+                row += (size_t)len;
+            }
+        for (int e = 0; e < kStreamSlack; ++e, ++row)
+            for (int lane = 0; lane < kWave; ++lane) rows[row * kWave + (size_t)lane] = pad_pair;
+    }
+    H->q_total_rows = (int32_t)row;
 
     // ---- P^T: for each subspace row a, the (row of G, value) pairs, cut into pieces -------------
     RowItem* items = reinterpret_cast<RowItem*>(out + L.off_p_item);
     uint2*   pent  = reinterpret_cast<uint2*>(out + L.off_p_ent);
-    std::fill(cnt.begin(), cnt.end(), 0);
+    std::vector<int32_t> cnt((size_t)r + 1, 0);
     for (int64_t i = 0; i < m; ++i)
         for (int k = 0; k < d; ++k) cnt[(size_t)P_idx[i * d + k] + 1]++;
     for (int a = 0; a < r; ++a) cnt[(size_t)a + 1] += cnt[(size_t)a];
@@ -148,6 +169,7 @@ void build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_
     }
     H->p_nitems = nitems;
     H->p_any_split = any_split;
+    return LSP_OK;
 }
 
 }  // namespace lsp

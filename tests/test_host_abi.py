@@ -12,7 +12,7 @@ import lsp_synth as syn
 import paper_2406_10181_amd as L
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-CHUNK = 1024
+CHUNK = 2048
 PAD_OFFSET = CHUNK * 16
 
 
@@ -74,51 +74,63 @@ def _build_host_plan(pb):
 
 
 def _replay_plan(buf, pb):
-    """What the plan means: T = G Qhat from the Q section, then S = Phat^T T from the P section."""
-    hdr32 = buf[:64].view(np.int32)
-    assert hdr32[0] == 0x4C535031
-    m, n, r, d, nchunks, total_rounds, nitems, any_split = [int(x) for x in hdr32[1:9]]
+    """What the plan means: T = G Qhat from the Q part, then S = Phat^T T from the P part.
+    The Q streams are walked exactly as the kernel walks them: wave by wave, chunk-major, slot by
+    slot, each segment's length from the table; lane l of wave w in slot s owns virtual column
+    s*512 + w*64 + l."""
+    hdr32 = buf[:48].view(np.int32)
+    assert hdr32[0] == 0x4C535034
+    m, n, r, d, nchunks, nslots, nvcols, total_rows, nitems, any_split, cap = [int(x) for x in hdr32[1:12]]
     assert (m, n, r, d) == (pb.m, pb.n, pb.r, pb.d) and nchunks == -(-n // CHUNK)
-    offs = buf[64:64 + 56].view(np.uint64)
-    o_chunk, o_round, o_cols, o_ent, o_item, o_pent, total = [int(x) for x in offs]
-    assert total == buf.size and all(o % 16 == 0 for o in (o_chunk, o_round, o_cols, o_ent, o_item, o_pent))
-    chunks = buf[o_chunk:o_chunk + nchunks * 8].view(np.int32).reshape(nchunks, 2)
-    rounds = buf[o_round:o_round + total_rounds * 8].view(np.uint32).reshape(total_rounds, 2)
-    cols = buf[o_cols:o_cols + total_rounds * 64 * 2].view(np.uint16).reshape(total_rounds, 64)
+    assert 1 <= nslots <= 4 and nvcols <= nslots * 512
+    stream_row = [int(x) for x in buf[48:80].view(np.uint32)]
+    o_seg, o_vcol, o_rows, o_item, o_pent, total = [int(x) for x in buf[96:144].view(np.uint64)]
+    assert total == buf.size and all(o % 16 == 0 for o in (o_seg, o_vcol, o_rows, o_item, o_pent))
+    assert o_rows + total_rows * 64 * 8 <= o_item
+    seg = buf[o_seg:o_seg + nchunks * nslots * 8 * 4].view(np.uint32).reshape(nchunks, nslots, 8)
+    vcol = buf[o_vcol:o_vcol + nslots * 512 * 2].view(np.uint16).reshape(nslots, 8, 64)
+    rows = buf[o_rows:o_rows + total_rows * 64 * 8].view(np.uint32).reshape(total_rows, 64, 2)
     G = syn.storage_to_f64(pb.G, pb.dtype)
     T = np.zeros((m, r))
-    used_slots = 0
     nent = 0
-    for c in range(nchunks):
-        first, nr = int(chunks[c, 0]), int(chunks[c, 1])
-        prev_len = None
-        for rho in range(first, first + nr):
-            eo, ln = int(rounds[rho, 0]), int(rounds[rho, 1])
-            assert eo == used_slots, "rounds must be packed back to back"
-            assert prev_len is None or ln <= prev_len, "rounds of a chunk are sorted by length"
-            prev_len = ln
-            assert 1 <= ln <= 64
-            ent = buf[o_ent + eo * 8:o_ent + (eo + ln * 64) * 8].view(np.uint32).reshape(ln, 64, 2)
-            used_slots += ln * 64
+    owners = {}
+    for s in range(nslots):
+        for w in range(8):
             for lane in range(64):
-                b = int(cols[rho, lane])
-                if b != 0xFFFF:
-                    b &= 0x7FFF                       # bit 15 marks a piece of a cut list
-                for e in range(ln):
-                    off, vb = int(ent[e, lane, 0]), ent[e, lane, 1:2]
-                    v = float(vb.view(np.float32)[0])
-                    assert off % 16 == 0 and off <= PAD_OFFSET, "LDS offset inside one plane"
-                    if off == PAD_OFFSET:
-                        assert v == 0.0
-                        continue
-                    assert b != 0xFFFF and b < r
-                    j = c * CHUNK + _decode_col(off)
-                    assert j < n
-                    T[:, b] += v * G[:, j]
-                    nent += 1
+                c = int(vcol[s, w, lane])
+                if c != 0xFFFF:
+                    assert (c & 0x7FFF) < r
+                    owners.setdefault(c & 0x7FFF, []).append(bool(c & 0x8000))
+    assert sorted(owners) == list(range(r)), "every column has an owner"
+    assert all(all(f) == (len(f) > 1) and (all(f) or not any(f)) for f in owners.values()), \
+        "a column is flagged shared exactly when it has several owners"
+    for w in range(8):
+        p = stream_row[w]
+        for c in range(nchunks):
+            for s in range(nslots):
+                ln = int(seg[c, s, w])
+                assert ln % 8 == 0 and ln <= -(-cap // 8) * 8
+                ent = rows[p:p + ln]
+                for lane in range(64):
+                    col = int(vcol[s, w, lane])
+                    for e in range(ln):
+                        off = int(ent[e, lane, 0])
+                        v = float(ent[e, lane, 1:2].view(np.float32)[0])
+                        assert off % 16 == 0 and off <= PAD_OFFSET, "LDS offset inside one plane"
+                        if off == PAD_OFFSET:
+                            assert v == 0.0
+                            continue
+                        assert col != 0xFFFF
+                        j = c * CHUNK + _decode_col(off)
+                        assert j < n
+                        T[:, col & 0x7FFF] += v * G[:, j]
+                        nent += 1
+                p += ln
+        # the kernel prefetches one batch past the end of the stream: 16 harmless rows follow
+        assert p + 16 <= total_rows and (w == 7 or p + 16 <= stream_row[w + 1])
+        tail = rows[p:p + 16]
+        assert np.all(tail[:, :, 0] == PAD_OFFSET) and np.all(tail[:, :, 1] == 0)
     assert nent == n * d
-    max_slots_bytes = o_item - o_ent
-    assert used_slots * 8 <= max_slots_bytes
     items = buf[o_item:o_item + nitems * 16].view(np.int32).reshape(nitems, 4)
     pent = buf[o_pent:o_pent + m * d * 8].view(np.uint32).reshape(m * d, 2)
     S = np.zeros((r, r))
@@ -148,10 +160,11 @@ def _dense(idx, val, r):
 
 
 @pytest.mark.parametrize("m,n,r,d,dist", [
-    (48, 2100, 16, 2, "distinct"),      # three chunks, ragged last chunk
-    (40, 1024, 64, 4, "uniform"),
-    (33, 1500, 8, 8, "zipf"),           # lists longer than 64 -> cut into pieces; rows of P^T > 128
+    (48, 4200, 16, 2, "distinct"),      # three chunks, ragged last chunk
+    (40, 2048, 64, 4, "uniform"),
+    (33, 2500, 96, 8, "zipf"),          # hot columns get several owners; rows of P^T > 128 entries
     (2000, 64, 4, 2, "uniform"),        # every row of P^T has ~1000 entries -> pieces + atomic flag
+    (24, 3000, 600, 2, "uniform"),      # more columns than lanes: two slots
     (10, 7, 3, 1, "uniform"),
 ])
 def test_plan_replay_matches_dense_definition(m, n, r, d, dist):
@@ -176,3 +189,18 @@ def test_plan_build_host_rejects_bad_index_and_small_buffer():
     assert L.lsp_plan_build_host(pb.P_idx, pb.P_val, bad, pb.Q_val, 16, 16, 8, 2, buf, nbytes, check=False) == -6
     assert L.lsp_plan_build_host(pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, 16, 16, 8, 2, buf, nbytes - 1,
                                  check=False) == -4
+
+
+def test_plan_build_reports_unplannable_skew():
+    # r = 2048 uniformly used columns already fill all 4 x 512 lanes; one hot column on top of
+    # that needs extra owners that do not exist -> LSP_ERR_SKEW (the caller falls back to lsp_compress)
+    m, n, r, d = 8, 2048, 2048, 16
+    rng = np.random.default_rng(3)
+    P_idx, P_val = syn.ell_projector(m, r, d, rng)
+    Q_idx, Q_val = syn.ell_projector(n, r, d, rng, "distinct")
+    nbytes = L.lsp_plan_bytes(m, n, r, d)
+    buf = np.zeros(nbytes, dtype=np.uint8)
+    assert L.lsp_plan_build_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, buf, nbytes, check=False) == 0
+    Q_idx[:, 0] = 0                      # every row of Q also hits column 0
+    assert L.lsp_plan_build_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, buf, nbytes, check=False) == -8
+    assert "unevenly" in L.lsp_strerror(-8)
