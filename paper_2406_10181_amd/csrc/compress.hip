@@ -16,13 +16,6 @@ namespace lsp {
 
 constexpr int kPlaneStride = kChunk * 16 + 16;   // bytes; last 16 bytes of a plane stay zero
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-#ifndef LSP_ABL
-#define LSP_ABL 0          // development ablations, compile-time only; 0 in every shipped build
-#endif
-#define LSP_ABL_NOCONSUME ((LSP_ABL & 1) != 0)
-#define LSP_ABL_NOSTREAM  ((LSP_ABL & 2) != 0)
-#define LSP_ABL_NOSTAGE   ((LSP_ABL & 4) != 0)
-#define LSP_ABL_NOTWRITE  ((LSP_ABL & 8) != 0)
 
 // ----------------------------------------------------------------------------------------------
 // eight consecutive elements of one row, as loaded
@@ -77,44 +70,24 @@ template <> __device__ __forceinline__ void oct_widen<F16>(const Oct<F16>& o, fl
 // (virtual) column of T; the lane keeps its 16 partial sums per owned column in registers for the
 // whole kernel, so there is no flush and no atomic in the main loop.
 // LDS: 4 planes of kPlaneStride bytes (staged chunk of G, fp32); at the very end the same memory
-// holds the T tile [16][r] for a coalesced write.
-// Each wave reads one linear stream of plan rows (64 x (LDS offset, value)), always one batch of 8
-// rows ahead in registers; segment lengths come from a small table (scalar loads).
+// holds the T tile [16][r] when partial sums of several owners have to meet.
+// Each wave reads one linear stream of plan rows (64 x (LDS offset, value)); segment lengths come
+// from a small table (scalar loads).
 // VEC: rows are 8-element aligned (n % 8 == 0), vector loads; otherwise element-wise loads.
 constexpr int kPlanes = 4;
+constexpr int kRowsGQ = 4 * kPlanes;
+constexpr int kBatchLoads = kSegBatch / 2;                    // 128-bit loads per batch of plan rows
+
+// Global -> register -> LDS staging of one chunk of G, shared by both variants of kernel A.
 template <typename D, bool VEC>
-__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::elem* __restrict__ G,
-                                                           const uint8_t* __restrict__ plan,
-                                                           float* __restrict__ T, float* __restrict__ S,
-                                                           int m, int n, int r) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    constexpr int R = 4 * kPlanes;
-    constexpr int UNITS = kPlanes * (kChunk / 8);             // (plane, column octet) units per chunk
-    constexpr int UPT = UNITS / kThreadsGQ;                   // units per thread
+struct ChunkStager {
+    static constexpr int UNITS = kPlanes * (kChunk / 8);      // (plane, column octet) units per chunk
+    static constexpr int UPT = UNITS / kThreadsGQ;            // units per thread
     static_assert(UNITS % kThreadsGQ == 0, "staging assumes whole units per thread");
-
-    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
-    if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t i0 = (int64_t)blockIdx.x * R;
-    const int nchunks = H->nchunks;
-    const int nslots = H->nslots;
-    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg);
-    const uint2* rp = reinterpret_cast<const uint2*>(plan + H->off_q_rows) + (size_t)H->q_stream_row[wave] * kWave + lane;
-
-    // S must start at zero only when some row of P^T was cut into pieces (kernel B then adds).
-    if (H->p_any_split) {
-        const int64_t total = (int64_t)r * r;
-        for (int64_t k = (int64_t)blockIdx.x * kThreadsGQ + tid; k < total; k += (int64_t)gridDim.x * kThreadsGQ) S[k] = 0.0f;
-    }
-    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
-    Oct<D> pre[UPT][4];
+    Oct<D> pre[VEC ? UPT : 1][VEC ? 4 : 1];
     float  preg[VEC ? 1 : UPT][VEC ? 1 : 4][VEC ? 1 : 8];
 
-    auto fetch = [&](int c) {
+    __device__ __forceinline__ void fetch(const typename D::elem* __restrict__ G, int64_t i0, int m, int n, int c, int tid) {
 #pragma unroll
         for (int u = 0; u < UPT; ++u) {
             const int unit = tid + u * kThreadsGQ;
@@ -125,7 +98,11 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::el
                 const int64_t row = i0 + plane * 4 + t;
                 const bool ok = row < m && col0 < n;
                 if constexpr (VEC) {
-                    pre[u][t] = ok ? oct_load<D>(G + row * (int64_t)n + col0) : oct_zero<D>();
+                    // always load (from a clamped, valid address) and select afterwards: a branch
+                    // around the load would make the wave wait for each load in turn
+                    const int64_t rowc = row < m ? row : (int64_t)m - 1, colc = col0 < n ? col0 : 0;
+                    pre[u][t] = oct_load<D>(G + rowc * (int64_t)n + colc);
+                    if (!ok) pre[u][t] = oct_zero<D>();
                 } else {
                     if (ok) oct_gather<D>(G + row * (int64_t)n, col0, n, preg[u][t]);
                     else {
@@ -135,8 +112,8 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::el
                 }
             }
         }
-    };
-    auto stage = [&]() {
+    }
+    __device__ __forceinline__ void stage(uint8_t* smem, int tid) const {
 #pragma unroll
         for (int u = 0; u < UPT; ++u) {
             const int unit = tid + u * kThreadsGQ;
@@ -155,61 +132,60 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::el
             for (int q = 0; q < 8; ++q)
                 *reinterpret_cast<f32x4*>(base + q * (kChunk / 8) * 16) = f32x4{f[0][q], f[1][q], f[2][q], f[3][q]};
         }
-    };
+    }
+};
 
-    float acc[kMaxSlots][kPlanes][4];
+// the staged values of the two columns named by e, for all 16 rows
+__device__ __forceinline__ void gather_pair(const uint8_t* smem, const u32x4 e, f32x4 (&x)[2][kPlanes]) {
 #pragma unroll
-    for (int s = 0; s < kMaxSlots; ++s)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int g = 0; g < kPlanes; ++g) acc[s][g][0] = acc[s][g][1] = acc[s][g][2] = acc[s][g][3] = 0.0f;
-
-    uint2 cur[kSegBatch], nxt[kSegBatch];
+        for (int g = 0; g < kPlanes; ++g)
+            x[h][g] = *reinterpret_cast<const f32x4*>(smem + (h ? e.z : e.x) + g * kPlaneStride);
+}
+__device__ __forceinline__ void fma_pair(const u32x4 e, const f32x4 (&x)[2][kPlanes], float (&acc)[kPlanes][4]) {
 #pragma unroll
-    for (int q = 0; q < kSegBatch; ++q) cur[q] = rp[(size_t)q * kWave];
-    if (!LSP_ABL_NOSTAGE) fetch(0);
-
-    for (int c = 0; c < nchunks; ++c) {
-        __syncthreads();                     // everyone is done reading the previous chunk
-        if (!LSP_ABL_NOSTAGE) stage();
-        __syncthreads();
-        if (c + 1 < nchunks && !LSP_ABL_NOSTAGE) fetch(c + 1);
+    for (int h = 0; h < 2; ++h) {
+        const float v = __uint_as_float(h ? e.w : e.y);
 #pragma unroll
-        for (int s = 0; s < kMaxSlots; ++s) {
-            if (s < nslots) {
-                const int nb = (int)(seg[(c * nslots + s) * kWavesGQ + wave] / kSegBatch);
-                for (int b = 0; b < nb; ++b) {
-#pragma unroll
-                    for (int q = 0; q < kSegBatch; ++q) nxt[q] = LSP_ABL_NOSTREAM ? cur[q] : rp[(size_t)(kSegBatch + q) * kWave];   // one batch ahead
-                    if (!LSP_ABL_NOCONSUME)
-#pragma unroll
-                    for (int q = 0; q < kSegBatch; ++q) {
-                        const float v = __uint_as_float(cur[q].y);
-#pragma unroll
-                        for (int g = 0; g < kPlanes; ++g) {
-                            const f32x4 x = *reinterpret_cast<const f32x4*>(smem + cur[q].x + g * kPlaneStride);
-                            acc[s][g][0] = fmaf(v, x.x, acc[s][g][0]);
-                            acc[s][g][1] = fmaf(v, x.y, acc[s][g][1]);
-                            acc[s][g][2] = fmaf(v, x.z, acc[s][g][2]);
-                            acc[s][g][3] = fmaf(v, x.w, acc[s][g][3]);
-                        }
-                    }
-#pragma unroll
-                    for (int q = 0; q < kSegBatch; ++q) cur[q] = nxt[q];
-                    rp += (size_t)kSegBatch * kWave;
-                }
-            }
+        for (int g = 0; g < kPlanes; ++g) {
+            acc[g][0] = fmaf(v, x[h][g].x, acc[g][0]);
+            acc[g][1] = fmaf(v, x[h][g].y, acc[g][1]);
+            acc[g][2] = fmaf(v, x[h][g].z, acc[g][2]);
+            acc[g][3] = fmaf(v, x[h][g].w, acc[g][3]);
         }
     }
+}
 
-    if (LSP_ABL_NOTWRITE) { if (acc[0][0][0] == 123.0f) T[tid] = acc[1][1][1] + acc[2][2][2] + acc[3][3][3]; return; }
-    // T tile through LDS: owners of a shared column add, all others store
+// acc[g][t] += value * (staged G)[row 4g+t][column] for the two (offset, value) pairs of e
+__device__ __forceinline__ void consume_pair(const uint8_t* smem, const u32x4 e, float (&acc)[kPlanes][4]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t off = h ? e.z : e.x;
+        const float v = __uint_as_float(h ? e.w : e.y);
+#pragma unroll
+        for (int g = 0; g < kPlanes; ++g) {
+            const f32x4 x = *reinterpret_cast<const f32x4*>(smem + off + g * kPlaneStride);
+            acc[g][0] = fmaf(v, x.x, acc[g][0]);
+            acc[g][1] = fmaf(v, x.y, acc[g][1]);
+            acc[g][2] = fmaf(v, x.z, acc[g][2]);
+            acc[g][3] = fmaf(v, x.w, acc[g][3]);
+        }
+    }
+}
+
+// Partial sums of several owners of one column meet in an LDS tile [16][r]; the tile then goes
+// out with coalesced stores.  Called by all threads of the workgroup.
+template <int NS>
+__device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* plan, const PlanHeader* H, float* __restrict__ T,
+                                                  const float (&acc)[NS][kPlanes][4], int nslots, int64_t i0, int m, int r, int tid) {
     __syncthreads();
     float* Tl = reinterpret_cast<float*>(smem);
-    for (int k = tid; k < R * r; k += kThreadsGQ) Tl[k] = 0.0f;
+    for (int k = tid; k < kRowsGQ * r; k += kThreadsGQ) Tl[k] = 0.0f;
     __syncthreads();
     const uint16_t* vcol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol);
 #pragma unroll
-    for (int s = 0; s < kMaxSlots; ++s) {
+    for (int s = 0; s < NS; ++s) {
         if (s < nslots) {
             const uint32_t col = vcol[s * kThreadsGQ + tid];
             if (col != kNoColumn) {
@@ -229,10 +205,169 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::el
         }
     }
     __syncthreads();
-    for (int k = tid; k < R * r; k += kThreadsGQ) {
+    for (int k = tid; k < kRowsGQ * r; k += kThreadsGQ) {
         const int t = k / r;
         if (i0 + t < m) T[(i0 + t) * (int64_t)r + (k - t * r)] = Tl[k];
     }
+}
+
+// Common case: every lane owns at most one column (nslots == 1).  The wave's plan stream is
+// consumed as one flat sequence of batches, kPrefetch batches deep in registers, running ahead
+// across chunk boundaries; a chunk boundary only costs the two barriers around the staging.
+template <typename D, bool VEC>
+__device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+                                            const uint8_t* __restrict__ plan, const PlanHeader* H,
+                                            float* __restrict__ T, int64_t i0, int m, int n, int r,
+                                            int tid, int lane, int wave) {
+    const int nchunks = H->nchunks;
+    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg) + wave;
+    const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+    const uint32_t mycol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol)[tid];
+
+    // Ring of kPrefetch batches with fixed register slots: slot k is consumed, then refilled with
+    // the batch kPrefetch further on.  (Shifting the ring instead would make every iteration wait
+    // for the newest load.)  Slot 0 holds the oldest batch at the start of each chunk; a chunk
+    // whose batch count is not a multiple of kPrefetch leaves the ring rotated, which is undone
+    // once per chunk, behind the staging barrier, when the loads in flight have long landed.
+    u32x4 ring[kPrefetch][kBatchLoads];
+#pragma unroll
+    for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
+    rp += (size_t)kPrefetch * kBatchLoads * kWave;
+
+    float acc[1][kPlanes][4];
+#pragma unroll
+    for (int g = 0; g < kPlanes; ++g) acc[0][g][0] = acc[0][g][1] = acc[0][g][2] = acc[0][g][3] = 0.0f;
+
+    auto step = [&](u32x4 (&slot)[kBatchLoads]) {
+        // gathers of pair q+1 are issued before the multiply-adds of pair q, not further ahead, so
+        // that at most two pairs of gathered data (64 registers) are live
+        f32x4 x[2][2][kPlanes];
+        gather_pair(smem, slot[0], x[0]);
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) {
+            if (q + 1 < kBatchLoads) gather_pair(smem, slot[q + 1], x[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            fma_pair(slot[q], x[q & 1], acc[0]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) slot[q] = rp[(size_t)q * kWave];
+        rp += (size_t)kBatchLoads * kWave;
+    };
+
+    int rot = 0;                                                      // slots the ring is rotated by
+    for (int c = 0; c < nchunks; ++c) {
+        __syncthreads();                                              // everyone is done reading the previous chunk
+        stg.stage(smem, tid);
+        __syncthreads();
+        if (c + 1 < nchunks) stg.fetch(G, i0, m, n, c + 1, tid);
+        if (rot != 0) {
+            u32x4 t[kPrefetch][kBatchLoads];
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) {
+                    t[k][q] = ring[(k + 1) % kPrefetch][q];
+                    if (rot == 2) t[k][q] = ring[(k + 2) % kPrefetch][q];
+                    if (rot == 3) t[k][q] = ring[(k + 3) % kPrefetch][q];
+                }
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = t[k][q];
+        }
+        static_assert(kPrefetch == 4, "the rotation above is written for four slots");
+        const int nb = (int)(seg[c * kWavesGQ] / kSegBatch);
+        for (int g = nb / kPrefetch; g > 0; --g) {
+            step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
+        }
+        rot = nb % kPrefetch;
+        if (rot > 0) step(ring[0]);
+        if (rot > 1) step(ring[1]);
+        if (rot > 2) step(ring[2]);
+    }
+    if (H->q_any_shared) {
+        write_tile_shared<1>(smem, plan, H, T, acc, 1, i0, m, r, tid);
+    } else if (mycol != kNoColumn) {
+#pragma unroll
+        for (int g = 0; g < kPlanes; ++g)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (i0 + g * 4 + t < m) T[(i0 + g * 4 + t) * (int64_t)r + mycol] = acc[0][g][t];
+    }
+}
+
+// General case (up to kMaxSlots columns per lane): slot by slot inside each chunk, one batch ahead.
+template <typename D, bool VEC>
+__device__ __attribute__((noinline)) void gq_any_slots(ChunkStager<D, VEC> stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+                                             const uint8_t* __restrict__ plan, const PlanHeader* H,
+                                             float* __restrict__ T, int64_t i0, int m, int n, int r,
+                                             int tid, int lane, int wave) {
+    const int nchunks = H->nchunks;
+    const int nslots = H->nslots;
+    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg);
+    const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+
+    float acc[kMaxSlots][kPlanes][4];
+#pragma unroll
+    for (int s = 0; s < kMaxSlots; ++s)
+#pragma unroll
+        for (int g = 0; g < kPlanes; ++g) acc[s][g][0] = acc[s][g][1] = acc[s][g][2] = acc[s][g][3] = 0.0f;
+
+    u32x4 cur[kBatchLoads], nxt[kBatchLoads];
+#pragma unroll
+    for (int q = 0; q < kBatchLoads; ++q) cur[q] = rp[(size_t)q * kWave];
+
+    for (int c = 0; c < nchunks; ++c) {
+        __syncthreads();                     // everyone is done reading the previous chunk
+        stg.stage(smem, tid);
+        __syncthreads();
+        if (c + 1 < nchunks) stg.fetch(G, i0, m, n, c + 1, tid);
+#pragma unroll
+        for (int s = 0; s < kMaxSlots; ++s) {
+            if (s < nslots) {
+                const int nb = (int)(seg[(c * nslots + s) * kWavesGQ + wave] / kSegBatch);
+                for (int b = 0; b < nb; ++b) {
+#pragma unroll
+                    for (int q = 0; q < kBatchLoads; ++q) nxt[q] = rp[(size_t)(kBatchLoads + q) * kWave];   // one batch ahead
+#pragma unroll
+                    for (int q = 0; q < kBatchLoads; ++q) consume_pair(smem, cur[q], acc[s]);
+#pragma unroll
+                    for (int q = 0; q < kBatchLoads; ++q) cur[q] = nxt[q];
+                    rp += (size_t)kBatchLoads * kWave;
+                }
+            }
+        }
+    }
+    write_tile_shared<kMaxSlots>(smem, plan, H, T, acc, nslots, i0, m, r, tid);
+}
+
+template <typename D, bool VEC>
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::elem* __restrict__ G,
+                                                           const uint8_t* __restrict__ plan,
+                                                           float* __restrict__ T, float* __restrict__ S,
+                                                           int m, int n, int r) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t i0 = (int64_t)blockIdx.x * kRowsGQ;
+
+    ChunkStager<D, VEC> stg;
+    stg.fetch(G, i0, m, n, 0, tid);                                   // depends on nothing but the arguments
+
+    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
+    // S must start at zero only when some row of P^T was cut into pieces (kernel B then adds).
+    if (H->p_any_split) {
+        const int64_t total = (int64_t)r * r;
+        for (int64_t k = (int64_t)blockIdx.x * kThreadsGQ + tid; k < total; k += (int64_t)gridDim.x * kThreadsGQ) S[k] = 0.0f;
+    }
+    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (H->nslots == 1) gq_one_slot<D, VEC>(stg, smem, G, plan, H, T, i0, m, n, r, tid, lane, wave);
+    else                gq_any_slots<D, VEC>(stg, smem, G, plan, H, T, i0, m, n, r, tid, lane, wave);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -344,7 +479,7 @@ __global__ __launch_bounds__(256) void k_raw_pt(const float* __restrict__ T, con
 template <typename D>
 static hipError_t launch_gq(const void* G, const uint8_t* plan, float* T, float* S, int64_t m, int64_t n, int32_t r, hipStream_t st) {
     const size_t lds = (size_t)kPlanes * kPlaneStride;       // >= 64 r bytes for every supported r
-    const unsigned grid = (unsigned)((m + kPlanes * 4 - 1) / (kPlanes * 4));
+    const unsigned grid = (unsigned)((m + kRowsGQ - 1) / kRowsGQ);
     const bool vec = (n % 8) == 0;
     auto kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

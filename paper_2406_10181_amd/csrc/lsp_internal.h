@@ -18,7 +18,8 @@ constexpr int kThreadsGQ  = 512;   // threads of the T = G Q kernel: one lane pe
 constexpr int kWavesGQ    = kThreadsGQ / kWave;
 constexpr int kMaxSlots   = 4;     // a lane owns at most this many virtual columns
 constexpr int kSegBatch   = 8;     // segment lengths are multiples of this many rows
-constexpr int kStreamSlack = 2 * kSegBatch;   // readable padding rows after the last segment
+constexpr int kPrefetch   = 4;     // batches of plan rows a wave holds in registers (one consumed, the rest in flight)
+constexpr int kStreamSlack = kPrefetch * kSegBatch;   // readable padding rows after the last segment
 constexpr int kRowPiece   = 128;   // a row list of P^T longer than this is cut into pieces
 constexpr uint32_t kNoColumn = 0xFFFFu;      // virtual column slot without a column
 constexpr uint32_t kSharedColumn = 0x8000u;  // flag: the column is owned by several lanes
@@ -42,7 +43,8 @@ __host__ __device__ static inline uint32_t chunk_col_offset(uint32_t j) {
 // columns"), each taking an equal share of the list in every chunk; the owners' sums are added at
 // the end.  Virtual column v sits in slot v / 512, lane v % 512.  For each (chunk, slot, wave) the
 // 64 lists are padded to a common length (a multiple of kSegBatch) with pairs that point at an
-// always-zero LDS unit, and stored lane-interleaved: one row = 64 x (LDS offset, value bits).
+// always-zero LDS unit, and stored lane-interleaved two rows at a time: rows 2p and 2p+1 form
+// 64 x (LDS offset, value bits, LDS offset, value bits), one 128-bit load per lane.
 // The rows of one wave are contiguous over all chunks and slots (chunk-major), so a wave reads
 // one linear stream.
 // ------------------------------------------------------------------------------------------
@@ -57,18 +59,19 @@ struct PlanHeader {            // first 256 bytes of the plan buffer
     int32_t  p_any_split;      // 1 if some row of P^T was cut (S must start at zero)
     int32_t  list_cap;         // longest list a lane walks in one chunk
     uint32_t q_stream_row[kWavesGQ];   // first row of each wave's stream
-    uint32_t pad[4];
+    int32_t  q_any_shared;     // 1 if some column of T has several owners
+    uint32_t pad[3];
     // section offsets
     uint64_t off_q_seg;        // uint32[nchunks][nslots][kWavesGQ]  rows of each segment
     uint64_t off_q_vcol;       // uint16[nslots * 512]               column b (| kSharedColumn) or kNoColumn
-    uint64_t off_q_rows;       // uint2[q_total_rows][64]
+    uint64_t off_q_rows;       // uint4[q_total_rows / 2][64]
     uint64_t off_p_item;       // RowItem[p_nitems]
     uint64_t off_p_ent;        // uint2[m*d]                         (row i, value bits)
     uint64_t total_bytes;
     uint64_t pad2[6];
 };
 static_assert(sizeof(PlanHeader) == 192, "PlanHeader layout");
-constexpr uint32_t kPlanMagic = 0x4C535034u;   // "LSP4"
+constexpr uint32_t kPlanMagic = 0x4C535035u;   // "LSP5"
 constexpr size_t   kPlanHeaderBytes = 256;
 
 struct RowItem   { int32_t a; int32_t start; int32_t len; int32_t atomic; };

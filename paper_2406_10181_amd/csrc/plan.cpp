@@ -116,6 +116,11 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
         hi = s0 + (int32_t)((int64_t)len * (o + 1) / k);
     };
     const uint2 pad_pair{(uint32_t)kChunk * 16u, 0u};       // the always-zero unit of each plane
+    // rows 2p and 2p+1 are interleaved per lane (every segment has an even number of rows)
+    auto row_slot = [](size_t rw, int lane) { return ((rw >> 1) * kWave + (size_t)lane) * 2 + (rw & 1); };
+    int any_shared = 0;
+    for (int b = 0; b < r; ++b) any_shared |= owners[(size_t)b] > 1;
+    H->q_any_shared = any_shared;
     size_t row = 0;
     for (int w = 0; w < kWavesGQ; ++w) {
         H->q_stream_row[w] = (uint32_t)row;
@@ -135,13 +140,13 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
                     int32_t lo = 0, hi = 0;
                     if (v_col[v] >= 0) share(c, v_col[v], v_own[v], lo, hi);
                     for (int32_t e = 0; e < len; ++e)
-                        rows[(row + (size_t)e) * kWave + (size_t)lane] =
+                        rows[row_slot(row + (size_t)e, lane)] =
                             e < hi - lo ? sorted[(size_t)c][(size_t)(lo + e)] : pad_pair;
                 }
                 row += (size_t)len;
             }
         for (int e = 0; e < kStreamSlack; ++e, ++row)
-            for (int lane = 0; lane < kWave; ++lane) rows[row * kWave + (size_t)lane] = pad_pair;
+            for (int lane = 0; lane < kWave; ++lane) rows[row_slot(row, lane)] = pad_pair;
     }
     H->q_total_rows = (int32_t)row;
 

@@ -79,7 +79,7 @@ def _replay_plan(buf, pb):
     slot, each segment's length from the table; lane l of wave w in slot s owns virtual column
     s*512 + w*64 + l."""
     hdr32 = buf[:48].view(np.int32)
-    assert hdr32[0] == 0x4C535034
+    assert hdr32[0] == 0x4C535035
     m, n, r, d, nchunks, nslots, nvcols, total_rows, nitems, any_split, cap = [int(x) for x in hdr32[1:12]]
     assert (m, n, r, d) == (pb.m, pb.n, pb.r, pb.d) and nchunks == -(-n // CHUNK)
     assert 1 <= nslots <= 4 and nvcols <= nslots * 512
@@ -89,7 +89,11 @@ def _replay_plan(buf, pb):
     assert o_rows + total_rows * 64 * 8 <= o_item
     seg = buf[o_seg:o_seg + nchunks * nslots * 8 * 4].view(np.uint32).reshape(nchunks, nslots, 8)
     vcol = buf[o_vcol:o_vcol + nslots * 512 * 2].view(np.uint16).reshape(nslots, 8, 64)
-    rows = buf[o_rows:o_rows + total_rows * 64 * 8].view(np.uint32).reshape(total_rows, 64, 2)
+    # rows 2p and 2p+1 are interleaved per lane: [pair][lane][row parity][offset, value bits]
+    assert total_rows % 2 == 0 and all(x % 2 == 0 for x in stream_row)
+    rows = buf[o_rows:o_rows + total_rows * 64 * 8].view(np.uint32).reshape(total_rows // 2, 64, 2, 2)
+    rows = np.ascontiguousarray(rows.transpose(0, 2, 1, 3)).reshape(total_rows, 64, 2)
+    any_shared = int(buf[80:84].view(np.int32)[0])
     G = syn.storage_to_f64(pb.G, pb.dtype)
     T = np.zeros((m, r))
     nent = 0
@@ -104,6 +108,7 @@ def _replay_plan(buf, pb):
     assert sorted(owners) == list(range(r)), "every column has an owner"
     assert all(all(f) == (len(f) > 1) and (all(f) or not any(f)) for f in owners.values()), \
         "a column is flagged shared exactly when it has several owners"
+    assert any_shared == int(any(len(f) > 1 for f in owners.values()))
     for w in range(8):
         p = stream_row[w]
         for c in range(nchunks):
@@ -126,9 +131,9 @@ def _replay_plan(buf, pb):
                         T[:, col & 0x7FFF] += v * G[:, j]
                         nent += 1
                 p += ln
-        # the kernel prefetches one batch past the end of the stream: 16 harmless rows follow
-        assert p + 16 <= total_rows and (w == 7 or p + 16 <= stream_row[w + 1])
-        tail = rows[p:p + 16]
+        # the kernel prefetches four batches past the end of the stream: 32 harmless rows follow
+        assert p + 32 <= total_rows and (w == 7 or p + 32 <= stream_row[w + 1])
+        tail = rows[p:p + 32]
         assert np.all(tail[:, :, 0] == PAD_OFFSET) and np.all(tail[:, :, 1] == 0)
     assert nent == n * d
     items = buf[o_item:o_item + nitems * 16].view(np.int32).reshape(nitems, 4)
