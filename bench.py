@@ -3,9 +3,11 @@
 
 A step is one pass of the whole hot path over the 6.7B-style layer stack (BASELINE config 4):
 32 layers x {down 11008x4096, gate/up 4096x11008, o/v/k/q 4096x4096}, bf16, r = 512, d = 8,
-visited layer by layer in backward order on one stream; every matrix gets one
-lsp_compress_planned (S = P^T G Q) and one lsp_decompress_apply (W -= P S Q^T).  All inputs
-are resident in HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
+visited layer by layer in backward order; every matrix gets one lsp_compress_planned
+(S = P^T G Q) and one lsp_decompress_apply (W -= P S Q^T).  The seven matrices of a layer are
+independent and are dealt to --streams HIP streams (default priority), joined at the end of the
+step; the roofline leg times each kernel family alone on one stream.  All inputs are resident in
+HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
 
 Prints ONE JSON line: throughput in algorithmic GB/s (bytes the method must move, see
 the design doc) with a roofline object for the dominant kernel and the CPU oracle timed on a bounded
@@ -40,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=32, help="layers of the stack (32 = the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="HIP streams the matrices of a layer are dealt to (default priority; joined at step end)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path is single-GPU by construction (no collectives are built); run with --gpus 1",
@@ -83,24 +87,47 @@ def main():
             ws_bytes = max(ws_bytes, L.lsp_compress_planned_workspace_bytes(m, n, r, d))
             e["cb"], e["db"] = algorithmic_bytes(m, n, r, d, sz)
             mats.append(e)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    nstreams = max(1, args.streams)
+    lanes = [stream] + [torch.cuda.Stream(device=dev) for _ in range(nstreams - 1)]   # default priority
+    wss = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in lanes]       # one workspace per stream
+    fork = torch.cuda.Event()
+    joins = [torch.cuda.Event() for _ in lanes]
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
-    def compress_all(ms):
-        for e in ms:
-            L.lsp_compress_planned(e["G"], e["plan"], e["m"], e["n"], r, d, e["S"], code, ws, ws_bytes, stream)
+    def compress_all(ms, ns=1):
+        for k, e in enumerate(ms):
+            q = k % ns
+            L.lsp_compress_planned(e["G"], e["plan"], e["m"], e["n"], r, d, e["S"], code, wss[q], ws_bytes, lanes[q])
 
-    def decompress_all(ms):
-        for e in ms:
+    def decompress_all(ms, ns=1):
+        for k, e in enumerate(ms):
+            q = k % ns
             L.lsp_decompress_apply(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"],
-                                   e["m"], e["n"], r, d, code, stream)
+                                   e["m"], e["n"], r, d, code, lanes[q])
+
+    def forked(fn):
+        # side streams start after everything already queued on the main stream and are joined
+        # back into it, so events recorded on the main stream bracket all the work
+        if nstreams == 1:
+            return fn()
+        fork.record(stream)
+        for s in lanes[1:]:
+            s.wait_event(fork)
+        fn()
+        for s, ev in zip(lanes[1:], joins[1:]):
+            ev.record(s)
+            stream.wait_event(ev)
+
+    def step_body():
+        # layer by layer: the layer's compress calls, then its decompress-apply calls; a matrix
+        # stays on one stream, so its two calls are ordered
+        for k in range(0, len(mats), 7):
+            compress_all(mats[k:k + 7], nstreams)
+            decompress_all(mats[k:k + 7], nstreams)
 
     def step():
-        # layer by layer: the layer's compress calls, then its decompress-apply calls
-        for k in range(0, len(mats), 7):
-            compress_all(mats[k:k + 7])
-            decompress_all(mats[k:k + 7])
+        forked(step_body)
 
     def timed(fn, reps):
         torch.cuda.synchronize()
@@ -115,7 +142,8 @@ def main():
     for _ in range(args.warmup):
         step()
     ms_step = timed(step, args.steps)
-    # per-kernel passes (same buffers, still cold: 26 GB is swept between two visits of a buffer)
+    # per-kernel passes for the roofline: one stream, launches back to back, so the time per launch
+    # is the kernel's own duration (same buffers, still cold: 26 GB is swept between two visits)
     sub = max(3, min(args.steps, 10))
     ms_comp = timed(lambda: compress_all(mats), sub)
     ms_deco = timed(lambda: decompress_all(mats), sub)
@@ -141,8 +169,8 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg4: 6.7B-style stack, {args.layers} layers x 7 matrices, bf16 G/W, r=512, d=8, "
-                               "uniform projector columns, backward order on one stream",
-                   "storage": "bf16", "accumulate": "f32", "matrices": nlaunch,
+                               f"uniform projector columns, backward order, {nstreams} stream(s)",
+                   "storage": "bf16", "accumulate": "f32", "matrices": nlaunch, "streams": nstreams,
                    "algorithmic_GB_per_step": round((cbytes + dbytes) / 1e9, 3)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "per_layer_us": round(ms_step * 1e3 / args.layers, 2),

@@ -8,7 +8,6 @@
 //   B  S = P^T T   one workgroup per piece of a row of P^T; reads rows of T.
 // The path is bandwidth-bound (one pass over G); no matrix cores are involved because the
 // projectors are sparse (d entries per row, Def. 1) and the work is gather + fp32 FMA.
-#include <cstdlib>
 
 #include "lsp_internal.h"
 
@@ -295,7 +294,7 @@ __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* s
         for (int g = 0; g < kPlanes; ++g)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                if (i0 + g * 4 + t < m) T[(i0 + g * 4 + t) * (int64_t)r + mycol] = acc[0][g][t];
+                if (i0 + g * 4 + t < m) stream_store(&T[(i0 + g * 4 + t) * (int64_t)r + mycol], acc[0][g][t]);
     }
 }
 

@@ -6,8 +6,6 @@
 //            their rows of Q in registers, and for each 4-row plane gathers U with one 128-bit
 //            LDS read per pair; W is read, updated in fp32 and rounded once.
 // Bandwidth-bound (read + write of W); no matrix cores (sparse gather + fp32 FMA).
-#include <cstdlib>
-
 #include "lsp_internal.h"
 
 namespace lsp {
@@ -121,11 +119,11 @@ __device__ __forceinline__ void build_u_tile_fast(uint8_t* smem, int2* pent, con
 // folds into the immediate offset of the LDS read and a gather costs no address arithmetic.
 // All loads of a pass (the thread's rows of Q and its R x CPT patch of W) are issued before the
 // gathers start, so one pass costs one HBM round trip; many waves per CU overlap the passes.
-template <typename D, int RG, int DD, int PS, int NT, int CPT>
+template <typename D, int RG, int DD, int PS, int NT, int CPT, int kDepth>
 __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict__ W, const float* __restrict__ S,
                                                   const int32_t* __restrict__ P_idx, const float* __restrict__ P_val,
                                                   const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
-                                                  int m, int n, int r, int devmode) {
+                                                  int m, int n, int r) {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int R = 4 * RG;
     constexpr int NE = CPT * DD;                                    // entries owned by a thread in one pass
@@ -142,8 +140,8 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
         const f32x4* qvp = reinterpret_cast<const f32x4*>(Q_val + j0 * DD);
 #pragma unroll
         for (int k = 0; k < NE / 4; ++k) {
-            if (devmode & 4) { p.qi[k] = make_int4(k, k + 1, k + 2, k + 3); p.qv[k] = f32x4{1.f, 2.f, 3.f, 4.f}; }
-            else { p.qi[k] = qip[k]; p.qv[k] = qvp[k]; }
+            p.qi[k] = qip[k];
+            p.qv[k] = qvp[k];
         }
 #pragma unroll
         for (int t = 0; t < R; ++t) {
@@ -165,22 +163,13 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
     // without the rotation they would all ask the same few L2 channels for the same lines at once.
     const int64_t step = (int64_t)NT * CPT;
     const int npass = (int)((n + step - 1) / step);
-    const int rot = (devmode & 8) ? 0 : (int)((blockIdx.x / 8) % npass);
+    const int rot = (int)((blockIdx.x / 8) % npass);
     auto pass_col = [&](int p) -> int64_t {
         int q = p + rot;
         if (q >= npass) q -= npass;
         return (int64_t)q * step + (int64_t)threadIdx.x * CPT;
     };
-    Pass cur, nxt;
-    int64_t j0 = pass_col(0);
-    if (j0 < n) load_pass(j0, cur);                                 // in flight while the U tile is built
-    if (!(devmode & 2)) build_u_tile_fast<RG, DD, PS, NT>(smem, pent, S, P_idx, P_val, i0, m, r);
-    __syncthreads();
-
-    for (int p = 0; p < npass; ++p) {
-        const int64_t j1 = p + 1 < npass ? pass_col(p + 1) : n;
-        if (j1 < n) load_pass(j1, nxt);                             // next pass in flight during this one
-        if (j0 < n)
+    auto compute_pass = [&](const Pass& cur, int64_t j0) {
 #pragma unroll
         for (int g = 0; g < RG; ++g) {
             float acc[4][CPT];
@@ -188,7 +177,6 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int c = 0; c < CPT; ++c) acc[t][c] = 0.0f;
-            if (!(devmode & 1))
 #pragma unroll
             for (int c = 0; c < CPT; ++c)
 #pragma unroll
@@ -212,8 +200,33 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
                 }
             }
         }
-        cur = nxt;
-        j0 = j1;
+    };
+
+    // kDepth passes live in fixed register slots: one being computed, the others in flight.
+    // (Copying a slot to another would wait for its loads.)
+    Pass slot[kDepth];
+    auto load_if = [&](int p, Pass& s) {
+        if (p < npass) {
+            const int64_t j = pass_col(p);
+            if (j < n) load_pass(j, s);
+        }
+    };
+    auto compute_if = [&](int p, const Pass& s) {
+        if (p < npass) {
+            const int64_t j = pass_col(p);
+            if (j < n) compute_pass(s, j);
+        }
+    };
+#pragma unroll
+    for (int k = 0; k + 1 < kDepth; ++k) load_if(k, slot[k]);       // in flight while the U tile is built
+    build_u_tile_fast<RG, DD, PS, NT>(smem, pent, S, P_idx, P_val, i0, m, r);
+    __syncthreads();
+    for (int p = 0; p < npass; p += kDepth) {
+#pragma unroll
+        for (int k = 0; k < kDepth; ++k) {
+            load_if(p + k + kDepth - 1, slot[(k + kDepth - 1) % kDepth]);
+            compute_if(p + k, slot[k]);
+        }
     }
 }
 
@@ -256,7 +269,7 @@ __global__ __launch_bounds__(kThreadsD) void k_decompress_any(typename D::elem* 
     }
 }
 
-template <typename D, int RG, int PS, int NT, int CPT>
+template <typename D, int RG, int PS, int NT, int CPT, int DEPTH>
 static hipError_t launch_d(void* W, const float* S, const int32_t* P_idx, const float* P_val,
                            const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
                            hipStream_t st) {
@@ -266,12 +279,12 @@ static hipError_t launch_d(void* W, const float* S, const int32_t* P_idx, const 
     hipError_t e;
 #define LSP_LAUNCH_FAST(DDV)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT>;                                                          \
+        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, DEPTH>;                                                    \
         const size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                              \
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         if (e != hipSuccess) return e;                                                                         \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, reinterpret_cast<E*>(W), S, P_idx, P_val,      \
-                           Q_idx, Q_val, (int)m, (int)n, (int)r, getenv("LSP_DEV_MODE") ? atoi(getenv("LSP_DEV_MODE")) : 0); \
+                           Q_idx, Q_val, (int)m, (int)n, (int)r);                                              \
     } while (0)
     if (fast && d == 2) LSP_LAUNCH_FAST(2);
     else if (fast && d == 4) LSP_LAUNCH_FAST(4);
@@ -289,54 +302,32 @@ static hipError_t launch_d(void* W, const float* S, const int32_t* P_idx, const 
     return hipGetLastError();
 }
 
-// rows per workgroup: 16 (four planes) when that still leaves at least three workgroups per CU, else 8
-static int pick_planes(int64_t m, int32_t r) {
-    if (r > 1024) return 2;
-    if (const char* e = getenv("LSP_DEV_RGD")) return atoi(e) == 2 ? 2 : 4;
-    (void)m;
-    return 4;
-}
-
-template <typename D, int NT, int CPT>
-static hipError_t launch_d_rg(void* W, const float* S, const int32_t* P_idx, const float* P_val,
-                              const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
-                              hipStream_t st) {
-    const int rg = pick_planes(m, r);
-#define LSP_D_CASE(RGV, PSV) return launch_d<D, RGV, PSV, NT, CPT>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st)
-    if (rg == 4) {
-        if (r <= 256) LSP_D_CASE(4, 4096);
-        if (r <= 512) LSP_D_CASE(4, 8192);
-        LSP_D_CASE(4, 16384);
-    }
-    if (r <= 256) LSP_D_CASE(2, 4096);
-    if (r <= 512) LSP_D_CASE(2, 8192);
-    if (r <= 1024) LSP_D_CASE(2, 16384);
+// Rows per workgroup: 16 (four planes of U in LDS), 8 when the tile of U would not fit otherwise.
+// Passes held in registers: three when the grid is small (few workgroups per CU, so each has to
+// keep more bytes in flight itself), two otherwise.
+template <typename D>
+static hipError_t launch_d_shape(void* W, const float* S, const int32_t* P_idx, const float* P_val,
+                                 const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
+                                 hipStream_t st) {
+    constexpr int NT = 512, CPT = 2;
+    const bool deep = (m + 15) / 16 <= 512;
+#define LSP_D_CASE(RGV, PSV)                                                                                        \
+    return deep ? launch_d<D, RGV, PSV, NT, CPT, 3>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st)               \
+                : launch_d<D, RGV, PSV, NT, CPT, 2>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st)
+    if (r <= 256) LSP_D_CASE(4, 4096);
+    if (r <= 512) LSP_D_CASE(4, 8192);
+    if (r <= 1024) LSP_D_CASE(4, 16384);
     LSP_D_CASE(2, 32768);
 #undef LSP_D_CASE
-}
-
-template <typename D>
-static hipError_t launch_d_nt(void* W, const float* S, const int32_t* P_idx, const float* P_val,
-                              const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
-                              hipStream_t st) {
-    int nt = 512, cpt = 2;
-    if (const char* e = getenv("LSP_DEV_NTD")) nt = atoi(e);
-    if (const char* e = getenv("LSP_DEV_CPT")) cpt = atoi(e);
-#define LSP_D_ARGS W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st
-    if (cpt == 4) return launch_d_rg<D, 256, 4>(LSP_D_ARGS);
-    if (nt == 1024) return launch_d_rg<D, 1024, 2>(LSP_D_ARGS);
-    if (nt == 512) return launch_d_rg<D, 512, 2>(LSP_D_ARGS);
-    return launch_d_rg<D, 256, 2>(LSP_D_ARGS);
-#undef LSP_D_ARGS
 }
 
 hipError_t launch_decompress(void* W, const float* S, const int32_t* P_idx, const float* P_val,
                              const int32_t* Q_idx, const float* Q_val,
                              int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
     switch (dtype) {
-        case LSP_F32:  return launch_d_nt<F32>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-        case LSP_F16:  return launch_d_nt<F16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-        default:       return launch_d_nt<BF16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+        case LSP_F32:  return launch_d_shape<F32>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+        case LSP_F16:  return launch_d_shape<F16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+        default:       return launch_d_shape<BF16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
     }
 }
 
