@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=32, help="layers of the stack (32 = the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--grouped", type=int, default=1,
+                    help="1: one grouped call per layer and kernel family; 0: one call per matrix")
     ap.add_argument("--streams", type=int, default=4,
                     help="HIP streams the matrices of a layer are dealt to (default priority; joined at step end)")
     args = ap.parse_args()
@@ -106,6 +108,22 @@ def main():
             L.lsp_decompress_apply(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"],
                                    e["m"], e["n"], r, d, code, lanes[q])
 
+    # grouped mode: the seven matrices of a layer in one call (own S and workspace each); layers
+    # alternate over the streams
+    layers = [mats[k:k + 7] for k in range(0, len(mats), 7)]
+    gws = [[torch.empty(L.lsp_compress_planned_workspace_bytes(e["m"], e["n"], r, d), dtype=torch.uint8, device=dev)
+            for e in layers[0]] for _ in lanes]
+    citems = [L.compress_items([(e["G"], e["plan"], e["S"], gws[li % nstreams][k], gws[li % nstreams][k].numel(),
+                                 e["m"], e["n"]) for k, e in enumerate(ly)]) for li, ly in enumerate(layers)]
+    aitems = [L.apply_items([(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], e["m"], e["n"])
+                             for e in ly]) for ly in layers]
+
+    def step_grouped():
+        for li in range(len(layers)):
+            q = lanes[li % nstreams]
+            L.lsp_compress_planned_grouped(citems[li], 7, r, d, code, q)
+            L.lsp_decompress_apply_grouped(aitems[li], 7, r, d, code, q)
+
     def forked(fn):
         # side streams start after everything already queued on the main stream and are joined
         # back into it, so events recorded on the main stream bracket all the work
@@ -127,7 +145,7 @@ def main():
             decompress_all(mats[k:k + 7], nstreams)
 
     def step():
-        forked(step_body)
+        forked(step_grouped if args.grouped else step_body)
 
     def timed(fn, reps):
         torch.cuda.synchronize()
@@ -170,8 +188,9 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg4: 6.7B-style stack, {args.layers} layers x 7 matrices, bf16 G/W, r=512, d=8, "
-                               f"uniform projector columns, backward order, {nstreams} stream(s)",
-                   "storage": "bf16", "accumulate": "f32", "matrices": nlaunch, "streams": nstreams,
+                               f"uniform projector columns, backward order, {nstreams} stream(s), " +
+                               ("one grouped call per layer and kernel family" if args.grouped else "one call per matrix"),
+                   "storage": "bf16", "accumulate": "f32", "matrices": nlaunch, "streams": nstreams, "grouped": bool(args.grouped),
                    "algorithmic_GB_per_step": round((cbytes + dbytes) / 1e9, 3)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "per_layer_us": round(ms_step * 1e3 / args.layers, 2),

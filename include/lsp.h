@@ -58,6 +58,7 @@ typedef enum {
 
 #define LSP_MAX_R 2048       /* largest supported subspace size (the paper's largest setting) */
 #define LSP_MAX_D 64         /* largest supported number of entries per projector row */
+#define LSP_MAX_GROUP 16     /* most problems in one grouped call */
 
 /* ------------------------------------------------------------------------------------------
  * Compress:  S := P^T G Q.
@@ -142,6 +143,48 @@ int lsp_decompress_apply(void* W, const float* S,
                          const int32_t* Q_idx, const float* Q_val,
                          int64_t m, int64_t n, int32_t r, int32_t d,
                          lsp_dtype dtype, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Grouped calls: several independent matrices in one call.
+ * Alg. 3 walks the model layer by layer, and the weight matrices of one layer (their gradients
+ * are all there when the layer's backward pass ends) are independent problems with the same
+ * subspace size: a grouped call serves them with one launch per kernel, so that workgroups of
+ * different matrices fill the GPU together.  Results are those of the single calls, matrix by
+ * matrix, bit for bit.
+ *
+ *   items      HOST array of `count` descriptors (1 <= count <= LSP_MAX_GROUP); read during the
+ *              call only; every pointer inside is a device pointer with the meaning, layout and
+ *              alignment of the same-named argument of the single call
+ *   r, d, dtype  shared by all problems of the group; m and n are per problem
+ * Problems of a group run concurrently: every item needs its own S and its own workspace
+ * (LSP_ERR_WORKSPACE otherwise), and a W may appear only once (LSP_ERR_SHAPE).  Errors are
+ * those of the single calls; on any error nothing is enqueued.  When the problems need different
+ * kernel variants (e.g. some n divisible by 8 and some not) the call enqueues them one by one.
+ */
+typedef struct {
+    const void* G;            /* device, m*n elements of `dtype` */
+    const void* plan;         /* device, from lsp_plan_build for this problem's projectors */
+    float*      S;            /* device, r*r fp32, written */
+    void*       workspace;    /* device, >= lsp_compress_planned_workspace_bytes(m,n,r,d) */
+    size_t      workspace_bytes;
+    int64_t     m, n;
+} lsp_compress_item;
+
+typedef struct {
+    void*          W;         /* device, m*n elements of `dtype`, read and written */
+    const float*   S;         /* device, r*r fp32 */
+    const int32_t* P_idx;     /* device, [m][d] */
+    const float*   P_val;
+    const int32_t* Q_idx;     /* device, [n][d] */
+    const float*   Q_val;
+    int64_t        m, n;
+} lsp_apply_item;
+
+int lsp_compress_planned_grouped(const lsp_compress_item* items, int32_t count,
+                                 int32_t r, int32_t d, lsp_dtype dtype, void* stream);
+
+int lsp_decompress_apply_grouped(const lsp_apply_item* items, int32_t count,
+                                 int32_t r, int32_t d, lsp_dtype dtype, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Utilities.

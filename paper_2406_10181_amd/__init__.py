@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     lsp_compress, lsp_compress_workspace_bytes,
     lsp_plan_bytes, lsp_plan_build, lsp_plan_build_host,
     lsp_compress_planned, lsp_compress_planned_workspace_bytes,
-    lsp_decompress_apply, lsp_validate_projector, lsp_strerror, lsp_version,
+    lsp_decompress_apply, lsp_compress_planned_grouped, lsp_decompress_apply_grouped,
+    lsp_compress_item, lsp_apply_item, compress_items, apply_items, lsp_validate_projector, lsp_strerror, lsp_version,
     torch_dtype_code,
 )

@@ -11,6 +11,19 @@ _LIB_PATH = os.path.join(_PKG, "liblsp_hip.so")
 DTYPE_CODE = {"f32": 0, "f16": 1, "bf16": 2}
 
 
+class lsp_compress_item(ctypes.Structure):
+    """One problem of lsp_compress_planned_grouped (field for field the C struct)."""
+    _fields_ = [("G", ctypes.c_void_p), ("plan", ctypes.c_void_p), ("S", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("m", ctypes.c_int64), ("n", ctypes.c_int64)]
+
+
+class lsp_apply_item(ctypes.Structure):
+    """One problem of lsp_decompress_apply_grouped (field for field the C struct)."""
+    _fields_ = [("W", ctypes.c_void_p), ("S", ctypes.c_void_p), ("P_idx", ctypes.c_void_p), ("P_val", ctypes.c_void_p),
+                ("Q_idx", ctypes.c_void_p), ("Q_val", ctypes.c_void_p), ("m", ctypes.c_int64), ("n", ctypes.c_int64)]
+
+
 class LspError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -50,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.lsp_compress_planned_workspace_bytes.restype = sz
         L.lsp_decompress_apply.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, vp]
         L.lsp_decompress_apply.restype = ctypes.c_int
+        L.lsp_compress_planned_grouped.argtypes = [vp, i32, i32, i32, i32, vp]
+        L.lsp_compress_planned_grouped.restype = ctypes.c_int
+        L.lsp_decompress_apply_grouped.argtypes = [vp, i32, i32, i32, i32, vp]
+        L.lsp_decompress_apply_grouped.restype = ctypes.c_int
         L.lsp_validate_projector.argtypes = [vp, i64, i32, i32, vp, vp]
         L.lsp_validate_projector.restype = ctypes.c_int
         L.lsp_strerror.argtypes = [ctypes.c_int]
@@ -151,6 +168,40 @@ def lsp_decompress_apply(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, dtype: in
                                     m, n, r, d, dtype, _stream(stream))
     if check:
         _check(rc, "lsp_decompress_apply")
+    return rc
+
+
+def compress_items(problems):
+    """Host array of lsp_compress_item from (G, plan, S, workspace, workspace_bytes, m, n) tuples."""
+    arr = (lsp_compress_item * len(problems))()
+    for k, (G, plan, S, ws, ws_bytes, m, n) in enumerate(problems):
+        arr[k] = lsp_compress_item(_ptr(G), _ptr(plan), _ptr(S), _ptr(ws), ws_bytes, m, n)
+    return arr
+
+
+def apply_items(problems):
+    """Host array of lsp_apply_item from (W, S, P_idx, P_val, Q_idx, Q_val, m, n) tuples."""
+    arr = (lsp_apply_item * len(problems))()
+    for k, (W, S, P_idx, P_val, Q_idx, Q_val, m, n) in enumerate(problems):
+        arr[k] = lsp_apply_item(_ptr(W), _ptr(S), _ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val), m, n)
+    return arr
+
+
+def lsp_compress_planned_grouped(items, count, r, d, dtype: int, stream=None, check: bool = True) -> int:
+    """items: a ctypes array from compress_items() (kept alive by the caller for the call)."""
+    rc = lib().lsp_compress_planned_grouped(ctypes.addressof(items) if items is not None else None, count, r, d, dtype,
+                                            _stream(stream))
+    if check:
+        _check(rc, "lsp_compress_planned_grouped")
+    return rc
+
+
+def lsp_decompress_apply_grouped(items, count, r, d, dtype: int, stream=None, check: bool = True) -> int:
+    """items: a ctypes array from apply_items()."""
+    rc = lib().lsp_decompress_apply_grouped(ctypes.addressof(items) if items is not None else None, count, r, d, dtype,
+                                            _stream(stream))
+    if check:
+        _check(rc, "lsp_decompress_apply_grouped")
     return rc
 
 

@@ -102,34 +102,99 @@ int lsp_plan_build_host(const int32_t* P_idx, const float* P_val, const int32_t*
     return lsp::build_plan_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, static_cast<uint8_t*>(plan_host));
 }
 
+int lsp_compress_planned_grouped(const lsp_compress_item* items, int32_t count, int32_t r, int32_t d,
+                                 lsp_dtype dtype, void* stream) {
+    if (!items) return LSP_ERR_NULL;
+    if (count <= 0 || count > LSP_MAX_GROUP) return LSP_ERR_SHAPE;
+    int rc = check_dtype(dtype);
+    if (rc != LSP_OK) return rc;
+    lsp::CompressGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.count = count;
+    for (int p = 0; p < count; ++p) {
+        const lsp_compress_item& it = items[p];
+        if (!it.G || !it.plan || !it.S) return LSP_ERR_NULL;
+        rc = check_shape(it.m, it.n, r, d);
+        if (rc != LSP_OK) return rc;
+        if (!it.workspace || it.workspace_bytes < lsp_compress_planned_workspace_bytes(it.m, it.n, r, d)) return LSP_ERR_WORKSPACE;
+        if (!aligned16(it.workspace) || !aligned16(it.plan)) return LSP_ERR_WORKSPACE;
+        if (!aligned16(it.G) || !aligned16(it.S)) return LSP_ERR_ALIGN;
+        for (int q = 0; q < p; ++q)                            // problems of a group run concurrently
+            if (items[q].workspace == it.workspace || items[q].S == it.S) return LSP_ERR_WORKSPACE;
+        g.G[p] = it.G; g.plan[p] = static_cast<const uint8_t*>(it.plan);
+        g.T[p] = static_cast<float*>(it.workspace); g.S[p] = it.S;
+        g.m[p] = (int32_t)it.m; g.n[p] = (int32_t)it.n;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (lsp::compress_group_uniform(g)) {
+        hipError_t e = lsp::launch_compress_planned(g, r, d, dtype, st);
+        return e == hipSuccess ? LSP_OK : fail_launch(e);
+    }
+    for (int p = 0; p < count; ++p) {                          // mixed kernel variants: one launch per problem
+        lsp::CompressGroup one;
+        std::memset(&one, 0, sizeof(one));
+        one.count = 1;
+        one.G[0] = g.G[p]; one.plan[0] = g.plan[p]; one.T[0] = g.T[p]; one.S[0] = g.S[p]; one.m[0] = g.m[p]; one.n[0] = g.n[p];
+        hipError_t e = lsp::launch_compress_planned(one, r, d, dtype, st);
+        if (e != hipSuccess) return fail_launch(e);
+    }
+    return LSP_OK;
+}
+
 int lsp_compress_planned(const void* G, const void* plan, int64_t m, int64_t n, int32_t r, int32_t d,
                          float* S, lsp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
     if (!G || !plan || !S) return LSP_ERR_NULL;
-    int rc = check_shape(m, n, r, d);
+    lsp_compress_item it;
+    it.G = G; it.plan = plan; it.S = S; it.workspace = workspace; it.workspace_bytes = workspace_bytes; it.m = m; it.n = n;
+    return lsp_compress_planned_grouped(&it, 1, r, d, dtype, stream);
+}
+
+int lsp_decompress_apply_grouped(const lsp_apply_item* items, int32_t count, int32_t r, int32_t d,
+                                 lsp_dtype dtype, void* stream) {
+    if (!items) return LSP_ERR_NULL;
+    if (count <= 0 || count > LSP_MAX_GROUP) return LSP_ERR_SHAPE;
+    int rc = check_dtype(dtype);
     if (rc != LSP_OK) return rc;
-    rc = check_dtype(dtype);
-    if (rc != LSP_OK) return rc;
-    if (!workspace || workspace_bytes < lsp_compress_planned_workspace_bytes(m, n, r, d)) return LSP_ERR_WORKSPACE;
-    if (!aligned16(workspace) || !aligned16(plan)) return LSP_ERR_WORKSPACE;
-    if (!aligned16(G) || !aligned16(S)) return LSP_ERR_ALIGN;
-    hipError_t e = lsp::launch_compress_planned(G, static_cast<const uint8_t*>(plan), m, n, r, d, S, dtype,
-                                                static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LSP_OK : fail_launch(e);
+    lsp::ApplyGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.count = count;
+    for (int p = 0; p < count; ++p) {
+        const lsp_apply_item& it = items[p];
+        if (!it.W || !it.S || !it.P_idx || !it.P_val || !it.Q_idx || !it.Q_val) return LSP_ERR_NULL;
+        rc = check_shape(it.m, it.n, r, d);
+        if (rc != LSP_OK) return rc;
+        if (!aligned16(it.W) || !aligned16(it.S) || !aligned16(it.P_idx) || !aligned16(it.P_val) || !aligned16(it.Q_idx) ||
+            !aligned16(it.Q_val))
+            return LSP_ERR_ALIGN;
+        for (int q = 0; q < p; ++q)
+            if (items[q].W == it.W) return LSP_ERR_SHAPE;      // one matrix twice in a group would race
+        g.W[p] = it.W; g.S[p] = it.S; g.P_idx[p] = it.P_idx; g.P_val[p] = it.P_val; g.Q_idx[p] = it.Q_idx; g.Q_val[p] = it.Q_val;
+        g.m[p] = (int32_t)it.m; g.n[p] = (int32_t)it.n;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (lsp::apply_group_uniform(g, r, d)) {
+        hipError_t e = lsp::launch_decompress(g, r, d, dtype, st);
+        return e == hipSuccess ? LSP_OK : fail_launch(e);
+    }
+    for (int p = 0; p < count; ++p) {
+        lsp::ApplyGroup one;
+        std::memset(&one, 0, sizeof(one));
+        one.count = 1;
+        one.W[0] = g.W[p]; one.S[0] = g.S[p]; one.P_idx[0] = g.P_idx[p]; one.P_val[0] = g.P_val[p];
+        one.Q_idx[0] = g.Q_idx[p]; one.Q_val[0] = g.Q_val[p]; one.m[0] = g.m[p]; one.n[0] = g.n[p];
+        hipError_t e = lsp::launch_decompress(one, r, d, dtype, st);
+        if (e != hipSuccess) return fail_launch(e);
+    }
+    return LSP_OK;
 }
 
 int lsp_decompress_apply(void* W, const float* S, const int32_t* P_idx, const float* P_val,
                          const int32_t* Q_idx, const float* Q_val,
                          int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype, void* stream) {
     if (!W || !S || !P_idx || !P_val || !Q_idx || !Q_val) return LSP_ERR_NULL;
-    int rc = check_shape(m, n, r, d);
-    if (rc != LSP_OK) return rc;
-    rc = check_dtype(dtype);
-    if (rc != LSP_OK) return rc;
-    if (!aligned16(W) || !aligned16(S) || !aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val))
-        return LSP_ERR_ALIGN;
-    hipError_t e = lsp::launch_decompress(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, dtype,
-                                          static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LSP_OK : fail_launch(e);
+    lsp_apply_item it;
+    it.W = W; it.S = S; it.P_idx = P_idx; it.P_val = P_val; it.Q_idx = Q_idx; it.Q_val = Q_val; it.m = m; it.n = n;
+    return lsp_decompress_apply_grouped(&it, 1, r, d, dtype, stream);
 }
 
 int lsp_validate_projector(const int32_t* idx, int64_t rows, int32_t d, int32_t r, int32_t* flag, void* stream) {

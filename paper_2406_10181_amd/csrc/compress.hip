@@ -344,15 +344,19 @@ __device__ __attribute__((noinline)) void gq_any_slots(ChunkStager<D, VEC> stg, 
 }
 
 template <typename D, bool VEC>
-__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::elem* __restrict__ G,
-                                                           const uint8_t* __restrict__ plan,
-                                                           float* __restrict__ T, float* __restrict__ S,
-                                                           int m, int n, int r) {
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup grp, int r) {
     extern __shared__ __align__(16) uint8_t smem[];
+    const int prob = group_find(grp.first_gq, grp.count, (int)blockIdx.x);
+    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(grp.G[prob]);
+    const uint8_t* __restrict__ plan = grp.plan[prob];
+    float* __restrict__ T = grp.T[prob];
+    float* __restrict__ S = grp.S[prob];
+    const int m = grp.m[prob], n = grp.n[prob];
+    const int block = (int)blockIdx.x - grp.first_gq[prob], nblocks = grp.first_gq[prob + 1] - grp.first_gq[prob];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t i0 = (int64_t)blockIdx.x * kRowsGQ;
+    const int64_t i0 = (int64_t)block * kRowsGQ;
 
     ChunkStager<D, VEC> stg;
     stg.fetch(G, i0, m, n, 0, tid);                                   // depends on nothing but the arguments
@@ -362,7 +366,7 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::el
     // S must start at zero only when some row of P^T was cut into pieces (kernel B then adds).
     if (H->p_any_split) {
         const int64_t total = (int64_t)r * r;
-        for (int64_t k = (int64_t)blockIdx.x * kThreadsGQ + tid; k < total; k += (int64_t)gridDim.x * kThreadsGQ) S[k] = 0.0f;
+        for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
     }
     if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     if (H->nslots == 1) gq_one_slot<D, VEC>(stg, smem, G, plan, H, T, i0, m, n, r, tid, lane, wave);
@@ -377,11 +381,15 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const typename D::el
 constexpr int kThreadsB = 256;
 constexpr int kStripeQuads = 64;                              // column quads (float4) per stripe
 template <bool VEC4>
-__global__ __launch_bounds__(kThreadsB) void k_compress_pt(const uint8_t* __restrict__ plan, const float* __restrict__ T,
-                                                          float* __restrict__ S, int r, int nstripes) {
+__global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup grp, int r, int nstripes) {
     __shared__ f32x4 part[3][kStripeQuads];
+    const int prob = group_find(grp.first_pt, grp.count, (int)blockIdx.x);
+    const uint8_t* __restrict__ plan = grp.plan[prob];
+    const float* __restrict__ T = grp.T[prob];
+    float* __restrict__ S = grp.S[prob];
+    const int block = (int)blockIdx.x - grp.first_pt[prob];
     const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
-    const int stripe = blockIdx.x % nstripes, item = blockIdx.x / nstripes;
+    const int stripe = block % nstripes, item = block / nstripes;
     if (item >= H->p_nitems) return;
     const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[item];
     const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
@@ -475,32 +483,40 @@ __global__ __launch_bounds__(256) void k_raw_pt(const float* __restrict__ T, con
 }
 
 // ----------------------------------------------------------------------------------------------
+bool compress_group_uniform(const CompressGroup& g) {
+    for (int p = 1; p < g.count; ++p)
+        if ((g.n[p] % 8 == 0) != (g.n[0] % 8 == 0)) return false;     // selects vector or element-wise loads
+    return true;
+}
+
 template <typename D>
-static hipError_t launch_gq(const void* G, const uint8_t* plan, float* T, float* S, int64_t m, int64_t n, int32_t r, hipStream_t st) {
+static hipError_t launch_gq(const CompressGroup& g, int32_t r, hipStream_t st) {
     const size_t lds = (size_t)kPlanes * kPlaneStride;       // >= 64 r bytes for every supported r
-    const unsigned grid = (unsigned)((m + kRowsGQ - 1) / kRowsGQ);
-    const bool vec = (n % 8) == 0;
+    const bool vec = (g.n[0] % 8) == 0;
     auto kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsGQ), lds, st,
-                       reinterpret_cast<const typename D::elem*>(G), plan, T, S, (int)m, (int)n, (int)r);
+    hipLaunchKernelGGL(kern, dim3((unsigned)g.first_gq[g.count]), dim3(kThreadsGQ), lds, st, g, (int)r);
     return hipGetLastError();
 }
 
-hipError_t launch_compress_planned(const void* G, const uint8_t* plan, int64_t m, int64_t n, int32_t r, int32_t d,
-                                   float* S, lsp_dtype dtype, float* T, hipStream_t st) {
+hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
+    const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
+    g.first_gq[0] = g.first_pt[0] = 0;
+    for (int p = 0; p < g.count; ++p) {
+        g.first_gq[p + 1] = g.first_gq[p] + (g.m[p] + kRowsGQ - 1) / kRowsGQ;
+        g.first_pt[p + 1] = g.first_pt[p] + (int32_t)plan_max_items(g.m[p], r, d) * nstripes;
+    }
     hipError_t e;
     switch (dtype) {
-        case LSP_F32:  e = launch_gq<F32>(G, plan, T, S, m, n, r, st); break;
-        case LSP_F16:  e = launch_gq<F16>(G, plan, T, S, m, n, r, st); break;
-        default:       e = launch_gq<BF16>(G, plan, T, S, m, n, r, st); break;
+        case LSP_F32:  e = launch_gq<F32>(g, r, st); break;
+        case LSP_F16:  e = launch_gq<F16>(g, r, st); break;
+        default:       e = launch_gq<BF16>(g, r, st); break;
     }
     if (e != hipSuccess) return e;
-    const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
-    const unsigned items = (unsigned)plan_max_items(m, r, d) * (unsigned)nstripes;
-    if (r % 4 == 0) hipLaunchKernelGGL(k_compress_pt<true>, dim3(items), dim3(kThreadsB), 0, st, plan, T, S, (int)r, nstripes);
-    else            hipLaunchKernelGGL(k_compress_pt<false>, dim3(items), dim3(kThreadsB), 0, st, plan, T, S, (int)r, nstripes);
+    const unsigned blocks = (unsigned)g.first_pt[g.count];
+    if (r % 4 == 0) hipLaunchKernelGGL(k_compress_pt<true>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, nstripes);
+    else            hipLaunchKernelGGL(k_compress_pt<false>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, nstripes);
     return hipGetLastError();
 }
 

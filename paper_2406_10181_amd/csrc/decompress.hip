@@ -120,15 +120,21 @@ __device__ __forceinline__ void build_u_tile_fast(uint8_t* smem, int2* pent, con
 // All loads of a pass (the thread's rows of Q and its R x CPT patch of W) are issued before the
 // gathers start, so one pass costs one HBM round trip; many waves per CU overlap the passes.
 template <typename D, int RG, int DD, int PS, int NT, int CPT, int kDepth>
-__global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict__ W, const float* __restrict__ S,
-                                                  const int32_t* __restrict__ P_idx, const float* __restrict__ P_val,
-                                                  const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
-                                                  int m, int n, int r) {
+__global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r) {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int R = 4 * RG;
     constexpr int NE = CPT * DD;                                    // entries owned by a thread in one pass
     static_assert(NE % 4 == 0, "entries are loaded 4 at a time");
-    const int64_t i0 = (int64_t)blockIdx.x * R;
+    const int prob = group_find(grp.first, grp.count, (int)blockIdx.x);
+    typename D::elem* __restrict__ W = static_cast<typename D::elem*>(grp.W[prob]);
+    const float* __restrict__ S = grp.S[prob];
+    const int32_t* __restrict__ P_idx = grp.P_idx[prob];
+    const float* __restrict__ P_val = grp.P_val[prob];
+    const int32_t* __restrict__ Q_idx = grp.Q_idx[prob];
+    const float* __restrict__ Q_val = grp.Q_val[prob];
+    const int m = grp.m[prob], n = grp.n[prob];
+    const int block = (int)blockIdx.x - grp.first[prob];
+    const int64_t i0 = (int64_t)block * R;
     int2* pent = reinterpret_cast<int2*>(smem + RG * PS);
     const f32x4* Us4 = reinterpret_cast<const f32x4*>(smem);
 
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(NT) void k_decompress(typename D::elem* __restrict_
     // without the rotation they would all ask the same few L2 channels for the same lines at once.
     const int64_t step = (int64_t)NT * CPT;
     const int npass = (int)((n + step - 1) / step);
-    const int rot = (int)((blockIdx.x / 8) % npass);
+    const int rot = (int)((block / 8) % npass);
     auto pass_col = [&](int p) -> int64_t {
         int q = p + rot;
         if (q >= npass) q -= npass;
@@ -269,35 +275,44 @@ __global__ __launch_bounds__(kThreadsD) void k_decompress_any(typename D::elem* 
     }
 }
 
+// The fast kernel needs n % 4 == 0, r % 4 == 0 and d in {2, 4, 8, 16}; a group takes it only if all
+// of its problems qualify.
+static bool fast_shape(int32_t n, int32_t r, int32_t d) {
+    return (n % 4) == 0 && (r % 4) == 0 && (d == 2 || d == 4 || d == 8 || d == 16);
+}
+bool apply_group_uniform(const ApplyGroup& g, int32_t r, int32_t d) {
+    for (int p = 1; p < g.count; ++p)
+        if (fast_shape(g.n[p], r, d) != fast_shape(g.n[0], r, d)) return false;
+    return g.count == 1 || fast_shape(g.n[0], r, d);                // the generic kernel takes one problem at a time
+}
+
 template <typename D, int RG, int PS, int NT, int CPT, int DEPTH>
-static hipError_t launch_d(void* W, const float* S, const int32_t* P_idx, const float* P_val,
-                           const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
-                           hipStream_t st) {
+static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st) {
     using E = typename D::elem;
-    const unsigned grid = (unsigned)((m + RG * 4 - 1) / (RG * 4));
-    const bool fast = (n % 4) == 0 && (r % 4) == 0 && (d == 2 || d == 4 || d == 8 || d == 16);   // CPT * d % 4 == 0 holds
+    g.first[0] = 0;
+    for (int p = 0; p < g.count; ++p) g.first[p + 1] = g.first[p] + (g.m[p] + RG * 4 - 1) / (RG * 4);
+    const unsigned grid = (unsigned)g.first[g.count];
     hipError_t e;
 #define LSP_LAUNCH_FAST(DDV)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, DEPTH>;                                                    \
+        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, DEPTH>;                                              \
         const size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                              \
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         if (e != hipSuccess) return e;                                                                         \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, reinterpret_cast<E*>(W), S, P_idx, P_val,      \
-                           Q_idx, Q_val, (int)m, (int)n, (int)r);                                              \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, g, (int)r);                                    \
     } while (0)
-    if (fast && d == 2) LSP_LAUNCH_FAST(2);
-    else if (fast && d == 4) LSP_LAUNCH_FAST(4);
-    else if (fast && d == 8) LSP_LAUNCH_FAST(8);
-    else if (fast && d == 16) LSP_LAUNCH_FAST(16);
-    else {
+    if (!fast_shape(g.n[0], r, d)) {
         auto kern = k_decompress_any<D, RG>;
         const size_t lds = (size_t)RG * r * 16;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsD), lds, st, reinterpret_cast<E*>(W), S, P_idx, P_val,
-                           Q_idx, Q_val, (int)m, (int)n, (int)r, (int)d);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsD), lds, st, static_cast<E*>(g.W[0]), g.S[0], g.P_idx[0], g.P_val[0],
+                           g.Q_idx[0], g.Q_val[0], (int)g.m[0], (int)g.n[0], (int)r, (int)d);
     }
+    else if (d == 2) LSP_LAUNCH_FAST(2);
+    else if (d == 4) LSP_LAUNCH_FAST(4);
+    else if (d == 8) LSP_LAUNCH_FAST(8);
+    else LSP_LAUNCH_FAST(16);
 #undef LSP_LAUNCH_FAST
     return hipGetLastError();
 }
@@ -306,14 +321,14 @@ static hipError_t launch_d(void* W, const float* S, const int32_t* P_idx, const 
 // Passes held in registers: three when the grid is small (few workgroups per CU, so each has to
 // keep more bytes in flight itself), two otherwise.
 template <typename D>
-static hipError_t launch_d_shape(void* W, const float* S, const int32_t* P_idx, const float* P_val,
-                                 const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
-                                 hipStream_t st) {
+static hipError_t launch_d_shape(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st) {
     constexpr int NT = 512, CPT = 2;
-    const bool deep = (m + 15) / 16 <= 512;
-#define LSP_D_CASE(RGV, PSV)                                                                                        \
-    return deep ? launch_d<D, RGV, PSV, NT, CPT, 3>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st)               \
-                : launch_d<D, RGV, PSV, NT, CPT, 2>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st)
+    int64_t blocks = 0;
+    for (int p = 0; p < g.count; ++p) blocks += (g.m[p] + 15) / 16;
+    const bool deep = blocks <= 512;
+#define LSP_D_CASE(RGV, PSV)                                                          \
+    return deep ? launch_d<D, RGV, PSV, NT, CPT, 3>(g, r, d, st)                      \
+                : launch_d<D, RGV, PSV, NT, CPT, 2>(g, r, d, st)
     if (r <= 256) LSP_D_CASE(4, 4096);
     if (r <= 512) LSP_D_CASE(4, 8192);
     if (r <= 1024) LSP_D_CASE(4, 16384);
@@ -321,13 +336,11 @@ static hipError_t launch_d_shape(void* W, const float* S, const int32_t* P_idx, 
 #undef LSP_D_CASE
 }
 
-hipError_t launch_decompress(void* W, const float* S, const int32_t* P_idx, const float* P_val,
-                             const int32_t* Q_idx, const float* Q_val,
-                             int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
+hipError_t launch_decompress(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
     switch (dtype) {
-        case LSP_F32:  return launch_d_shape<F32>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-        case LSP_F16:  return launch_d_shape<F16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
-        default:       return launch_d_shape<BF16>(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, st);
+        case LSP_F32:  return launch_d_shape<F32>(g, r, d, st);
+        case LSP_F16:  return launch_d_shape<F16>(g, r, d, st);
+        default:       return launch_d_shape<BF16>(g, r, d, st);
     }
 }
 

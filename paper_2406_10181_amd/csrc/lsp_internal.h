@@ -89,17 +89,55 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
                     int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* host_plan);
 
 // ------------------------------------------------------------------------------------------
-// Kernel launchers (each returns hipSuccess or the launch error).
+// Groups: several independent problems (same r, d, dtype) served by one launch per kernel, so that
+// workgroups of different matrices fill the CUs together.  Passed to the kernels by value.
+// first[p] .. first[p+1] are the workgroups of problem p.
 // ------------------------------------------------------------------------------------------
-hipError_t launch_compress_planned(const void* G, const uint8_t* plan, int64_t m, int64_t n, int32_t r, int32_t d,
-                                   float* S, lsp_dtype dtype, float* T, hipStream_t st);
+constexpr int kMaxGroup = LSP_MAX_GROUP;
+struct CompressGroup {
+    const void*    G[kMaxGroup];
+    const uint8_t* plan[kMaxGroup];
+    float*         T[kMaxGroup];
+    float*         S[kMaxGroup];
+    int32_t        m[kMaxGroup], n[kMaxGroup];
+    int32_t        first_gq[kMaxGroup + 1];      // workgroups of the T = G Q kernel
+    int32_t        first_pt[kMaxGroup + 1];      // workgroups of the S = P^T T kernel
+    int32_t        count;
+};
+struct ApplyGroup {
+    void*          W[kMaxGroup];
+    const float*   S[kMaxGroup];
+    const int32_t* P_idx[kMaxGroup];
+    const float*   P_val[kMaxGroup];
+    const int32_t* Q_idx[kMaxGroup];
+    const float*   Q_val[kMaxGroup];
+    int32_t        m[kMaxGroup], n[kMaxGroup];
+    int32_t        first[kMaxGroup + 1];
+    int32_t        count;
+};
+
+#if defined(__HIPCC__)
+// index of the problem that owns workgroup `block` (uniform; count <= kMaxGroup)
+__device__ __forceinline__ int group_find(const int32_t* first, int count, int block) {
+    int p = 0;
+    while (p + 1 < count && block >= first[p + 1]) ++p;
+    return p;
+}
+#endif
+
+// ------------------------------------------------------------------------------------------
+// Kernel launchers (each returns hipSuccess or the launch error).  The group launchers fill in
+// first_* themselves; all problems of a group must agree on what selects the kernel variant
+// (see compress_group_uniform / apply_group_uniform).
+// ------------------------------------------------------------------------------------------
+bool       compress_group_uniform(const CompressGroup& g);
+bool       apply_group_uniform(const ApplyGroup& g, int32_t r, int32_t d);
+hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
 hipError_t launch_compress_raw(const void* G, const int32_t* P_idx, const float* P_val,
                                const int32_t* Q_idx, const float* Q_val,
                                int64_t m, int64_t n, int32_t r, int32_t d,
                                float* S, lsp_dtype dtype, float* T, hipStream_t st);
-hipError_t launch_decompress(void* W, const float* S, const int32_t* P_idx, const float* P_val,
-                             const int32_t* Q_idx, const float* Q_val,
-                             int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
+hipError_t launch_decompress(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
 hipError_t launch_validate(const int32_t* idx, int64_t count, int32_t r, int32_t* flag, hipStream_t st);
 
 // ------------------------------------------------------------------------------------------

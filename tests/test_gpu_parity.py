@@ -154,6 +154,69 @@ def test_planned_path_is_reproducible_and_plan_reusable():
     gu.check_compress(S2, S2_o, "cfg2 second gradient")
 
 
+def _grouped_case(pbs, tight=5e-5):
+    """Grouped calls against the oracle, and bit for bit against the single calls."""
+    import torch
+    import gpu_util as gu
+    import paper_2406_10181_amd as L
+    r, d, code = pbs[0].r, pbs[0].d, syn.DTYPE_CODE[pbs[0].dtype]
+    dps = [_dp(pb) for pb in pbs]
+    for dp in dps:
+        dp.build_plan()
+    singles = [dp.compress_planned() for dp in dps]
+    for dp in dps:
+        dp.S.fill_(float("nan"))
+    stream = torch.cuda.current_stream()
+    items = L.compress_items([(dp.G, dp.plan, dp.S, dp.ws, dp.ws_bytes, dp.pb.m, dp.pb.n) for dp in dps])
+    L.lsp_compress_planned_grouped(items, len(dps), r, d, code, stream)
+    torch.cuda.synchronize()
+    for dp, single in zip(dps, singles):
+        pb = dp.pb
+        print(f"[case] grouped {pb.name} m={pb.m} n={pb.n} r={pb.r} d={pb.d} {pb.dtype}", flush=True)
+        S_g = dp.S.cpu().numpy()
+        S_o = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, threads=THREADS)
+        gu.check_compress(S_g, S_o, pb.name + " grouped", tight)
+        assert np.array_equal(S_g, single), f"{pb.name}: grouped compress differs from the single call"
+    W_single = [dp.decompress(dp.pb.S_in) for dp in dps]
+    Wd = [dp.W.clone() for dp in dps]
+    Sd = [torch.from_numpy(np.ascontiguousarray(dp.pb.S_in, dtype=np.float32)).cuda() for dp in dps]
+    aitems = L.apply_items([(w, s, dp.P_idx, dp.P_val, dp.Q_idx, dp.Q_val, dp.pb.m, dp.pb.n)
+                            for w, s, dp in zip(Wd, Sd, dps)])
+    L.lsp_decompress_apply_grouped(aitems, len(dps), r, d, code, stream)
+    torch.cuda.synchronize()
+    for dp, w, ws in zip(dps, Wd, W_single):
+        pb = dp.pb
+        W_g = gu.to_host(w, pb.dtype)
+        Wp, Wr = oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, threads=THREADS)
+        gu.check_decompress(W_g, pb.W, Wp, Wr, pb.dtype, pb.name + " grouped")
+        assert np.array_equal(W_g, ws), f"{pb.name}: grouped decompress differs from the single call"
+
+
+def test_grouped_calls_mixed_shapes():
+    # three problems of different shapes (tall, wide with a ragged row block, small) in one launch per kernel
+    pbs = [syn.make_problem("grp_a", 300, 4096, 256, 4, "bf16", seed=901),
+           syn.make_problem("grp_b", 70, 6152, 256, 4, "bf16", seed=902),
+           syn.make_problem("grp_c", 16, 2048, 256, 4, "bf16", seed=903)]
+    _grouped_case(pbs)
+
+
+def test_grouped_calls_fall_back_when_kernel_variants_differ():
+    # n % 8 != 0 in one problem (element-wise loads, generic decompress): the call serves them one by one
+    pbs = [syn.make_problem("grpmix_a", 64, 1030, 64, 3, "f16", seed=911),
+           syn.make_problem("grpmix_b", 40, 2048, 64, 3, "f16", seed=912)]
+    _grouped_case(pbs)
+
+
+def test_grouped_layer_of_config4():
+    # the seven matrices of one layer of the 6.7B-style stack, at full size, as bench.py launches them:
+    # sampled rows against the oracle, everything bit for bit against the single calls
+    import torch
+    import gpu_util as gu
+    import paper_2406_10181_amd as L
+    pbs = [syn.config4_matrix(31, which) for which in (0, 1, 3)]       # down, gate, o: one of each shape
+    _grouped_case(pbs)
+
+
 def test_fp16_subnormals_are_not_flushed():
     m, n, r, d = 32, 1024, 16, 2
     rng = np.random.default_rng(7)

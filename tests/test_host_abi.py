@@ -60,6 +60,33 @@ def test_argument_errors_without_gpu():
         L.lsp_compress(None, fake, fake, fake, fake, 64, 64, 16, 2, fake, 0, fake, big)
 
 
+def test_grouped_argument_errors_without_gpu():
+    fake, big = 0x1000, 1 << 20
+    one = L.compress_items([(fake, fake, fake, fake, big, 64, 64)])
+    assert L.lsp_compress_planned_grouped(None, 1, 16, 2, 0, check=False) == -1
+    assert L.lsp_compress_planned_grouped(one, 0, 16, 2, 0, check=False) == -2
+    assert L.lsp_compress_planned_grouped(one, 17, 16, 2, 0, check=False) == -2
+    assert L.lsp_compress_planned_grouped(one, 1, 16, 2, 9, check=False) == -3
+    assert L.lsp_compress_planned_grouped(L.compress_items([(fake, None, fake, fake, big, 64, 64)]), 1, 16, 2, 0, check=False) == -1
+    assert L.lsp_compress_planned_grouped(L.compress_items([(fake, fake, fake, fake, 8, 64, 64)]), 1, 16, 2, 0, check=False) == -4
+    assert L.lsp_compress_planned_grouped(L.compress_items([(fake, fake, fake, fake, big, 64, 0)]), 1, 16, 2, 0, check=False) == -2
+    # two problems sharing a workspace or an S would race
+    two = L.compress_items([(fake, fake, fake, fake, big, 64, 64), (fake, fake, 0x2000, fake, big, 64, 64)])
+    assert L.lsp_compress_planned_grouped(two, 2, 16, 2, 0, check=False) == -4
+    two = L.compress_items([(fake, fake, fake, fake, big, 64, 64), (fake, fake, fake, 0x100000, big, 64, 64)])
+    assert L.lsp_compress_planned_grouped(two, 2, 16, 2, 0, check=False) == -4
+    a1 = L.apply_items([(fake, fake, fake, fake, fake, fake, 64, 64)])
+    assert L.lsp_decompress_apply_grouped(None, 1, 16, 2, 0, check=False) == -1
+    assert L.lsp_decompress_apply_grouped(a1, 0, 16, 2, 0, check=False) == -2
+    assert L.lsp_decompress_apply_grouped(a1, 1, 16, 2, 5, check=False) == -3
+    assert L.lsp_decompress_apply_grouped(L.apply_items([(fake, fake, None, fake, fake, fake, 64, 64)]), 1, 16, 2, 0, check=False) == -1
+    assert L.lsp_decompress_apply_grouped(L.apply_items([(fake + 2, fake, fake, fake, fake, fake, 64, 64)]), 1, 16, 2, 0, check=False) == -7
+    a2 = L.apply_items([(fake, fake, fake, fake, fake, fake, 64, 64), (fake, fake, fake, fake, fake, fake, 64, 64)])
+    assert L.lsp_decompress_apply_grouped(a2, 2, 16, 2, 0, check=False) == -2       # the same W twice
+    import ctypes
+    assert ctypes.sizeof(L.lsp_compress_item) == 56 and ctypes.sizeof(L.lsp_apply_item) == 64
+
+
 # ------------------------------------------------------------------ plan decoding
 def _decode_col(off):
     unit = off // 16
