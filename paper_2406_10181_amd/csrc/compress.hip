@@ -177,7 +177,7 @@ __device__ __forceinline__ void consume_pair(const uint8_t* smem, const u32x4 e,
 // out with coalesced stores.  Called by all threads of the workgroup.
 template <int NS>
 __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* plan, const PlanHeader* H, float* __restrict__ T,
-                                                  const float (&acc)[NS][kPlanes][4], int nslots, int64_t i0, int m, int r, int tid) {
+                                                  const float (&acc)[NS][kRowsGQ], int nslots, int64_t i0, int m, int r, int tid) {
     __syncthreads();
     float* Tl = reinterpret_cast<float*>(smem);
     for (int k = tid; k < kRowsGQ * r; k += kThreadsGQ) Tl[k] = 0.0f;
@@ -191,14 +191,10 @@ __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* 
                 const uint32_t bb = col & 0x7FFFu;
                 if (col & kSharedColumn) {
 #pragma unroll
-                    for (int g = 0; g < kPlanes; ++g)
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) atomicAdd(&Tl[(g * 4 + t) * r + bb], acc[s][g][t]);
+                    for (int t = 0; t < kRowsGQ; ++t) atomicAdd(&Tl[t * r + bb], acc[s][t]);
                 } else {
 #pragma unroll
-                    for (int g = 0; g < kPlanes; ++g)
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) Tl[(g * 4 + t) * r + bb] = acc[s][g][t];
+                    for (int t = 0; t < kRowsGQ; ++t) Tl[t * r + bb] = acc[s][t];
                 }
             }
         }
@@ -288,7 +284,7 @@ __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* s
         if (rot > 2) step(ring[2]);
     }
     if (H->q_any_shared) {
-        write_tile_shared<1>(smem, plan, H, T, acc, 1, i0, m, r, tid);
+        write_tile_shared<1>(smem, plan, H, T, reinterpret_cast<const float(&)[1][kRowsGQ]>(acc), 1, i0, m, r, tid);
     } else if (mycol != kNoColumn) {
 #pragma unroll
         for (int g = 0; g < kPlanes; ++g)
@@ -340,7 +336,207 @@ __device__ __attribute__((noinline)) void gq_any_slots(ChunkStager<D, VEC> stg, 
             }
         }
     }
-    write_tile_shared<kMaxSlots>(smem, plan, H, T, acc, nslots, i0, m, r, tid);
+    write_tile_shared<kMaxSlots>(smem, plan, H, T, reinterpret_cast<const float(&)[kMaxSlots][kRowsGQ]>(acc), nslots, i0, m, r, tid);
+}
+
+// ----------------------------------------------------------------------------------------------
+// 16-bit storage types (fp16, bf16), n % 8 == 0, one column per lane: G is staged as it is stored,
+// 8 rows to a 16-byte LDS unit ([plane of 8 rows][column][8 rows]), so one 128-bit gather serves
+// eight rows (half the LDS bytes per pair) and a chunk takes half the space: the LDS holds two
+// chunks, the one being consumed and the one being staged, with one barrier per chunk.  The
+// elements are widened in registers when they are used (exact: a shift or mask for bf16, a
+// conversion for fp16).
+constexpr int kPlanes16 = 2;                                          // planes of 8 rows
+constexpr int kBufStride16 = kPlanes16 * kPlaneStride;                // bytes between the two chunk buffers
+static_assert(2 * kBufStride16 == kPlanes * kPlaneStride, "both layouts use the same LDS allocation");
+
+template <typename D> __device__ __forceinline__ void widen2(uint32_t w, float& lo, float& hi);
+template <> __device__ __forceinline__ void widen2<BF16>(uint32_t w, float& lo, float& hi) {
+    lo = __uint_as_float(w << 16); hi = __uint_as_float(w & 0xFFFF0000u);
+}
+template <> __device__ __forceinline__ void widen2<F16>(uint32_t w, float& lo, float& hi) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 h; __builtin_memcpy(&h, &w, 4);
+    lo = (float)h.x; hi = (float)h.y;
+}
+
+struct ChunkStager16 {
+    u32x4 pre[8];                                                     // 8 rows x 8 columns, as stored
+    uint32_t live = 0;                                                // bit t: pre[t] holds data of the matrix
+
+    template <typename E>
+    __device__ __forceinline__ void fetch(const E* __restrict__ G, int64_t i0, int m, int n, int c, int tid) {
+        const int plane = tid / (kChunk / 8), oct = tid % (kChunk / 8);
+        const int64_t col0 = (int64_t)c * kChunk + (int64_t)oct * 8;
+        const int64_t colc = col0 < n ? col0 : 0;                    // clamped: always a valid address
+        live = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int64_t row = i0 + plane * 8 + t;
+            const int64_t rowc = row < m ? row : (int64_t)m - 1;
+            pre[t] = stream_load(reinterpret_cast<const u32x4*>(G + rowc * (int64_t)n + colc));
+            live |= (row < m && col0 < n) ? (1u << t) : 0u;
+        }
+    }
+    // transposes the 8x8 block and writes its 8 units (column q: rows 0..7) into buffer `buf`
+    __device__ __forceinline__ void stage(uint8_t* smem, int buf, int tid) {
+        const int plane = tid / (kChunk / 8), oct = tid % (kChunk / 8);
+        if (live != 0xFFu) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (!((live >> t) & 1u)) pre[t] = u32x4{0u, 0u, 0u, 0u};
+        }
+        uint8_t* base = smem + buf * kBufStride16 + plane * kPlaneStride + oct * 16;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            u32x4 unit;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t a = pre[2 * k][q >> 1], b = pre[2 * k + 1][q >> 1];   // rows 2k, 2k+1; columns q&~1, q|1
+                unit[k] = (q & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+            }
+            *reinterpret_cast<u32x4*>(base + q * (kChunk / 8) * 16) = unit;
+        }
+    }
+};
+
+__device__ __forceinline__ void gather_pair16(const uint8_t* buf, const u32x4 e, u32x4 (&x)[2][kPlanes16]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int g = 0; g < kPlanes16; ++g)
+            x[h][g] = *reinterpret_cast<const u32x4*>(buf + (h ? e.z : e.x) + g * kPlaneStride);
+}
+template <typename D>
+__device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][kPlanes16], float (&acc)[kRowsGQ]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float v = __uint_as_float(h ? e.w : e.y);
+#pragma unroll
+        for (int g = 0; g < kPlanes16; ++g)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float lo, hi;
+                widen2<D>(x[h][g][k], lo, hi);
+                acc[g * 8 + 2 * k]     = fmaf(v, lo, acc[g * 8 + 2 * k]);
+                acc[g * 8 + 2 * k + 1] = fmaf(v, hi, acc[g * 8 + 2 * k + 1]);
+            }
+    }
+}
+
+template <typename D>
+__device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+                                              const uint8_t* __restrict__ plan, const PlanHeader* H,
+                                              float* __restrict__ T, int64_t i0, int m, int n, int r,
+                                              int tid, int lane, int wave) {
+    const int nchunks = H->nchunks;
+    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg) + wave;
+    const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+    const uint32_t mycol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol)[tid];
+
+    // ring of kPrefetch batches of plan rows in fixed register slots (see gq_one_slot)
+    u32x4 ring[kPrefetch][kBatchLoads];
+#pragma unroll
+    for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
+    rp += (size_t)kPrefetch * kBatchLoads * kWave;
+
+    float acc[1][kRowsGQ];
+#pragma unroll
+    for (int t = 0; t < kRowsGQ; ++t) acc[0][t] = 0.0f;
+
+    const uint8_t* buf = smem;
+    auto step = [&](u32x4 (&slot)[kBatchLoads]) {
+        u32x4 x[2][2][kPlanes16];
+        gather_pair16(buf, slot[0], x[0]);
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) {
+            if (q + 1 < kBatchLoads) gather_pair16(buf, slot[q + 1], x[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            fma_pair16<D>(slot[q], x[q & 1], acc[0]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) slot[q] = rp[(size_t)q * kWave];
+        rp += (size_t)kBatchLoads * kWave;
+    };
+
+    stg.stage(smem, 0, tid);                                          // chunk 0 (fetched by the caller)
+    __syncthreads();
+    int rot = 0;
+    for (int c = 0; c < nchunks; ++c) {
+        if (rot != 0) {                                               // undo the slot rotation left by the previous chunk
+            u32x4 t[kPrefetch][kBatchLoads];
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) {
+                    t[k][q] = ring[(k + 1) % kPrefetch][q];
+                    if (rot == 2) t[k][q] = ring[(k + 2) % kPrefetch][q];
+                    if (rot == 3) t[k][q] = ring[(k + 3) % kPrefetch][q];
+                }
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = t[k][q];
+        }
+        static_assert(kPrefetch == 4, "the rotation above is written for four slots");
+        if (c + 1 < nchunks) stg.fetch(G, i0, m, n, c + 1, tid);      // lands while this chunk is consumed
+        buf = smem + (c & 1) * kBufStride16;
+        const int nb = (int)(seg[c * kWavesGQ] / kSegBatch);
+        for (int g = nb / kPrefetch; g > 0; --g) {
+            step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
+        }
+        rot = nb % kPrefetch;
+        if (rot > 0) step(ring[0]);
+        if (rot > 1) step(ring[1]);
+        if (rot > 2) step(ring[2]);
+        if (c + 1 < nchunks) stg.stage(smem, (c + 1) & 1, tid);       // the other buffer: nobody reads it now
+        __syncthreads();                                              // chunk c+1 is staged; chunk c is no longer read
+    }
+
+    if (H->q_any_shared) {
+        write_tile_shared<1>(smem, plan, H, T, acc, 1, i0, m, r, tid);
+    } else if (mycol != kNoColumn) {
+#pragma unroll
+        for (int t = 0; t < kRowsGQ; ++t)
+            if (i0 + t < m) stream_store(&T[(i0 + t) * (int64_t)r + mycol], acc[0][t]);
+    }
+}
+
+// Kernel A for fp16 / bf16 with n % 8 == 0.
+template <typename D>
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int prob = group_find(grp.first_gq, grp.count, (int)blockIdx.x);
+    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(grp.G[prob]);
+    const uint8_t* __restrict__ plan = grp.plan[prob];
+    float* __restrict__ T = grp.T[prob];
+    float* __restrict__ S = grp.S[prob];
+    const int m = grp.m[prob], n = grp.n[prob];
+    const int block = (int)blockIdx.x - grp.first_gq[prob], nblocks = grp.first_gq[prob + 1] - grp.first_gq[prob];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t i0 = (int64_t)block * kRowsGQ;
+
+    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
+    if (H->p_any_split) {
+        const int64_t total = (int64_t)r * r;
+        for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
+    }
+    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (H->nslots == 1) {
+        ChunkStager16 stg;
+        stg.fetch(G, i0, m, n, 0, tid);
+        gq16_one_slot<D>(stg, smem, G, plan, H, T, i0, m, n, r, tid, lane, wave);
+    } else {
+        ChunkStager<D, true> stg;
+        stg.fetch(G, i0, m, n, 0, tid);
+        gq_any_slots<D, true>(stg, smem, G, plan, H, T, i0, m, n, r, tid, lane, wave);
+    }
 }
 
 template <typename D, bool VEC>
@@ -493,7 +689,9 @@ template <typename D>
 static hipError_t launch_gq(const CompressGroup& g, int32_t r, hipStream_t st) {
     const size_t lds = (size_t)kPlanes * kPlaneStride;       // >= 64 r bytes for every supported r
     const bool vec = (g.n[0] % 8) == 0;
-    auto kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
+    void (*kern)(const CompressGroup, int);
+    if constexpr (D::size == 2) kern = vec ? k_compress_gq16<D> : k_compress_gq<D, false>;
+    else                        kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)g.first_gq[g.count]), dim3(kThreadsGQ), lds, st, g, (int)r);
