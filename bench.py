@@ -5,8 +5,10 @@ A step is one pass of the whole hot path over the 6.7B-style layer stack (BASELI
 32 layers x {down 11008x4096, gate/up 4096x11008, o/v/k/q 4096x4096}, bf16, r = 512, d = 8,
 visited layer by layer in backward order; every matrix gets one lsp_compress_planned
 (S = P^T G Q) and one lsp_decompress_apply (W -= P S Q^T).  The seven matrices of a layer are
-independent and are dealt to --streams HIP streams (default priority), joined at the end of the
-step; the roofline leg times each kernel family alone on one stream.  All inputs are resident in
+independent: by default they go out as one grouped call per kernel family
+(lsp_compress_planned_grouped, lsp_decompress_apply_grouped), layers alternating over --streams HIP
+streams (default priority), joined at the end of the step; --grouped 0 issues one call per matrix
+instead.  The roofline legs time each kernel family alone, one call per matrix, on one stream.  All inputs are resident in
 HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
 
 Prints ONE JSON line: throughput in algorithmic GB/s (bytes the method must move, see
@@ -44,7 +46,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--grouped", type=int, default=1,
                     help="1: one grouped call per layer and kernel family; 0: one call per matrix")
-    ap.add_argument("--streams", type=int, default=4,
+    ap.add_argument("--streams", type=int, default=2,
                     help="HIP streams the matrices of a layer are dealt to (default priority; joined at step end)")
     args = ap.parse_args()
     if args.gpus != 1:
