@@ -319,15 +319,18 @@ static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st) 
 
 // Rows per workgroup: 16 (four planes of U in LDS), 8 when the tile of U would not fit otherwise.
 // Passes held in registers: three when the grid is small (few workgroups per CU, so each has to
-// keep more bytes in flight itself), two otherwise.
+// keep more bytes in flight itself), two otherwise.  Big grids (grouped calls) use workgroups of
+// 256 threads, two of which share a CU and cover each other's set-up phase.
 template <typename D>
 static hipError_t launch_d_shape(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st) {
     constexpr int NT = 512, CPT = 2;
     int64_t blocks = 0;
     for (int p = 0; p < g.count; ++p) blocks += (g.m[p] + 15) / 16;
     const bool deep = blocks <= 512;
+    const bool many = blocks >= 1024;
 #define LSP_D_CASE(RGV, PSV)                                                          \
-    return deep ? launch_d<D, RGV, PSV, NT, CPT, 3>(g, r, d, st)                      \
+    return many ? launch_d<D, RGV, PSV, 256, CPT, 3>(g, r, d, st) :                   \
+           deep ? launch_d<D, RGV, PSV, NT, CPT, 3>(g, r, d, st)                      \
                 : launch_d<D, RGV, PSV, NT, CPT, 2>(g, r, d, st)
     if (r <= 256) LSP_D_CASE(4, 4096);
     if (r <= 512) LSP_D_CASE(4, 8192);

@@ -20,7 +20,7 @@ constexpr int kMaxSlots   = 4;     // a lane owns at most this many virtual colu
 constexpr int kSegBatch   = 8;     // segment lengths are multiples of this many rows
 constexpr int kPrefetch   = 4;     // batches of plan rows a wave holds in registers (one consumed, the rest in flight)
 constexpr int kStreamSlack = kPrefetch * kSegBatch;   // readable padding rows after the last segment
-constexpr int kRowPiece   = 128;   // a row list of P^T longer than this is cut into pieces
+constexpr int kRowPiece   = 256;   // a row list of P^T longer than this is cut into pieces
 constexpr uint32_t kNoColumn = 0xFFFFu;      // virtual column slot without a column
 constexpr uint32_t kSharedColumn = 0x8000u;  // flag: the column is owned by several lanes
 

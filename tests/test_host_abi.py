@@ -170,7 +170,7 @@ def _replay_plan(buf, pb):
     rows_seen = set()
     for a, start, ln, atomic in items.tolist():
         rows_seen.add(a)
-        assert 0 <= ln <= 128 and 0 <= a < r
+        assert 0 <= ln <= 256 and 0 <= a < r
         for e in range(start, start + ln):
             assert not seen[e]
             seen[e] = True
@@ -194,7 +194,7 @@ def _dense(idx, val, r):
 @pytest.mark.parametrize("m,n,r,d,dist", [
     (48, 4200, 16, 2, "distinct"),      # three chunks, ragged last chunk
     (40, 2048, 64, 4, "uniform"),
-    (33, 2500, 96, 8, "zipf"),          # hot columns get several owners; rows of P^T > 128 entries
+    (33, 2500, 96, 8, "zipf"),          # hot columns get several owners; long rows of P^T are cut
     (2000, 64, 4, 2, "uniform"),        # every row of P^T has ~1000 entries -> pieces + atomic flag
     (24, 3000, 600, 2, "uniform"),      # more columns than lanes: two slots
     (10, 7, 3, 1, "uniform"),
