@@ -2,10 +2,12 @@
 //
 // Two kernels per call, both gather-form and free of global atomics in the common case:
 //   A  T = G Q     one workgroup per block of 16 rows of G; G is streamed once from HBM in
-//                  chunks of kChunk columns, widened to fp32 and staged in LDS transposed
-//                  ([column][4 rows], so one 128-bit LDS read serves four rows); each lane owns one
-//                  column b of T and walks the plan's list of (column of G, value) pairs of b.
-//   B  S = P^T T   one workgroup per piece of a row of P^T; reads rows of T.
+//                  chunks of kChunk columns and staged in LDS transposed, one 16-byte unit per
+//                  column and group of rows (8 rows in storage precision for fp16 / bf16, 4 rows
+//                  widened to fp32 otherwise), so one 128-bit LDS read serves 8 (4) rows; each
+//                  lane owns one column b of T and walks the plan's list of (column of G, value)
+//                  pairs of b, accumulating in registers.
+//   B  S = P^T T   one wave per piece of a row of P^T and 1/8 of the columns; reads rows of T.
 // The path is bandwidth-bound (one pass over G); no matrix cores are involved because the
 // projectors are sparse (d entries per row, Def. 1) and the work is gather + fp32 FMA.
 
@@ -570,15 +572,11 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup 
 }
 
 // ----------------------------------------------------------------------------------------------
-// Kernel B.  S[a][stripe] (+)= sum_e v_e T[i_e][stripe] for one piece of a row of P^T and one
-// stripe of 256 columns.  A workgroup is 4 waves; wave w takes entries w, w+4, ... of the piece, so
-// an entry (row of T, value) is uniform over the wave (scalar loads) and the 64 lanes read 1 KB of
-// that row of T in one 128-bit load each; the four partial sums meet in LDS.
+// Kernel B, general variant (any r): S[a][stripe] (+)= sum_e v_e T[i_e][stripe] for one piece of a
+// row of P^T and one stripe of 256 columns, one column per thread.
 constexpr int kThreadsB = 256;
 constexpr int kStripeQuads = 64;                              // column quads (float4) per stripe
-template <bool VEC4>
 __global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup grp, int r, int nstripes) {
-    __shared__ f32x4 part[3][kStripeQuads];
     const int prob = group_find(grp.first_pt, grp.count, (int)blockIdx.x);
     const uint8_t* __restrict__ plan = grp.plan[prob];
     const float* __restrict__ T = grp.T[prob];
@@ -589,45 +587,63 @@ __global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup g
     if (item >= H->p_nitems) return;
     const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[item];
     const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
-    if constexpr (VEC4) {
-        const int nb4 = r >> 2;
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-        const int b4 = stripe * kStripeQuads + lane;
-        const bool live = b4 < nb4;
-        const float* Tcol = T + (live ? b4 * 4 : 0);
-        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int b = stripe * kStripeQuads * 4 + threadIdx.x; b < min(r, (stripe + 1) * kStripeQuads * 4); b += kThreadsB) {
+        float acc = 0.0f;
+        for (int e = 0; e < it.len; ++e) {
+            const uint2 en = ent[e];
+            acc = fmaf(__uint_as_float(en.y), T[(int64_t)en.x * r + b], acc);
+        }
+        float* dst = S + (int64_t)it.a * r + b;
+        if (it.atomic) atomicAdd(dst, acc); else *dst = acc;
+    }
+}
+
+// Kernel B, the usual variant (r % 4 == 0), XCD-aware.  The columns of T are cut into 8 stripes, one per XCD:
+// workgroups are dealt to the 8 XCDs round-robin, so with stripe = blockIdx % 8 an XCD only ever
+// touches its own m x r/8 slice of T, which fits its 4 MB L2 -- T comes from HBM once instead of
+// once per use (each row of T is used by d rows of S).  Each of the 4 waves of a workgroup takes
+// one piece of a row of P^T; its 64 lanes form 64/LG groups of LG lanes (LG = 16, 32 or 64 >= quads
+// per stripe), group g takes entries g, g + groups, ...; the groups' sums meet through lane
+// exchanges in a fixed order.
+template <int LG>
+__global__ __launch_bounds__(kThreadsB) void k_compress_pt8(const CompressGroup grp, int r, int sq) {
+    constexpr int NG = kWave / LG;                            // entry groups per wave
+    const int prob = group_find(grp.first_pt, grp.count, (int)blockIdx.x);
+    const uint8_t* __restrict__ plan = grp.plan[prob];
+    const float* __restrict__ T = grp.T[prob];
+    float* __restrict__ S = grp.S[prob];
+    const int block = (int)blockIdx.x - grp.first_pt[prob];
+    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    const int stripe = block & 7;
+    const int item = (block >> 3) * (kThreadsB / kWave) + (int)(threadIdx.x >> 6);
+    if (item >= H->p_nitems) return;
+    const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[item];
+    const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
+    const int lane = threadIdx.x & 63;
+    const int grp_e = lane / LG, ql = lane % LG;
+    const int b4 = stripe * sq + ql;
+    const bool live = ql < sq && b4 < (r >> 2);
+    const float* Tcol = T + (live ? b4 * 4 : 0);
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 8
-        for (int e = wave; e < it.len; e += 4) {
-            const uint2 en = ent[e];                          // uniform over the wave
-            const float v = __uint_as_float(en.y);
-            const f32x4 x = *reinterpret_cast<const f32x4*>(Tcol + (int64_t)en.x * r);
-            acc.x = fmaf(v, x.x, acc.x); acc.y = fmaf(v, x.y, acc.y);
-            acc.z = fmaf(v, x.z, acc.z); acc.w = fmaf(v, x.w, acc.w);
-        }
-        if (wave > 0) part[wave - 1][lane] = acc;
-        __syncthreads();
-        if (wave == 0 && live) {
+    for (int e = grp_e; e < it.len; e += NG) {
+        const uint2 en = ent[e];
+        const float v = __uint_as_float(en.y);
+        const f32x4 x = *reinterpret_cast<const f32x4*>(Tcol + (int64_t)en.x * r);
+        acc.x = fmaf(v, x.x, acc.x); acc.y = fmaf(v, x.y, acc.y);
+        acc.z = fmaf(v, x.z, acc.z); acc.w = fmaf(v, x.w, acc.w);
+    }
 #pragma unroll
-            for (int g = 0; g < 3; ++g) {
-                const f32x4 p = part[g][lane];
-                acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w;
-            }
-            float* dst = S + (int64_t)it.a * r + b4 * 4;
-            if (it.atomic) {
-                atomicAdd(dst + 0, acc.x); atomicAdd(dst + 1, acc.y); atomicAdd(dst + 2, acc.z); atomicAdd(dst + 3, acc.w);
-            } else {
-                *reinterpret_cast<f32x4*>(dst) = acc;
-            }
-        }
-    } else {
-        for (int b = stripe * kStripeQuads * 4 + threadIdx.x; b < min(r, (stripe + 1) * kStripeQuads * 4); b += kThreadsB) {
-            float acc = 0.0f;
-            for (int e = 0; e < it.len; ++e) {
-                const uint2 en = ent[e];
-                acc = fmaf(__uint_as_float(en.y), T[(int64_t)en.x * r + b], acc);
-            }
-            float* dst = S + (int64_t)it.a * r + b;
-            if (it.atomic) atomicAdd(dst, acc); else *dst = acc;
+    for (int step = LG; step < kWave; step *= 2) {            // group g adds group g ^ (step / LG)
+        acc.x += __shfl_xor(acc.x, step); acc.y += __shfl_xor(acc.y, step);
+        acc.z += __shfl_xor(acc.z, step); acc.w += __shfl_xor(acc.w, step);
+    }
+    if (lane < LG && live) {
+        float* dst = S + (int64_t)it.a * r + b4 * 4;
+        if (it.atomic) {
+            atomicAdd(dst + 0, acc.x); atomicAdd(dst + 1, acc.y); atomicAdd(dst + 2, acc.z); atomicAdd(dst + 3, acc.w);
+        } else {
+            *reinterpret_cast<f32x4*>(dst) = acc;
         }
     }
 }
@@ -700,10 +716,12 @@ static hipError_t launch_gq(const CompressGroup& g, int32_t r, hipStream_t st) {
 
 hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
     const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
+    const bool striped = (r % 4) == 0;
     g.first_gq[0] = g.first_pt[0] = 0;
     for (int p = 0; p < g.count; ++p) {
         g.first_gq[p + 1] = g.first_gq[p] + (g.m[p] + kRowsGQ - 1) / kRowsGQ;
-        g.first_pt[p + 1] = g.first_pt[p] + (int32_t)plan_max_items(g.m[p], r, d) * nstripes;
+        const int32_t items = (int32_t)plan_max_items(g.m[p], r, d);
+        g.first_pt[p + 1] = g.first_pt[p] + (striped ? ((items + 3) / 4) * 8 : items * nstripes);
     }
     hipError_t e;
     switch (dtype) {
@@ -713,8 +731,14 @@ hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_d
     }
     if (e != hipSuccess) return e;
     const unsigned blocks = (unsigned)g.first_pt[g.count];
-    if (r % 4 == 0) hipLaunchKernelGGL(k_compress_pt<true>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, nstripes);
-    else            hipLaunchKernelGGL(k_compress_pt<false>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, nstripes);
+    if (striped) {
+        const int sq = ((r >> 2) + 7) / 8;
+        if (sq <= 16)      hipLaunchKernelGGL(k_compress_pt8<16>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, sq);
+        else if (sq <= 32) hipLaunchKernelGGL(k_compress_pt8<32>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, sq);
+        else               hipLaunchKernelGGL(k_compress_pt8<64>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, sq);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(k_compress_pt, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, nstripes);
     return hipGetLastError();
 }
 
