@@ -293,9 +293,10 @@ static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st) 
     for (int p = 0; p < g.count; ++p) g.first[p + 1] = g.first[p] + (g.m[p] + RG * 4 - 1) / (RG * 4);
     const unsigned grid = (unsigned)g.first[g.count];
     hipError_t e;
+    // d = 16: a pass holds 32 (column, value) pairs per thread, so only one pass fits the registers
 #define LSP_LAUNCH_FAST(DDV)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, DEPTH>;                                              \
+        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, (DDV == 16 ? 1 : DEPTH)>;                            \
         const size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                              \
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         if (e != hipSuccess) return e;                                                                         \
