@@ -116,9 +116,8 @@ int lsp_plan_build_host(const int32_t* P_idx, const float* P_val,
 
 /* Same sums as lsp_compress, with the projectors given as a plan; gather form, no global
  * atomics unless a row of P^T has more than 256 entries (heavily skewed projectors), and
- * bit-reproducible from run to run whenever no list had to be cut (a column of Q used more than
- * about twice as often as the average inside one 2048-column chunk of G, or a row of P^T with more
- * than 256 entries).
+ * bit-reproducible from run to run whenever no row of P^T had to be cut for that reason
+ * (columns of Q that are shared among several lanes are summed in a fixed order).
  * workspace: at least lsp_compress_planned_workspace_bytes(m,n,r,d) bytes. */
 int lsp_compress_planned(const void* G, const void* plan,
                          int64_t m, int64_t n, int32_t r, int32_t d,

@@ -175,36 +175,40 @@ __device__ __forceinline__ void consume_pair(const uint8_t* smem, const u32x4 e,
     }
 }
 
-// Partial sums of several owners of one column meet in an LDS tile [16][r]; the tile then goes
-// out with coalesced stores.  Called by all threads of the workgroup.
+// Partial sums of several owners of one column meet in LDS: every lane parks its 16 sums at its
+// virtual column, [16][nslots * 512] floats; the first owner of a column then adds the owners'
+// sums in owner order (they sit side by side) and stores the column of T.  No atomics, so the
+// result does not depend on timing.  Called by all threads of the workgroup.
 template <int NS>
 __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* plan, const PlanHeader* H, float* __restrict__ T,
                                                   const float (&acc)[NS][kRowsGQ], int nslots, int64_t i0, int m, int r, int tid) {
-    __syncthreads();
+    __syncthreads();                                                  // the staged chunk is no longer read
     float* Tl = reinterpret_cast<float*>(smem);
-    for (int k = tid; k < kRowsGQ * r; k += kThreadsGQ) Tl[k] = 0.0f;
-    __syncthreads();
+    const int V = nslots * kThreadsGQ;
     const uint16_t* vcol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol);
+    const uint16_t* vcnt = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcnt);
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         if (s < nslots) {
-            const uint32_t col = vcol[s * kThreadsGQ + tid];
-            if (col != kNoColumn) {
-                const uint32_t bb = col & 0x7FFFu;
-                if (col & kSharedColumn) {
 #pragma unroll
-                    for (int t = 0; t < kRowsGQ; ++t) atomicAdd(&Tl[t * r + bb], acc[s][t]);
-                } else {
-#pragma unroll
-                    for (int t = 0; t < kRowsGQ; ++t) Tl[t * r + bb] = acc[s][t];
-                }
-            }
+            for (int t = 0; t < kRowsGQ; ++t) Tl[t * V + s * kThreadsGQ + tid] = acc[s][t];
         }
     }
     __syncthreads();
-    for (int k = tid; k < kRowsGQ * r; k += kThreadsGQ) {
-        const int t = k / r;
-        if (i0 + t < m) T[(i0 + t) * (int64_t)r + (k - t * r)] = Tl[k];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        if (s < nslots) {
+            const int v = s * kThreadsGQ + tid;
+            const int owners = vcnt[v];
+            if (owners > 0) {
+                const uint32_t bb = vcol[v] & 0x7FFFu;
+                for (int t = 0; t < kRowsGQ; ++t) {
+                    float sum = Tl[t * V + v];
+                    for (int o = 1; o < owners; ++o) sum += Tl[t * V + v + o];
+                    if (i0 + t < m) stream_store(&T[(i0 + t) * (int64_t)r + bb], sum);
+                }
+            }
+        }
     }
 }
 

@@ -41,7 +41,8 @@ __host__ __device__ static inline uint32_t chunk_col_offset(uint32_t j) {
 // chunks, so the lane can keep its partial sums in registers.  A column whose list of (column j of
 // G, value) pairs is longer than list_cap inside some chunk gets several owners ("virtual
 // columns"), each taking an equal share of the list in every chunk; the owners' sums are added at
-// the end.  Virtual column v sits in slot v / 512, lane v % 512.  For each (chunk, slot, wave) the
+// the end, in a fixed order.  Lanes left over (r < 512) are given to the columns with the longest
+// shares, so that all lanes of the workgroup carry about the same load.  Virtual column v sits in slot v / 512, lane v % 512.  For each (chunk, slot, wave) the
 // 64 lists are padded to a common length (a multiple of kSegBatch) with pairs that point at an
 // always-zero LDS unit, and stored lane-interleaved two rows at a time: rows 2p and 2p+1 form
 // 64 x (LDS offset, value bits, LDS offset, value bits), one 128-bit load per lane.
@@ -68,10 +69,11 @@ struct PlanHeader {            // first 256 bytes of the plan buffer
     uint64_t off_p_item;       // RowItem[p_nitems]
     uint64_t off_p_ent;        // uint2[m*d]                         (row i, value bits)
     uint64_t total_bytes;
-    uint64_t pad2[6];
+    uint64_t off_q_vcnt;       // uint16[nslots * 512]               owners of the column if this is its first owner, else 0
+    uint64_t pad2[5];
 };
 static_assert(sizeof(PlanHeader) == 192, "PlanHeader layout");
-constexpr uint32_t kPlanMagic = 0x4C535035u;   // "LSP5"
+constexpr uint32_t kPlanMagic = 0x4C535036u;   // "LSP6"
 constexpr size_t   kPlanHeaderBytes = 256;
 
 struct RowItem   { int32_t a; int32_t start; int32_t len; int32_t atomic; };

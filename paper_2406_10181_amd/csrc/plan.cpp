@@ -7,6 +7,7 @@
 // arithmetic on G, W or S.
 #include <algorithm>
 #include <cstring>
+#include <utility>
 #include <vector>
 
 #include "lsp_internal.h"
@@ -31,13 +32,14 @@ size_t plan_max_items(int64_t m, int32_t r, int32_t d) {
 }
 
 namespace {
-struct Layout { size_t off_q_seg, off_q_vcol, off_q_rows, off_p_item, off_p_ent, total; };
+struct Layout { size_t off_q_seg, off_q_vcol, off_q_vcnt, off_q_rows, off_p_item, off_p_ent, total; };
 Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
     Layout L;
     const size_t nchunks = (size_t)((n + kChunk - 1) / kChunk);
     size_t o = kPlanHeaderBytes;
     L.off_q_seg  = o; o = align_up(o + nchunks * kMaxSlots * kWavesGQ * sizeof(uint32_t), 256);
     L.off_q_vcol = o; o = align_up(o + (size_t)kMaxSlots * kThreadsGQ * sizeof(uint16_t), 256);
+    L.off_q_vcnt = o; o = align_up(o + (size_t)kMaxSlots * kThreadsGQ * sizeof(uint16_t), 256);
     L.off_q_rows = o; o = align_up(o + plan_max_rows(n, r, d) * kWave * sizeof(uint2), 256);
     L.off_p_item = o; o = align_up(o + plan_max_items(m, r, d) * sizeof(RowItem), 256);
     L.off_p_ent  = o; o = align_up(o + (size_t)(m * d) * sizeof(uint2), 256);
@@ -75,15 +77,39 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
                     uint2{chunk_col_offset((uint32_t)(j - j0)), float_bits(Q_val[j * d + k])};
             }
     }
-    // owners per column: enough that no owner's share exceeds `cap` in any chunk
-    std::vector<int32_t> owners((size_t)r, 1), first_v((size_t)r + 1, 0);
+    // owners per column: enough that no owner's share exceeds `cap` in any chunk; lanes left over
+    // go, one at a time, to the column whose owners currently have the longest share (as long as
+    // that share is at least 64 pairs)
+    std::vector<int32_t> owners((size_t)r, 1), first_v((size_t)r + 1, 0), longest_of((size_t)r, 0);
+    int64_t vneed = 0;
     for (int b = 0; b < r; ++b) {
         int32_t longest = 0;
         for (int c = 0; c < nchunks; ++c)
             longest = std::max(longest, start[(size_t)c][(size_t)b + 1] - start[(size_t)c][(size_t)b]);
+        longest_of[(size_t)b] = longest;
         owners[(size_t)b] = std::max(1, (longest + cap - 1) / cap);
-        first_v[(size_t)b + 1] = first_v[(size_t)b] + owners[(size_t)b];
+        vneed += owners[(size_t)b];
     }
+    if (vneed < kThreadsGQ) {
+        auto share_of = [&](int b) { return (double)longest_of[(size_t)b] / owners[(size_t)b]; };
+        std::vector<std::pair<double, int>> heap;
+        for (int b = 0; b < r; ++b) heap.emplace_back(share_of(b), -b);           // ties: lower column first
+        std::make_heap(heap.begin(), heap.end());
+        int64_t spare = kThreadsGQ - vneed;
+        while (spare > 0 && !heap.empty()) {
+            std::pop_heap(heap.begin(), heap.end());
+            const int b = -heap.back().second;
+            if (share_of(b) < 8.0 * kSegBatch) {                  // short lists: the merge would cost more than it saves
+                heap.pop_back();
+                continue;
+            }
+            owners[(size_t)b]++;
+            --spare;
+            heap.back().first = share_of(b);
+            std::push_heap(heap.begin(), heap.end());
+        }
+    }
+    for (int b = 0; b < r; ++b) first_v[(size_t)b + 1] = first_v[(size_t)b] + owners[(size_t)b];
     const int V = first_v[(size_t)r];
     if (V > kMaxSlots * kThreadsGQ) return LSP_ERR_SKEW;
     const int nslots = std::max(1, (V + kThreadsGQ - 1) / kThreadsGQ);
@@ -92,7 +118,7 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
     PlanHeader* H = reinterpret_cast<PlanHeader*>(out);
     H->magic = kPlanMagic; H->m = (int32_t)m; H->n = (int32_t)n; H->r = r; H->d = d; H->nchunks = nchunks;
     H->nslots = nslots; H->nvcols = V; H->list_cap = cap;
-    H->off_q_seg = L.off_q_seg; H->off_q_vcol = L.off_q_vcol; H->off_q_rows = L.off_q_rows;
+    H->off_q_seg = L.off_q_seg; H->off_q_vcol = L.off_q_vcol; H->off_q_vcnt = L.off_q_vcnt; H->off_q_rows = L.off_q_rows;
     H->off_p_item = L.off_p_item; H->off_p_ent = L.off_p_ent; H->total_bytes = L.total;
 
     uint32_t* seg  = reinterpret_cast<uint32_t*>(out + L.off_q_seg);
@@ -104,9 +130,12 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
             const int v = first_v[(size_t)b] + o;
             v_col[(size_t)v] = b; v_own[(size_t)v] = o;
         }
-    for (size_t v = 0; v < v_col.size(); ++v)
+    uint16_t* vcnt = reinterpret_cast<uint16_t*>(out + L.off_q_vcnt);
+    for (size_t v = 0; v < v_col.size(); ++v) {
         vcol[v] = v_col[v] < 0 ? (uint16_t)kNoColumn
                                : (uint16_t)((uint32_t)v_col[v] | (owners[(size_t)v_col[v]] > 1 ? kSharedColumn : 0u));
+        vcnt[v] = (v_col[v] >= 0 && v_own[v] == 0) ? (uint16_t)owners[(size_t)v_col[v]] : (uint16_t)0;
+    }
 
     // share of owner o of column b in chunk c: [lo, hi) inside the chunk's sorted list of b
     auto share = [&](int c, int b, int o, int32_t& lo, int32_t& hi) {

@@ -13,6 +13,7 @@ import paper_2406_10181_amd as L
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CHUNK = 2048
+THREADS = 512           # threads of the T = G Q kernel
 PAD_OFFSET = CHUNK * 16
 
 
@@ -106,7 +107,7 @@ def _replay_plan(buf, pb):
     slot, each segment's length from the table; lane l of wave w in slot s owns virtual column
     s*512 + w*64 + l."""
     hdr32 = buf[:48].view(np.int32)
-    assert hdr32[0] == 0x4C535035
+    assert hdr32[0] == 0x4C535036
     m, n, r, d, nchunks, nslots, nvcols, total_rows, nitems, any_split, cap = [int(x) for x in hdr32[1:12]]
     assert (m, n, r, d) == (pb.m, pb.n, pb.r, pb.d) and nchunks == -(-n // CHUNK)
     assert 1 <= nslots <= 4 and nvcols <= nslots * 512
@@ -133,6 +134,20 @@ def _replay_plan(buf, pb):
                     assert (c & 0x7FFF) < r
                     owners.setdefault(c & 0x7FFF, []).append(bool(c & 0x8000))
     assert sorted(owners) == list(range(r)), "every column has an owner"
+    # the owners of a column sit side by side; the first one carries their number, the others 0
+    o_vcnt = int(buf[144:152].view(np.uint64)[0])
+    vcnt = buf[o_vcnt:o_vcnt + nslots * THREADS * 2].view(np.uint16)
+    flat = vcol.reshape(-1)
+    v = 0
+    while v < flat.size:
+        if flat[v] == 0xFFFF:
+            assert vcnt[v] == 0
+            v += 1
+            continue
+        k = int(vcnt[v])
+        assert k == len(owners[int(flat[v]) & 0x7FFF]) and k >= 1
+        assert all((int(flat[v + o]) & 0x7FFF) == (int(flat[v]) & 0x7FFF) and (o == 0 or vcnt[v + o] == 0) for o in range(k))
+        v += k
     assert all(all(f) == (len(f) > 1) and (all(f) or not any(f)) for f in owners.values()), \
         "a column is flagged shared exactly when it has several owners"
     assert any_shared == int(any(len(f) > 1 for f in owners.values()))
