@@ -629,13 +629,32 @@ __global__ __launch_bounds__(kThreadsB) void k_compress_pt8(const CompressGroup 
     const bool live = ql < sq && b4 < (r >> 2);
     const float* Tcol = T + (live ? b4 * 4 : 0);
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll 8
-    for (int e = grp_e; e < it.len; e += NG) {
-        const uint2 en = ent[e];
-        const float v = __uint_as_float(en.y);
-        const f32x4 x = *reinterpret_cast<const f32x4*>(Tcol + (int64_t)en.x * r);
-        acc.x = fmaf(v, x.x, acc.x); acc.y = fmaf(v, x.y, acc.y);
-        acc.z = fmaf(v, x.z, acc.z); acc.w = fmaf(v, x.w, acc.w);
+    // The piece's entries are loaded once, 64 at a time (one per lane), and handed to the groups by
+    // lane exchange, so that the loads of T do not each wait for a load of their entry and can
+    // all be in flight together.
+    for (int base = 0; base < it.len; base += kWave) {
+        const int e_mine = base + lane;
+        const uint2 mine = e_mine < it.len ? ent[e_mine] : make_uint2(0u, 0u);
+        const int steps = (min(it.len - base, (int)kWave) + NG - 1) / NG;      // uniform over the wave
+        constexpr int kBlock = 16;                                              // loads of T in flight per lane
+        for (int k0 = 0; k0 < steps; k0 += kBlock) {
+            f32x4 x[kBlock];
+            float v[kBlock];
+#pragma unroll
+            for (int k = 0; k < kBlock; ++k) {
+                const int src = min((k0 + k) * NG + grp_e, (int)kWave - 1);     // lane holding entry base + (k0+k)*NG + grp
+                const uint32_t row = (uint32_t)__shfl((int)mine.x, src);
+                v[k] = __uint_as_float((uint32_t)__shfl((int)mine.y, src));
+                const bool on = k0 + k < steps && (k0 + k) * NG + grp_e < kWave;
+                if (!on) v[k] = 0.0f;
+                x[k] = *reinterpret_cast<const f32x4*>(Tcol + (int64_t)(on ? row : 0u) * r);
+            }
+#pragma unroll
+            for (int k = 0; k < kBlock; ++k) {
+                acc.x = fmaf(v[k], x[k].x, acc.x); acc.y = fmaf(v[k], x[k].y, acc.y);
+                acc.z = fmaf(v[k], x[k].z, acc.z); acc.w = fmaf(v[k], x[k].w, acc.w);
+            }
+        }
     }
 #pragma unroll
     for (int step = LG; step < kWave; step *= 2) {            // group g adds group g ^ (step / LG)
