@@ -11,8 +11,8 @@ streams (default priority), joined at the end of the step; --grouped 0 issues on
 instead.  The roofline legs time each kernel family alone, one call per matrix, on one stream.  All inputs are resident in
 HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
 
-Prints ONE JSON line: throughput in algorithmic GB/s (bytes the method must move, see
-the design doc) with a roofline object for the dominant kernel and the CPU oracle timed on a bounded
+Prints ONE JSON line: throughput in algorithmic GB/s (the bytes the method must move: G once for
+compress, W read and written for decompress-apply, plus the projector arrays and S) with a roofline object for the dominant kernel and the CPU oracle timed on a bounded
 sample beside it.
 """
 from __future__ import annotations
@@ -201,7 +201,7 @@ def main():
         "decompress_apply": {"GB/s": round(deco_gbs, 1), "pct_of_hbm_peak": round(100 * deco_gbs / HBM_PEAK_GBS, 2),
                              "ms_per_pass": round(ms_deco, 4)},
         # dominant by GPU time: the two kernels of one compress call, timed together (one API call)
-        "roofline": {"kernel": "k_compress_gq + k_compress_pt (one lsp_compress_planned call)", "bound": "hbm",
+        "roofline": {"kernel": "k_compress_gq16<bf16> + k_compress_pt8 (one lsp_compress_planned call)", "bound": "hbm",
                      "achieved": round(comp_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(comp_gbs / HBM_PEAK_GBS, 4), "traffic": traffic_c,
                      "launches": nlaunch, "avg_launch_us": round(ms_comp * 1e3 / nlaunch, 2),
