@@ -8,7 +8,8 @@ visited layer by layer in backward order; every matrix gets one lsp_compress_pla
 independent: by default they go out as one grouped call per kernel family
 (lsp_compress_planned_grouped, lsp_decompress_apply_grouped), layers alternating over --streams HIP
 streams (default priority), joined at the end of the step; --grouped 0 issues one call per matrix
-instead.  The roofline legs time each kernel family alone, one call per matrix, on one stream.  All inputs are resident in
+instead.  The roofline legs time each kernel family alone on one stream: the grouped calls of the
+step back to back, and (reported beside them) one call per matrix.  All inputs are resident in
 HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
 
 Prints ONE JSON line: throughput in algorithmic GB/s (the bytes the method must move: G once for
@@ -126,6 +127,15 @@ def main():
             L.lsp_compress_planned_grouped(citems[li], 7, r, d, code, q)
             L.lsp_decompress_apply_grouped(aitems[li], 7, r, d, code, q)
 
+    def grouped_pass(which, ns=None):
+        ns = nstreams if ns is None else ns
+        for li in range(len(layers)):
+            q = lanes[li % ns]
+            if which == "c":
+                L.lsp_compress_planned_grouped(citems[li], 7, r, d, code, q)
+            else:
+                L.lsp_decompress_apply_grouped(aitems[li], 7, r, d, code, q)
+
     def forked(fn):
         # side streams start after everything already queued on the main stream and are joined
         # back into it, so events recorded on the main stream bracket all the work
@@ -168,6 +178,13 @@ def main():
     ms_comp = timed(lambda: compress_all(mats), sub)
     ms_deco = timed(lambda: decompress_all(mats), sub)
 
+    ms_gcomp = timed(lambda: forked(lambda: grouped_pass("c")), sub)
+    ms_gdeco = timed(lambda: forked(lambda: grouped_pass("d")), sub)
+    # roofline legs: the grouped launches of the step, back to back on one stream, so that the time
+    # per launch is the kernels' own duration
+    ms_gcomp1 = timed(lambda: grouped_pass("c", 1), sub)
+    ms_gdeco1 = timed(lambda: grouped_pass("d", 1), sub)
+
     cbytes = sum(e["cb"] for e in mats)
     dbytes = sum(e["db"] for e in mats)
     value = (cbytes + dbytes) / (ms_step * 1e-3) / 1e9
@@ -200,17 +217,28 @@ def main():
                      "ms_per_pass": round(ms_comp, 4)},
         "decompress_apply": {"GB/s": round(deco_gbs, 1), "pct_of_hbm_peak": round(100 * deco_gbs / HBM_PEAK_GBS, 2),
                              "ms_per_pass": round(ms_deco, 4)},
-        # dominant by GPU time: the two kernels of one compress call, timed together (one API call)
-        "roofline": {"kernel": "k_compress_gq16<bf16> + k_compress_pt8 (one lsp_compress_planned call)", "bound": "hbm",
-                     "achieved": round(comp_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(comp_gbs / HBM_PEAK_GBS, 4), "traffic": traffic_c,
-                     "launches": nlaunch, "avg_launch_us": round(ms_comp * 1e3 / nlaunch, 2),
-                     "algorithmic_bytes_per_launch_avg": int(cbytes / nlaunch)},
-        "roofline_decompress": {"kernel": "k_decompress<bf16,d=8,r<=512>", "bound": "hbm",
-                                "achieved": round(deco_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                "frac": round(deco_gbs / HBM_PEAK_GBS, 4), "traffic": traffic_d,
-                                "launches": nlaunch, "avg_launch_us": round(ms_deco * 1e3 / nlaunch, 2),
-                                "algorithmic_bytes_per_launch_avg": int(dbytes / nlaunch)},
+        # the same two passes issued as in the step (grouped calls on the streams)
+        "grouped": {"compress_ms_per_pass": round(ms_gcomp, 4), "compress_GB/s": round(cbytes / (ms_gcomp * 1e-3) / 1e9, 1),
+                    "decompress_ms_per_pass": round(ms_gdeco, 4),
+                    "decompress_GB/s": round(dbytes / (ms_gdeco * 1e-3) / 1e9, 1)},
+        # dominant by GPU time: the two kernels of one grouped compress call (seven matrices), timed
+        # together (one API call) on one stream
+        "roofline": {"kernel": "k_compress_gq16<bf16> + k_compress_pt8 (one lsp_compress_planned_grouped call, 7 matrices)",
+                     "bound": "hbm", "achieved": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None if traffic_c is None else 7 * traffic_c,
+                     "launches": len(layers), "avg_launch_us": round(ms_gcomp1 * 1e3 / len(layers), 2),
+                     "algorithmic_bytes_per_launch_avg": int(cbytes / len(layers)),
+                     "per_matrix_calls": {"achieved": round(comp_gbs, 1), "frac": round(comp_gbs / HBM_PEAK_GBS, 4),
+                                          "avg_launch_us": round(ms_comp * 1e3 / nlaunch, 2), "traffic": traffic_c}},
+        "roofline_decompress": {"kernel": "k_decompress<bf16,d=8,r<=512> (one lsp_decompress_apply_grouped call, 7 matrices)",
+                                "bound": "hbm", "achieved": round(dbytes / (ms_gdeco1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                                "unit": "GB/s", "frac": round(dbytes / (ms_gdeco1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                "traffic": None if traffic_d is None else 7 * traffic_d,
+                                "launches": len(layers), "avg_launch_us": round(ms_gdeco1 * 1e3 / len(layers), 2),
+                                "algorithmic_bytes_per_launch_avg": int(dbytes / len(layers)),
+                                "per_matrix_calls": {"achieved": round(deco_gbs, 1), "frac": round(deco_gbs / HBM_PEAK_GBS, 4),
+                                                     "avg_launch_us": round(ms_deco * 1e3 / nlaunch, 2), "traffic": traffic_d}},
         "setup_s": round(setup_s, 1),
     }
 
