@@ -191,14 +191,16 @@ def main():
     comp_gbs = cbytes / (ms_comp * 1e-3) / 1e9
     deco_gbs = dbytes / (ms_deco * 1e-3) / 1e9
 
-    def traffic_of(fname):
+    def traffic_of(fname, key):
         tpath = os.path.join(ROOT, "profiles", fname)
         try:
-            return json.load(open(tpath)).get("hbm_bytes_per_launch")
+            return json.load(open(tpath)).get(key)
         except Exception:
             return None
-    traffic_c = traffic_of("traffic_compress_cfg4.json")
-    traffic_d = traffic_of("traffic_decompress_cfg4.json")
+    traffic_c = traffic_of("traffic_compress_cfg4.json", "hbm_bytes_per_launch")
+    traffic_d = traffic_of("traffic_decompress_cfg4.json", "hbm_bytes_per_launch")
+    traffic_gc = traffic_of("traffic_compress_cfg4.json", "hbm_bytes_per_grouped_launch")
+    traffic_gd = traffic_of("traffic_decompress_cfg4.json", "hbm_bytes_per_grouped_launch")
 
     nlaunch = len(mats)
     out = {
@@ -226,7 +228,7 @@ def main():
         "roofline": {"kernel": "k_compress_gq16<bf16> + k_compress_pt8 (one lsp_compress_planned_grouped call, 7 matrices)",
                      "bound": "hbm", "achieved": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": None if traffic_c is None else 7 * traffic_c,
+                     "traffic": traffic_gc,
                      "launches": len(layers), "avg_launch_us": round(ms_gcomp1 * 1e3 / len(layers), 2),
                      "algorithmic_bytes_per_launch_avg": int(cbytes / len(layers)),
                      "per_matrix_calls": {"achieved": round(comp_gbs, 1), "frac": round(comp_gbs / HBM_PEAK_GBS, 4),
@@ -234,7 +236,7 @@ def main():
         "roofline_decompress": {"kernel": "k_decompress<bf16,d=8,r<=512> (one lsp_decompress_apply_grouped call, 7 matrices)",
                                 "bound": "hbm", "achieved": round(dbytes / (ms_gdeco1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                                 "unit": "GB/s", "frac": round(dbytes / (ms_gdeco1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                                "traffic": None if traffic_d is None else 7 * traffic_d,
+                                "traffic": traffic_gd,
                                 "launches": len(layers), "avg_launch_us": round(ms_gdeco1 * 1e3 / len(layers), 2),
                                 "algorithmic_bytes_per_launch_avg": int(dbytes / len(layers)),
                                 "per_matrix_calls": {"achieved": round(deco_gbs, 1), "frac": round(deco_gbs / HBM_PEAK_GBS, 4),
