@@ -180,13 +180,13 @@ __device__ __forceinline__ void consume_pair(const uint8_t* smem, const u32x4 e,
 // sums in owner order (they sit side by side) and stores the column of T.  No atomics, so the
 // result does not depend on timing.  Called by all threads of the workgroup.
 template <int NS>
-__device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* plan, const PlanHeader* H, float* __restrict__ T,
+__device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* plan, PlanHeaderPtr H, float* __restrict__ T,
                                                   const float (&acc)[NS][kRowsGQ], int nslots, int64_t i0, int m, int r, int tid) {
     __syncthreads();                                                  // the staged chunk is no longer read
     float* Tl = reinterpret_cast<float*>(smem);
     const int V = nslots * kThreadsGQ;
-    const uint16_t* vcol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol);
-    const uint16_t* vcnt = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcnt);
+    const auto* vcol = as_const<uint16_t>(plan + H->off_q_vcol);
+    const auto* vcnt = as_const<uint16_t>(plan + H->off_q_vcnt);
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         if (s < nslots) {
@@ -217,13 +217,13 @@ __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* 
 // across chunk boundaries; a chunk boundary only costs the two barriers around the staging.
 template <typename D, bool VEC>
 __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
-                                            const uint8_t* __restrict__ plan, const PlanHeader* H,
+                                            const uint8_t* __restrict__ plan, PlanHeaderPtr H,
                                             float* __restrict__ T, int64_t i0, int m, int n, int r,
                                             int tid, int lane, int wave) {
     const int nchunks = H->nchunks;
-    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg) + wave;
+    const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
     const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
-    const uint32_t mycol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol)[tid];
+    const uint32_t mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
 
     // Ring of kPrefetch batches with fixed register slots: slot k is consumed, then refilled with
     // the batch kPrefetch further on.  (Shifting the ring instead would make every iteration wait
@@ -303,12 +303,12 @@ __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* s
 // General case (up to kMaxSlots columns per lane): slot by slot inside each chunk, one batch ahead.
 template <typename D, bool VEC>
 __device__ __attribute__((noinline)) void gq_any_slots(ChunkStager<D, VEC> stg, uint8_t* smem, const typename D::elem* __restrict__ G,
-                                             const uint8_t* __restrict__ plan, const PlanHeader* H,
+                                             const uint8_t* __restrict__ plan, PlanHeaderPtr H,
                                              float* __restrict__ T, int64_t i0, int m, int n, int r,
                                              int tid, int lane, int wave) {
     const int nchunks = H->nchunks;
     const int nslots = H->nslots;
-    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg);
+    const auto* seg = as_const<uint32_t>(plan + H->off_q_seg);
     const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
 
     float acc[kMaxSlots][kPlanes][4];
@@ -432,13 +432,13 @@ __device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][kP
 
 template <typename D>
 __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
-                                              const uint8_t* __restrict__ plan, const PlanHeader* H,
+                                              const uint8_t* __restrict__ plan, PlanHeaderPtr H,
                                               float* __restrict__ T, int64_t i0, int m, int n, int r,
                                               int tid, int lane, int wave) {
     const int nchunks = H->nchunks;
-    const uint32_t* seg = reinterpret_cast<const uint32_t*>(plan + H->off_q_seg) + wave;
+    const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
     const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
-    const uint32_t mycol = reinterpret_cast<const uint16_t*>(plan + H->off_q_vcol)[tid];
+    const uint32_t mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
 
     // ring of kPrefetch batches of plan rows in fixed register slots (see gq_one_slot)
     u32x4 ring[kPrefetch][kBatchLoads];
@@ -515,19 +515,19 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
 template <typename D>
 __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r) {
     extern __shared__ __align__(16) uint8_t smem[];
-    const int prob = group_find(grp.first_gq, grp.count, (int)blockIdx.x);
-    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(grp.G[prob]);
-    const uint8_t* __restrict__ plan = grp.plan[prob];
-    float* __restrict__ T = grp.T[prob];
-    float* __restrict__ S = grp.S[prob];
-    const int m = grp.m[prob], n = grp.n[prob];
-    const int block = (int)blockIdx.x - grp.first_gq[prob], nblocks = grp.first_gq[prob + 1] - grp.first_gq[prob];
+    const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
+    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
+    const uint8_t* __restrict__ plan = pr.plan;
+    float* __restrict__ T = pr.T;
+    float* __restrict__ S = pr.S;
+    const int m = pr.m, n = pr.n;
+    const int block = pr.block_gq, nblocks = pr.nblocks_gq;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t i0 = (int64_t)block * kRowsGQ;
 
-    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    PlanHeaderPtr H = as_const<PlanHeader>(plan);
     if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
     if (H->p_any_split) {
         const int64_t total = (int64_t)r * r;
@@ -548,13 +548,13 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
 template <typename D, bool VEC>
 __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup grp, int r) {
     extern __shared__ __align__(16) uint8_t smem[];
-    const int prob = group_find(grp.first_gq, grp.count, (int)blockIdx.x);
-    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(grp.G[prob]);
-    const uint8_t* __restrict__ plan = grp.plan[prob];
-    float* __restrict__ T = grp.T[prob];
-    float* __restrict__ S = grp.S[prob];
-    const int m = grp.m[prob], n = grp.n[prob];
-    const int block = (int)blockIdx.x - grp.first_gq[prob], nblocks = grp.first_gq[prob + 1] - grp.first_gq[prob];
+    const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
+    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
+    const uint8_t* __restrict__ plan = pr.plan;
+    float* __restrict__ T = pr.T;
+    float* __restrict__ S = pr.S;
+    const int m = pr.m, n = pr.n;
+    const int block = pr.block_gq, nblocks = pr.nblocks_gq;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -563,7 +563,7 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup 
     ChunkStager<D, VEC> stg;
     stg.fetch(G, i0, m, n, 0, tid);                                   // depends on nothing but the arguments
 
-    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    PlanHeaderPtr H = as_const<PlanHeader>(plan);
     if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
     // S must start at zero only when some row of P^T was cut into pieces (kernel B then adds).
     if (H->p_any_split) {
@@ -581,15 +581,16 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup 
 constexpr int kThreadsB = 256;
 constexpr int kStripeQuads = 64;                              // column quads (float4) per stripe
 __global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup grp, int r, int nstripes) {
-    const int prob = group_find(grp.first_pt, grp.count, (int)blockIdx.x);
-    const uint8_t* __restrict__ plan = grp.plan[prob];
-    const float* __restrict__ T = grp.T[prob];
-    float* __restrict__ S = grp.S[prob];
-    const int block = (int)blockIdx.x - grp.first_pt[prob];
-    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    const CompressProblem pr = group_pick(grp, (int)blockIdx.x, true);
+    const uint8_t* __restrict__ plan = pr.plan;
+    const float* __restrict__ T = pr.T;
+    float* __restrict__ S = pr.S;
+    const int block = pr.block_pt;
+    PlanHeaderPtr H = as_const<PlanHeader>(plan);
     const int stripe = block % nstripes, item = block / nstripes;
     if (item >= H->p_nitems) return;
-    const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[item];
+    const auto* itp = as_const<int32_t>(plan + H->off_p_item) + 4 * item;    // RowItem, field by field
+    const RowItem it{itp[0], itp[1], itp[2], itp[3]};
     const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
     for (int b = stripe * kStripeQuads * 4 + threadIdx.x; b < min(r, (stripe + 1) * kStripeQuads * 4); b += kThreadsB) {
         float acc = 0.0f;
@@ -612,16 +613,17 @@ __global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup g
 template <int LG>
 __global__ __launch_bounds__(kThreadsB) void k_compress_pt8(const CompressGroup grp, int r, int sq) {
     constexpr int NG = kWave / LG;                            // entry groups per wave
-    const int prob = group_find(grp.first_pt, grp.count, (int)blockIdx.x);
-    const uint8_t* __restrict__ plan = grp.plan[prob];
-    const float* __restrict__ T = grp.T[prob];
-    float* __restrict__ S = grp.S[prob];
-    const int block = (int)blockIdx.x - grp.first_pt[prob];
-    const PlanHeader* H = reinterpret_cast<const PlanHeader*>(plan);
+    const CompressProblem pr = group_pick(grp, (int)blockIdx.x, true);
+    const uint8_t* __restrict__ plan = pr.plan;
+    const float* __restrict__ T = pr.T;
+    float* __restrict__ S = pr.S;
+    const int block = pr.block_pt;
+    PlanHeaderPtr H = as_const<PlanHeader>(plan);
     const int stripe = block & 7;
     const int item = (block >> 3) * (kThreadsB / kWave) + (int)(threadIdx.x >> 6);
     if (item >= H->p_nitems) return;
-    const RowItem it = reinterpret_cast<const RowItem*>(plan + H->off_p_item)[item];
+    const auto* itp = as_const<int32_t>(plan + H->off_p_item) + 4 * item;    // RowItem, field by field
+    const RowItem it{itp[0], itp[1], itp[2], itp[3]};
     const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
     const int lane = threadIdx.x & 63;
     const int grp_e = lane / LG, ql = lane % LG;

@@ -119,11 +119,42 @@ struct ApplyGroup {
 };
 
 #if defined(__HIPCC__)
+// The problem that owns workgroup `block`, picked with compile-time indices only: indexing the
+// by-value group with a run-time index would make the compiler copy it to scratch memory and turn
+// every address derived from it into a per-lane (vector) value, so that the small uniform loads of
+// the kernels (plan header, segment table) would go through the vector memory path and wait for
+// all the data loads in flight.  Everything returned is wave-uniform and lives in scalar registers.
+struct CompressProblem { const void* G; const uint8_t* plan; float* T; float* S; int32_t m, n, block_gq, nblocks_gq, block_pt; };
+__device__ __forceinline__ CompressProblem group_pick(const CompressGroup& g, int block, bool kernel_b) {
+    CompressProblem o{g.G[0], g.plan[0], g.T[0], g.S[0], g.m[0], g.n[0], block, g.first_gq[1], block};
+#pragma unroll
+    for (int p = 1; p < kMaxGroup; ++p) {
+        const bool hit = p < g.count && block >= (kernel_b ? g.first_pt[p] : g.first_gq[p]);
+        if (hit) {
+            o.G = g.G[p]; o.plan = g.plan[p]; o.T = g.T[p]; o.S = g.S[p]; o.m = g.m[p]; o.n = g.n[p];
+            o.block_gq = block - g.first_gq[p]; o.nblocks_gq = g.first_gq[p + 1] - g.first_gq[p];
+            o.block_pt = block - g.first_pt[p];
+        }
+    }
+    return o;
+}
 // index of the problem that owns workgroup `block` (uniform; count <= kMaxGroup)
 __device__ __forceinline__ int group_find(const int32_t* first, int count, int block) {
     int p = 0;
     while (p + 1 < count && block >= first[p + 1]) ++p;
     return p;
+}
+struct ApplyProblem { void* W; const float* S; const int32_t* P_idx; const float* P_val; const int32_t* Q_idx; const float* Q_val; int32_t m, n, block; };
+__device__ __forceinline__ ApplyProblem group_pick(const ApplyGroup& g, int block) {
+    ApplyProblem o{g.W[0], g.S[0], g.P_idx[0], g.P_val[0], g.Q_idx[0], g.Q_val[0], g.m[0], g.n[0], block};
+#pragma unroll
+    for (int p = 1; p < kMaxGroup; ++p) {
+        if (p < g.count && block >= g.first[p]) {
+            o.W = g.W[p]; o.S = g.S[p]; o.P_idx = g.P_idx[p]; o.P_val = g.P_val[p]; o.Q_idx = g.Q_idx[p]; o.Q_val = g.Q_val[p];
+            o.m = g.m[p]; o.n = g.n[p]; o.block = block - g.first[p];
+        }
+    }
+    return o;
 }
 #endif
 
@@ -169,6 +200,16 @@ template <typename V> __device__ __forceinline__ void stream_store(V* p, const V
     else if constexpr (sizeof(V) == 8) { u32x2 t; __builtin_memcpy(&t, &v, 8); __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p)); }
     else { u32x4 t; __builtin_memcpy(&t, &v, 16); __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p)); }
 }
+
+// Read-only tables of the plan (header, segment lengths, column tables) are read through the
+// constant address space: the kernels never write the plan, and a uniform load from that address
+// space is a scalar load, which does not share the counter (and the waits) of the vector loads
+// that stream G and the plan rows.
+#define LSP_CONST_AS __attribute__((address_space(4)))
+template <typename T> __device__ __forceinline__ const LSP_CONST_AS T* as_const(const void* p) {
+    return (const LSP_CONST_AS T*)(uintptr_t)p;
+}
+typedef const LSP_CONST_AS PlanHeader* PlanHeaderPtr;
 
 template <typename D> __device__ __forceinline__ float widen(typename D::elem x);
 template <> __device__ __forceinline__ float widen<F32>(float x) { return x; }
