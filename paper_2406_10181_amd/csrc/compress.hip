@@ -430,23 +430,33 @@ __device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][kP
     }
 }
 
+// One workgroup walks `nblk` consecutive blocks of 16 rows (several when the grid is big: the first
+// chunk of the next block is fetched and staged while the last chunk of the current one is
+// consumed, and the stores of T go out under the next block's work, so that the set-up and the
+// tail of a block cost nothing but for the first and the last one).
 template <typename D>
 __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
                                               const uint8_t* __restrict__ plan, PlanHeaderPtr H,
-                                              float* __restrict__ T, int64_t i0, int m, int n, int r,
+                                              float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
                                               int tid, int lane, int wave) {
     const int nchunks = H->nchunks;
     const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
-    const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+    const u32x4* rp0 = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+    const u32x4* rp = rp0;
     const uint32_t mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
+    const bool shared = H->q_any_shared != 0;
 
     // ring of kPrefetch batches of plan rows in fixed register slots (see gq_one_slot)
     u32x4 ring[kPrefetch][kBatchLoads];
+    auto ring_restart = [&]() {
+        rp = rp0;
 #pragma unroll
-    for (int k = 0; k < kPrefetch; ++k)
+        for (int k = 0; k < kPrefetch; ++k)
 #pragma unroll
-        for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
-    rp += (size_t)kPrefetch * kBatchLoads * kWave;
+            for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
+        rp += (size_t)kPrefetch * kBatchLoads * kWave;
+    };
+    ring_restart();
 
     float acc[1][kRowsGQ];
 #pragma unroll
@@ -468,10 +478,11 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
         rp += (size_t)kBatchLoads * kWave;
     };
 
-    stg.stage(smem, 0, tid);                                          // chunk 0 (fetched by the caller)
+    stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
     __syncthreads();
-    int rot = 0;
-    for (int c = 0; c < nchunks; ++c) {
+    int rot = 0, c = 0, blk = 0;
+    const int units = nblk * nchunks;                                 // (row block, chunk) pairs, in order
+    for (int u = 0; u < units; ++u) {
         if (rot != 0) {                                               // undo the slot rotation left by the previous chunk
             u32x4 t[kPrefetch][kBatchLoads];
 #pragma unroll
@@ -488,8 +499,10 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
                 for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = t[k][q];
         }
         static_assert(kPrefetch == 4, "the rotation above is written for four slots");
-        if (c + 1 < nchunks) stg.fetch(G, i0, m, n, c + 1, tid);      // lands while this chunk is consumed
-        buf = smem + (c & 1) * kBufStride16;
+        const bool last_chunk = c + 1 == nchunks;
+        if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * kRowsGQ, m, n, last_chunk ? 0 : c + 1, tid);
+        buf = smem + (u & 1) * kBufStride16;
         const int nb = (int)(seg[c * kWavesGQ] / kSegBatch);
         for (int g = nb / kPrefetch; g > 0; --g) {
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
@@ -498,22 +511,31 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
         if (rot > 0) step(ring[0]);
         if (rot > 1) step(ring[1]);
         if (rot > 2) step(ring[2]);
-        if (c + 1 < nchunks) stg.stage(smem, (c + 1) & 1, tid);       // the other buffer: nobody reads it now
-        __syncthreads();                                              // chunk c+1 is staged; chunk c is no longer read
-    }
-
-    if (H->q_any_shared) {
-        write_tile_shared<1>(smem, plan, H, T, acc, 1, i0, m, r, tid);
-    } else if (mycol != kNoColumn) {
+        if (last_chunk) {                                             // the block's 16 sums per column are complete
+            const int64_t ib = i0 + (int64_t)blk * kRowsGQ;
+            if (u + 1 < units) { ring_restart(); rot = 0; }           // the stream starts over; in flight during the stores
+            if (shared) {
+                write_tile_shared<1>(smem, plan, H, T, acc, 1, ib, m, r, tid);   // uses the LDS of a buffer nobody reads now
+                if (u + 1 < units) __syncthreads();                   // before that LDS is staged into again
+            } else if (mycol != kNoColumn) {
 #pragma unroll
-        for (int t = 0; t < kRowsGQ; ++t)
-            if (i0 + t < m) stream_store(&T[(i0 + t) * (int64_t)r + mycol], acc[0][t]);
+                for (int t = 0; t < kRowsGQ; ++t)
+                    if (ib + t < m) stream_store(&T[(ib + t) * (int64_t)r + mycol], acc[0][t]);
+            }
+#pragma unroll
+            for (int t = 0; t < kRowsGQ; ++t) acc[0][t] = 0.0f;
+            c = 0; ++blk;
+        } else {
+            ++c;
+        }
+        if (u + 1 < units) stg.stage(smem, (u + 1) & 1, tid);         // the other buffer: nobody reads it now
+        __syncthreads();                                              // the next chunk is staged; this one is no longer read
     }
 }
 
 // Kernel A for fp16 / bf16 with n % 8 == 0.
 template <typename D>
-__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r) {
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r, int blocks_per_wg) {
     extern __shared__ __align__(16) uint8_t smem[];
     const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
     const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
@@ -525,7 +547,8 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t i0 = (int64_t)block * kRowsGQ;
+    const int64_t i0 = (int64_t)block * blocks_per_wg * kRowsGQ;
+    const int nblk = min(blocks_per_wg, (int)((m - i0 + kRowsGQ - 1) / kRowsGQ));   // row blocks of this workgroup
 
     PlanHeaderPtr H = as_const<PlanHeader>(plan);
     if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
@@ -537,11 +560,18 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
     if (H->nslots == 1) {
         ChunkStager16 stg;
         stg.fetch(G, i0, m, n, 0, tid);
-        gq16_one_slot<D>(stg, smem, G, plan, H, T, i0, m, n, r, tid, lane, wave);
+        gq16_one_slot<D>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
     } else {
-        ChunkStager<D, true> stg;
-        stg.fetch(G, i0, m, n, 0, tid);
-        gq_any_slots<D, true>(stg, smem, G, plan, H, T, i0, m, n, r, tid, lane, wave);
+        for (int b = 0; b < nblk; ++b) {                              // the general path takes one block at a time
+            if (b > 0) {
+                __syncthreads();
+                if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            const int64_t ib = i0 + (int64_t)b * kRowsGQ;
+            ChunkStager<D, true> stg;
+            stg.fetch(G, ib, m, n, 0, tid);
+            gq_any_slots<D, true>(stg, smem, G, plan, H, T, ib, m, n, r, tid, lane, wave);
+        }
     }
 }
 
@@ -726,33 +756,51 @@ bool compress_group_uniform(const CompressGroup& g) {
     return true;
 }
 
+// Row blocks per workgroup of kernel A: several on big grids (grouped calls) of the 16-bit kernel
+static int gq_blocks_per_wg(const CompressGroup& g, lsp_dtype dtype) {
+    if (dtype == LSP_F32 || g.n[0] % 8 != 0) return 1;
+    int64_t blocks = 0;
+    for (int p = 0; p < g.count; ++p) blocks += (g.m[p] + kRowsGQ - 1) / kRowsGQ;
+    return blocks >= 1024 ? 2 : 1;
+}
+
 template <typename D>
-static hipError_t launch_gq(const CompressGroup& g, int32_t r, hipStream_t st) {
+static hipError_t launch_gq(const CompressGroup& g, int32_t r, int blocks_per_wg, hipStream_t st) {
     const size_t lds = (size_t)kPlanes * kPlaneStride;       // >= 64 r bytes for every supported r
     const bool vec = (g.n[0] % 8) == 0;
-    void (*kern)(const CompressGroup, int);
-    if constexpr (D::size == 2) kern = vec ? k_compress_gq16<D> : k_compress_gq<D, false>;
-    else                        kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const unsigned grid = (unsigned)g.first_gq[g.count];
+    hipError_t e;
+    if constexpr (D::size == 2) {
+        if (vec) {
+            auto kern = k_compress_gq16<D>;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsGQ), lds, st, g, (int)r, blocks_per_wg);
+            return hipGetLastError();
+        }
+    }
+    auto kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)g.first_gq[g.count]), dim3(kThreadsGQ), lds, st, g, (int)r);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsGQ), lds, st, g, (int)r);
     return hipGetLastError();
 }
 
 hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
     const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
     const bool striped = (r % 4) == 0;
+    const int bpw = gq_blocks_per_wg(g, dtype);
     g.first_gq[0] = g.first_pt[0] = 0;
     for (int p = 0; p < g.count; ++p) {
-        g.first_gq[p + 1] = g.first_gq[p] + (g.m[p] + kRowsGQ - 1) / kRowsGQ;
+        g.first_gq[p + 1] = g.first_gq[p] + (int32_t)(((g.m[p] + kRowsGQ - 1) / kRowsGQ + bpw - 1) / bpw);
         const int32_t items = (int32_t)plan_max_items(g.m[p], r, d);
         g.first_pt[p + 1] = g.first_pt[p] + (striped ? ((items + 3) / 4) * 8 : items * nstripes);
     }
     hipError_t e;
     switch (dtype) {
-        case LSP_F32:  e = launch_gq<F32>(g, r, st); break;
-        case LSP_F16:  e = launch_gq<F16>(g, r, st); break;
-        default:       e = launch_gq<BF16>(g, r, st); break;
+        case LSP_F32:  e = launch_gq<F32>(g, r, bpw, st); break;
+        case LSP_F16:  e = launch_gq<F16>(g, r, bpw, st); break;
+        default:       e = launch_gq<BF16>(g, r, bpw, st); break;
     }
     if (e != hipSuccess) return e;
     const unsigned blocks = (unsigned)g.first_pt[g.count];
