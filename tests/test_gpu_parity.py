@@ -207,6 +207,14 @@ def test_grouped_calls_fall_back_when_kernel_variants_differ():
     _grouped_case(pbs)
 
 
+def test_big_grid_with_ragged_last_row_block():
+    # 1027 blocks of 16 rows (the last one with 5 rows): the big-grid geometry of both kernels (several row
+    # blocks per workgroup in compress, 32-row workgroups in decompress) with an odd block count and a ragged tail
+    pb = syn.make_problem("big_ragged", 16 * 1026 + 5, 2048, 512, 4, "bf16", seed=921)
+    _grouped_case([pb])
+    _full_check(pb, raw=False)
+
+
 def test_grouped_layer_of_config4():
     # the seven matrices of one layer of the 6.7B-style stack, at full size, as bench.py launches them:
     # sampled rows against the oracle, everything bit for bit against the single calls
