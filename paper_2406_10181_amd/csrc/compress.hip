@@ -212,6 +212,27 @@ __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* 
     }
 }
 
+// Hands the 16 partial sums of every virtual column from the lane that walked its list in one
+// chunk to the lane that walks it in the next (`from`, `to`: virtual columns of this thread; the
+// plan deals the lists of each chunk to the waves by length).  They pass through the first 32 KB
+// of `area`, the LDS of the chunk consumed last: the first barrier makes sure nobody reads that
+// chunk any more (and publishes whatever was written to other LDS before the call), the last one
+// that the area may be staged into again.  Called by all threads.
+__device__ __forceinline__ void swap_owner(uint8_t* area, float (&acc)[16], uint32_t from, uint32_t to) {
+    f32x4* X = reinterpret_cast<f32x4*>(area);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        X[q * kThreadsGQ + from] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};   // lanes spread over all banks
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f32x4 a = X[q * kThreadsGQ + to];
+        acc[4 * q] = a[0]; acc[4 * q + 1] = a[1]; acc[4 * q + 2] = a[2]; acc[4 * q + 3] = a[3];
+    }
+    __syncthreads();
+}
+
 // Common case: every lane owns at most one column (nslots == 1).  The wave's plan stream is
 // consumed as one flat sequence of batches, kPrefetch batches deep in registers, running ahead
 // across chunk boundaries; a chunk boundary only costs the two barriers around the staging.
@@ -224,6 +245,8 @@ __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* s
     const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
     const u32x4* rp = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
     const uint32_t mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
+    const uint16_t* __restrict__ perm = reinterpret_cast<const uint16_t*>(plan + H->off_q_perm) + tid;
+    uint32_t walked = perm[0];                                        // virtual column whose list this thread walks
 
     // Ring of kPrefetch batches with fixed register slots: slot k is consumed, then refilled with
     // the batch kPrefetch further on.  (Shifting the ring instead would make every iteration wait
@@ -264,6 +287,7 @@ __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* s
         stg.stage(smem, tid);
         __syncthreads();
         if (c + 1 < nchunks) stg.fetch(G, i0, m, n, c + 1, tid);
+        const uint32_t next = c + 1 < nchunks ? (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ] : (uint32_t)tid;
         if (rot != 0) {
             u32x4 t[kPrefetch][kBatchLoads];
 #pragma unroll
@@ -288,6 +312,9 @@ __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* s
         if (rot > 0) step(ring[0]);
         if (rot > 1) step(ring[1]);
         if (rot > 2) step(ring[2]);
+        // the sums move to the lanes that walk the columns next; after the last chunk, home (thread t: column t)
+        swap_owner(smem, reinterpret_cast<float(&)[kRowsGQ]>(acc), walked, next);   // through the LDS of the chunk just consumed
+        walked = next;
     }
     if (H->q_any_shared) {
         write_tile_shared<1>(smem, plan, H, T, reinterpret_cast<const float(&)[1][kRowsGQ]>(acc), 1, i0, m, r, tid);
@@ -445,6 +472,9 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
     const u32x4* rp = rp0;
     const uint32_t mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
     const bool shared = H->q_any_shared != 0;
+    const uint16_t* __restrict__ perm = reinterpret_cast<const uint16_t*>(plan + H->off_q_perm) + tid;
+    const uint32_t first = perm[0];
+    uint32_t walked = first;                                          // virtual column whose list this thread walks
 
     // ring of kPrefetch batches of plan rows in fixed register slots (see gq_one_slot)
     u32x4 ring[kPrefetch][kBatchLoads];
@@ -500,36 +530,56 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
         }
         static_assert(kPrefetch == 4, "the rotation above is written for four slots");
         const bool last_chunk = c + 1 == nchunks;
+        const uint32_t next = last_chunk ? (uint32_t)tid : (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ];
         if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
             stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * kRowsGQ, m, n, last_chunk ? 0 : c + 1, tid);
         buf = smem + (u & 1) * kBufStride16;
+        const bool more = u + 1 < units;
+        // The next chunk is staged (into the buffer nobody reads now) in the middle of this one's
+        // work rather than at its end, where every wave would wait for it; only a block's last
+        // chunk with shared columns stages later, behind the merge that uses the same LDS.
+        const bool stage_early = more && !(last_chunk && shared);
         const int nb = (int)(seg[c * kWavesGQ] / kSegBatch);
-        for (int g = nb / kPrefetch; g > 0; --g) {
+        const int groups = nb / kPrefetch, before = groups < 2 ? groups : 2;
+        for (int g = before; g > 0; --g) {
+            step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
+        }
+        if (stage_early) stg.stage(smem, (u + 1) & 1, tid);
+        for (int g = groups - before; g > 0; --g) {
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
         }
         rot = nb % kPrefetch;
         if (rot > 0) step(ring[0]);
         if (rot > 1) step(ring[1]);
         if (rot > 2) step(ring[2]);
-        if (last_chunk) {                                             // the block's 16 sums per column are complete
+        // The sums move to the lanes that walk the columns in the next chunk; after the last chunk
+        // of a block they go home (thread t: virtual column t) and out to T.
+        if (last_chunk && more) { ring_restart(); rot = 0; }          // the stream starts over; in flight during the stores
+        swap_owner(smem + (u & 1) * kBufStride16, acc[0], walked, next);
+        if (last_chunk) {
             const int64_t ib = i0 + (int64_t)blk * kRowsGQ;
-            if (u + 1 < units) { ring_restart(); rot = 0; }           // the stream starts over; in flight during the stores
             if (shared) {
-                write_tile_shared<1>(smem, plan, H, T, acc, 1, ib, m, r, tid);   // uses the LDS of a buffer nobody reads now
-                if (u + 1 < units) __syncthreads();                   // before that LDS is staged into again
+                write_tile_shared<1>(smem, plan, H, T, acc, 1, ib, m, r, tid);   // uses the LDS of the first chunk buffer
+                if (more) {
+                    __syncthreads();                                  // before that LDS is staged into again
+                    stg.stage(smem, (u + 1) & 1, tid);
+                    __syncthreads();
+                }
             } else if (mycol != kNoColumn) {
 #pragma unroll
                 for (int t = 0; t < kRowsGQ; ++t)
                     if (ib + t < m) stream_store(&T[(ib + t) * (int64_t)r + mycol], acc[0][t]);
             }
+        }
+        if (last_chunk) {                                             // the block's sums are out
 #pragma unroll
             for (int t = 0; t < kRowsGQ; ++t) acc[0][t] = 0.0f;
             c = 0; ++blk;
+            walked = first;
         } else {
             ++c;
+            walked = next;
         }
-        if (u + 1 < units) stg.stage(smem, (u + 1) & 1, tid);         // the other buffer: nobody reads it now
-        __syncthreads();                                              // the next chunk is staged; this one is no longer read
     }
 }
 

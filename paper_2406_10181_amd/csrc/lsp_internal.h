@@ -17,7 +17,7 @@ constexpr int kWave       = 64;    // gfx950 wavefront
 constexpr int kThreadsGQ  = 512;   // threads of the T = G Q kernel: one lane per (virtual) column of T
 constexpr int kWavesGQ    = kThreadsGQ / kWave;
 constexpr int kMaxSlots   = 4;     // a lane owns at most this many virtual columns
-constexpr int kSegBatch   = 8;     // segment lengths are multiples of this many rows
+constexpr int kSegBatch   = 4;     // segment lengths are multiples of this many rows
 constexpr int kPrefetch   = 4;     // batches of plan rows a wave holds in registers (one consumed, the rest in flight)
 constexpr int kStreamSlack = kPrefetch * kSegBatch;   // readable padding rows after the last segment
 constexpr int kRowPiece   = 256;   // a row list of P^T longer than this is cut into pieces
@@ -37,12 +37,18 @@ __host__ __device__ static inline uint32_t chunk_col_offset(uint32_t j) {
 // Plan: column-sorted projector copies, laid out for the compress kernels.
 // All offsets are bytes from the start of the plan buffer and multiples of 16.
 //
-// Q part.  Every column b of T = G Q is owned by one lane of the 512-thread workgroup, for all
-// chunks, so the lane can keep its partial sums in registers.  A column whose list of (column j of
+// Q part.  Every column b of T = G Q is owned by one lane of the 512-thread workgroup, which keeps
+// the column's partial sums in registers.  A column whose list of (column j of
 // G, value) pairs is longer than list_cap inside some chunk gets several owners ("virtual
 // columns"), each taking an equal share of the list in every chunk; the owners' sums are added at
 // the end, in a fixed order.  Lanes left over (r < 512) are given to the columns with the longest
-// shares, so that all lanes of the workgroup carry about the same load.  Virtual column v sits in slot v / 512, lane v % 512.  For each (chunk, slot, wave) the
+// shares, so that all lanes of the workgroup carry about the same load.  Virtual column v sits in
+// slot v / 512, lane v % 512 -- except that with one slot (q_permuted) the lane that walks a
+// column's list changes from chunk to chunk: inside each chunk the 512 lists are dealt to the waves
+// by length, longest first (a wave is as slow as its longest list, so lists of like length go
+// together; the two waves that share a SIMD get a long and a short group), and the kernel hands
+// the partial sums from lane to lane between chunks.  q_perm[c][t] is the virtual column that
+// thread t walks in chunk c.  For each (chunk, slot, wave) the
 // 64 lists are padded to a common length (a multiple of kSegBatch) with pairs that point at an
 // always-zero LDS unit, and stored lane-interleaved two rows at a time: rows 2p and 2p+1 form
 // 64 x (LDS offset, value bits, LDS offset, value bits), one 128-bit load per lane.
@@ -61,7 +67,8 @@ struct PlanHeader {            // first 256 bytes of the plan buffer
     int32_t  list_cap;         // longest list a lane walks in one chunk
     uint32_t q_stream_row[kWavesGQ];   // first row of each wave's stream
     int32_t  q_any_shared;     // 1 if some column of T has several owners
-    uint32_t pad[3];
+    int32_t  q_permuted;       // 1 if the owner of a virtual column changes per chunk (q_perm; one slot only)
+    uint32_t pad[2];
     // section offsets
     uint64_t off_q_seg;        // uint32[nchunks][nslots][kWavesGQ]  rows of each segment
     uint64_t off_q_vcol;       // uint16[nslots * 512]               column b (| kSharedColumn) or kNoColumn
@@ -70,10 +77,11 @@ struct PlanHeader {            // first 256 bytes of the plan buffer
     uint64_t off_p_ent;        // uint2[m*d]                         (row i, value bits)
     uint64_t total_bytes;
     uint64_t off_q_vcnt;       // uint16[nslots * 512]               owners of the column if this is its first owner, else 0
-    uint64_t pad2[5];
+    uint64_t off_q_perm;       // uint16[nchunks][512]               virtual column walked by thread t in chunk c
+    uint64_t pad2[4];
 };
 static_assert(sizeof(PlanHeader) == 192, "PlanHeader layout");
-constexpr uint32_t kPlanMagic = 0x4C535036u;   // "LSP6"
+constexpr uint32_t kPlanMagic = 0x4C535037u;   // "LSP7"
 constexpr size_t   kPlanHeaderBytes = 256;
 
 struct RowItem   { int32_t a; int32_t start; int32_t len; int32_t atomic; };

@@ -32,7 +32,7 @@ size_t plan_max_items(int64_t m, int32_t r, int32_t d) {
 }
 
 namespace {
-struct Layout { size_t off_q_seg, off_q_vcol, off_q_vcnt, off_q_rows, off_p_item, off_p_ent, total; };
+struct Layout { size_t off_q_seg, off_q_vcol, off_q_vcnt, off_q_perm, off_q_rows, off_p_item, off_p_ent, total; };
 Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
     Layout L;
     const size_t nchunks = (size_t)((n + kChunk - 1) / kChunk);
@@ -40,6 +40,7 @@ Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
     L.off_q_seg  = o; o = align_up(o + nchunks * kMaxSlots * kWavesGQ * sizeof(uint32_t), 256);
     L.off_q_vcol = o; o = align_up(o + (size_t)kMaxSlots * kThreadsGQ * sizeof(uint16_t), 256);
     L.off_q_vcnt = o; o = align_up(o + (size_t)kMaxSlots * kThreadsGQ * sizeof(uint16_t), 256);
+    L.off_q_perm = o; o = align_up(o + nchunks * kThreadsGQ * sizeof(uint16_t), 256);
     L.off_q_rows = o; o = align_up(o + plan_max_rows(n, r, d) * kWave * sizeof(uint2), 256);
     L.off_p_item = o; o = align_up(o + plan_max_items(m, r, d) * sizeof(RowItem), 256);
     L.off_p_ent  = o; o = align_up(o + (size_t)(m * d) * sizeof(uint2), 256);
@@ -99,7 +100,7 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
         while (spare > 0 && !heap.empty()) {
             std::pop_heap(heap.begin(), heap.end());
             const int b = -heap.back().second;
-            if (share_of(b) < 8.0 * kSegBatch) {                  // short lists: the merge would cost more than it saves
+            if (share_of(b) < 64.0) {                             // short lists: the merge would cost more than it saves
                 heap.pop_back();
                 continue;
             }
@@ -118,7 +119,7 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
     PlanHeader* H = reinterpret_cast<PlanHeader*>(out);
     H->magic = kPlanMagic; H->m = (int32_t)m; H->n = (int32_t)n; H->r = r; H->d = d; H->nchunks = nchunks;
     H->nslots = nslots; H->nvcols = V; H->list_cap = cap;
-    H->off_q_seg = L.off_q_seg; H->off_q_vcol = L.off_q_vcol; H->off_q_vcnt = L.off_q_vcnt; H->off_q_rows = L.off_q_rows;
+    H->off_q_seg = L.off_q_seg; H->off_q_vcol = L.off_q_vcol; H->off_q_vcnt = L.off_q_vcnt; H->off_q_perm = L.off_q_perm; H->off_q_rows = L.off_q_rows;
     H->off_p_item = L.off_p_item; H->off_p_ent = L.off_p_ent; H->total_bytes = L.total;
 
     uint32_t* seg  = reinterpret_cast<uint32_t*>(out + L.off_q_seg);
@@ -150,14 +151,41 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
     int any_shared = 0;
     for (int b = 0; b < r; ++b) any_shared |= owners[(size_t)b] > 1;
     H->q_any_shared = any_shared;
+    // With one slot the lists of a chunk are dealt to the waves by length: sorted longest first, the
+    // k-th group of 64 goes to wave k for k < 4 and to wave 11 - k otherwise, so that the two waves
+    // of a SIMD (w and w + 4) get a long and a short group.  walker[c][t]: virtual column of thread t.
+    const bool permuted = nslots == 1;
+    H->q_permuted = permuted ? 1 : 0;
+    uint16_t* perm = reinterpret_cast<uint16_t*>(out + L.off_q_perm);
+    std::vector<int32_t> order((size_t)kThreadsGQ), length((size_t)kThreadsGQ);
+    for (int c = 0; c < nchunks; ++c) {
+        for (int v = 0; v < kThreadsGQ; ++v) {
+            order[(size_t)v] = v;
+            int32_t lo = 0, hi = 0;
+            if (permuted && v_col[(size_t)v] >= 0) share(c, v_col[(size_t)v], v_own[(size_t)v], lo, hi);
+            length[(size_t)v] = hi - lo;
+        }
+        if (permuted)
+            std::stable_sort(order.begin(), order.end(),
+                             [&](int32_t x, int32_t y) { return length[(size_t)x] > length[(size_t)y]; });
+        for (int k = 0; k < kWavesGQ; ++k) {
+            const int w = k < kWavesGQ / 2 ? k : kWavesGQ + kWavesGQ / 2 - 1 - k;
+            for (int lane = 0; lane < kWave; ++lane)
+                perm[(size_t)c * kThreadsGQ + (size_t)w * kWave + (size_t)lane] = (uint16_t)order[(size_t)k * kWave + (size_t)lane];
+        }
+    }
     size_t row = 0;
     for (int w = 0; w < kWavesGQ; ++w) {
         H->q_stream_row[w] = (uint32_t)row;
         for (int c = 0; c < nchunks; ++c)
             for (int s = 0; s < nslots; ++s) {
+                auto walked = [&](int lane) {
+                    return permuted ? (size_t)perm[(size_t)c * kThreadsGQ + (size_t)w * kWave + (size_t)lane]
+                                    : (size_t)s * kThreadsGQ + (size_t)w * kWave + (size_t)lane;
+                };
                 int32_t longest = 0;
                 for (int lane = 0; lane < kWave; ++lane) {
-                    const size_t v = (size_t)s * kThreadsGQ + (size_t)w * kWave + (size_t)lane;
+                    const size_t v = walked(lane);
                     if (v_col[v] < 0) continue;
                     int32_t lo, hi; share(c, v_col[v], v_own[v], lo, hi);
                     longest = std::max(longest, hi - lo);
@@ -165,7 +193,7 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
                 const int32_t len = (int32_t)align_up((size_t)longest, kSegBatch);
                 seg[((size_t)c * nslots + (size_t)s) * kWavesGQ + (size_t)w] = (uint32_t)len;
                 for (int lane = 0; lane < kWave; ++lane) {
-                    const size_t v = (size_t)s * kThreadsGQ + (size_t)w * kWave + (size_t)lane;
+                    const size_t v = walked(lane);
                     int32_t lo = 0, hi = 0;
                     if (v_col[v] >= 0) share(c, v_col[v], v_own[v], lo, hi);
                     for (int32_t e = 0; e < len; ++e)

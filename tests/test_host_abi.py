@@ -15,6 +15,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CHUNK = 2048
 THREADS = 512           # threads of the T = G Q kernel
 PAD_OFFSET = CHUNK * 16
+BATCH = 4                # segment lengths are multiples of this many plan rows
+SLACK = 4 * BATCH        # readable rows behind each wave's stream (the kernel's prefetch depth)
 
 
 def test_every_declared_symbol_is_exported():
@@ -104,10 +106,10 @@ def _build_host_plan(pb):
 def _replay_plan(buf, pb):
     """What the plan means: T = G Qhat from the Q part, then S = Phat^T T from the P part.
     The Q streams are walked exactly as the kernel walks them: wave by wave, chunk-major, slot by
-    slot, each segment's length from the table; lane l of wave w in slot s owns virtual column
-    s*512 + w*64 + l."""
+    slot, each segment's length from the table; lane l of wave w in slot s walks the list of virtual
+    column s*512 + w*64 + l, or, with one slot, of the virtual column the per-chunk table names."""
     hdr32 = buf[:48].view(np.int32)
-    assert hdr32[0] == 0x4C535036
+    assert hdr32[0] == 0x4C535037
     m, n, r, d, nchunks, nslots, nvcols, total_rows, nitems, any_split, cap = [int(x) for x in hdr32[1:12]]
     assert (m, n, r, d) == (pb.m, pb.n, pb.r, pb.d) and nchunks == -(-n // CHUNK)
     assert 1 <= nslots <= 4 and nvcols <= nslots * 512
@@ -122,6 +124,13 @@ def _replay_plan(buf, pb):
     rows = buf[o_rows:o_rows + total_rows * 64 * 8].view(np.uint32).reshape(total_rows // 2, 64, 2, 2)
     rows = np.ascontiguousarray(rows.transpose(0, 2, 1, 3)).reshape(total_rows, 64, 2)
     any_shared = int(buf[80:84].view(np.int32)[0])
+    permuted = int(buf[84:88].view(np.int32)[0])
+    o_perm = int(buf[152:160].view(np.uint64)[0])
+    perm = buf[o_perm:o_perm + nchunks * THREADS * 2].view(np.uint16).reshape(nchunks, 8, 64)
+    assert permuted == int(nslots == 1) and o_perm % 16 == 0
+    if permuted:
+        for c in range(nchunks):
+            assert sorted(perm[c].reshape(-1).tolist()) == list(range(THREADS)), "every virtual column is walked by one thread"
     G = syn.storage_to_f64(pb.G, pb.dtype)
     T = np.zeros((m, r))
     nent = 0
@@ -151,15 +160,16 @@ def _replay_plan(buf, pb):
     assert all(all(f) == (len(f) > 1) and (all(f) or not any(f)) for f in owners.values()), \
         "a column is flagged shared exactly when it has several owners"
     assert any_shared == int(any(len(f) > 1 for f in owners.values()))
+    longest = np.zeros((nchunks, 8), dtype=np.int64)   # longest real list of each (chunk, wave), one slot
     for w in range(8):
         p = stream_row[w]
         for c in range(nchunks):
             for s in range(nslots):
                 ln = int(seg[c, s, w])
-                assert ln % 8 == 0 and ln <= -(-cap // 8) * 8
+                assert ln % BATCH == 0 and ln <= -(-cap // BATCH) * BATCH
                 ent = rows[p:p + ln]
                 for lane in range(64):
-                    col = int(vcol[s, w, lane])
+                    col = int(vcol[0].reshape(-1)[perm[c, w, lane]]) if permuted else int(vcol[s, w, lane])
                     for e in range(ln):
                         off = int(ent[e, lane, 0])
                         v = float(ent[e, lane, 1:2].view(np.float32)[0])
@@ -167,17 +177,25 @@ def _replay_plan(buf, pb):
                         if off == PAD_OFFSET:
                             assert v == 0.0
                             continue
+                        if nslots == 1:
+                            longest[c, w] = max(longest[c, w], e + 1)
                         assert col != 0xFFFF
                         j = c * CHUNK + _decode_col(off)
                         assert j < n
                         T[:, col & 0x7FFF] += v * G[:, j]
                         nent += 1
                 p += ln
-        # the kernel prefetches four batches past the end of the stream: 32 harmless rows follow
-        assert p + 32 <= total_rows and (w == 7 or p + 32 <= stream_row[w + 1])
-        tail = rows[p:p + 32]
+        # the kernel prefetches four batches past the end of the stream: harmless rows follow
+        assert p + SLACK <= total_rows and (w == 7 or p + SLACK <= stream_row[w + 1])
+        tail = rows[p:p + SLACK]
         assert np.all(tail[:, :, 0] == PAD_OFFSET) and np.all(tail[:, :, 1] == 0)
     assert nent == n * d
+    if permuted:
+        # the lists of a chunk are dealt by length: waves 0,1,2,3,7,6,5,4 get ever shorter ones, and
+        # no segment is padded by a whole batch
+        dealt = longest[:, [0, 1, 2, 3, 7, 6, 5, 4]]
+        assert np.all(np.diff(dealt, axis=1) <= 0)
+        assert np.all(seg[:, 0, :] - longest < BATCH)
     items = buf[o_item:o_item + nitems * 16].view(np.int32).reshape(nitems, 4)
     pent = buf[o_pent:o_pent + m * d * 8].view(np.uint32).reshape(m * d, 2)
     S = np.zeros((r, r))
