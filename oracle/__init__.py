@@ -1,8 +1,9 @@
-"""CPU oracle for the LSP compress / decompress-apply path.  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for the LSP compress / decompress-apply path and the estimation bias.  TEST INFRASTRUCTURE ONLY.
 
 Thin ctypes wrapper around ``lsp_oracle.c`` (plain fp64 loops written from the paper's
 two formulas: the compress step S = P^T G Q and the decompress-and-apply step
-W <- W - P S Q^T of Alg. 1 / Alg. 3 with the (d,r)-sparse projectors of Def. 1).
+W <- W - P S Q^T of Alg. 1 / Alg. 3 with the (d,r)-sparse projectors of Def. 1, and the
+estimation bias of Def. 2).
 
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
 may import this package.  It imports nothing from the HIP package and the HIP package
@@ -51,6 +52,8 @@ def _load():
         lib.lsp_oracle_decompress_apply_mt.argtypes = lib.lsp_oracle_decompress_apply.argtypes + [i32]
         lib.lsp_oracle_decompress_rows.argtypes = [vp, i32, vp] + proj + [i64, i64, i32, i32, vp, i64, vp]
         lib.lsp_oracle_compress_entries.argtypes = [vp, i32] + proj + [i64, i64, i32, i32, vp, vp, i64, vp]
+        lib.lsp_oracle_bias.argtypes = [vp, i32] + proj + [i64, i64, i32, i32, vp]
+        lib.lsp_oracle_bias_dense.argtypes = lib.lsp_oracle_bias.argtypes
         lib.lsp_oracle_round_to_storage.argtypes = [ctypes.c_double, i32]
         lib.lsp_oracle_round_to_storage.restype = ctypes.c_double
         lib.lsp_oracle_widen.argtypes = [vp, i64, i32]
@@ -130,6 +133,23 @@ def decompress_apply(W, dtype, S, P_idx, P_val, Q_idx, Q_val, *, dense: bool = F
     if rc != 0:
         raise RuntimeError(f"oracle decompress_apply failed rc={rc}")
     return Wp, Wr
+
+
+def estimation_bias(G, dtype, P_idx, P_val, Q_idx, Q_val, r: int, *, dense: bool = False) -> Tuple[float, float]:
+    """Def. 2: returns (||P P^T G Q Q^T - G||_F^2, ||G||_F^2) in float64; the bias is the square root of
+    their ratio.  dense=True forms P P^T and Q Q^T as dense matrices first (tiny inputs)."""
+    lib = _load()
+    m, n = G.shape
+    d = P_idx.shape[1]
+    G = _storage(G, dtype, (m, n))
+    P_idx, P_val = _proj(P_idx, P_val, m, r, d)
+    Q_idx, Q_val = _proj(Q_idx, Q_val, n, r, d)
+    out = np.zeros(2, dtype=np.float64)
+    fn = lib.lsp_oracle_bias_dense if dense else lib.lsp_oracle_bias
+    rc = fn(_p(G), DTYPE_CODE[dtype], _p(P_idx), _p(P_val), _p(Q_idx), _p(Q_val), m, n, r, d, _p(out))
+    if rc != 0:
+        raise RuntimeError(f"oracle estimation_bias failed rc={rc}")
+    return float(out[0]), float(out[1])
 
 
 def decompress_rows(W, dtype, S, P_idx, P_val, Q_idx, Q_val, rows: Sequence[int]) -> np.ndarray:

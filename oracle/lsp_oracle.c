@@ -14,6 +14,9 @@
  *                                                the projected gradient of a layer
  *   decompress-apply  W <- W - P S Q^T        -- Alg. 1, "Decompress, apply deltas on GPU";
  *                                                Alg. 3, the last step of the layer loop
+ *   estimation bias   b = ||P P^T G Q Q^T - G||_F / ||G||_F
+ *                                             -- Def. 2; the quantity MaybeUpdate in Alg. 1
+ *                                                compares with its threshold alpha
  *
  * P (m x r) and Q (n x r) are (d,r)-sparse projectors in the sense of Def. 1: exactly d
  * stored entries per row, kept in ELL layout as idx[row][k] (int32 column in [0,r)) and
@@ -184,6 +187,41 @@ int lsp_oracle_decompress_apply_dense(const void *W, int dtype, const float *S,
     return 0;
 }
 
+/* Def. 2 written out:  R = (Phat Phat^T) G (Qhat Qhat^T);  out[0] = sum (R - G)^2, out[1] = sum G^2.
+ * The two projector products are formed first, as m x m and n x n matrices. */
+int lsp_oracle_bias_dense(const void *G, int dtype,
+                          const int32_t *P_idx, const float *P_val,
+                          const int32_t *Q_idx, const float *Q_val,
+                          int64_t m, int64_t n, int r, int d, double *out) {
+    double *Ph = densify(P_idx, P_val, m, r, d);
+    double *Qh = densify(Q_idx, Q_val, n, r, d);
+    double *PP = (double *)calloc((size_t)(m * m), sizeof(double));
+    double *QQ = (double *)calloc((size_t)(n * n), sizeof(double));
+    double *A  = (double *)calloc((size_t)(m * n), sizeof(double));
+    if (!Ph || !Qh || !PP || !QQ || !A) { free(Ph); free(Qh); free(PP); free(QQ); free(A); return -1; }
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t i2 = 0; i2 < m; ++i2)
+            for (int a = 0; a < r; ++a) PP[i * m + i2] += Ph[i * r + a] * Ph[i2 * r + a];
+    for (int64_t j = 0; j < n; ++j)
+        for (int64_t j2 = 0; j2 < n; ++j2)
+            for (int b = 0; b < r; ++b) QQ[j * n + j2] += Qh[j * r + b] * Qh[j2 * r + b];
+    for (int64_t i = 0; i < m; ++i)                 /* A = (P P^T) G */
+        for (int64_t j = 0; j < n; ++j)
+            for (int64_t i2 = 0; i2 < m; ++i2) A[i * n + j] += PP[i * m + i2] * load_elem(G, i2 * n + j, dtype);
+    double num = 0.0, den = 0.0;
+    for (int64_t i = 0; i < m; ++i)                 /* R = A (Q Q^T) */
+        for (int64_t j = 0; j < n; ++j) {
+            double rij = 0.0;
+            for (int64_t j2 = 0; j2 < n; ++j2) rij += A[i * n + j2] * QQ[j2 * n + j];
+            double g = load_elem(G, i * n + j, dtype);
+            num += (rij - g) * (rij - g);
+            den += g * g;
+        }
+    out[0] = num; out[1] = den;
+    free(Ph); free(Qh); free(PP); free(QQ); free(A);
+    return 0;
+}
+
 /* ---------------------------------------------------------------- working form */
 
 /* rows [i0, i1) of the compress sum, accumulated into S (which the caller zeroed).
@@ -256,6 +294,38 @@ int lsp_oracle_decompress_apply(const void *W, int dtype, const float *S,
     if (!Urow) return -1;
     decompress_rows(W, dtype, S, P_idx, P_val, Q_idx, Q_val, 0, m, n, r, d, Urow, Wprime, W_out);
     free(Urow);
+    return 0;
+}
+
+/* Def. 2 by associativity:  S = P^T G Q (fp64, not rounded), then row by row U = P S,
+ * R[i][j] = sum_k U[i][Q_idx[j][k]] Q_val[j][k];  out[0] = sum (R - G)^2, out[1] = sum G^2. */
+int lsp_oracle_bias(const void *G, int dtype,
+                    const int32_t *P_idx, const float *P_val,
+                    const int32_t *Q_idx, const float *Q_val,
+                    int64_t m, int64_t n, int r, int d, double *out) {
+    double *S = (double *)malloc((size_t)r * (size_t)r * sizeof(double));
+    double *row = (double *)malloc((size_t)r * sizeof(double));
+    if (!S || !row) { free(S); free(row); return -1; }
+    memset(S, 0, (size_t)r * (size_t)r * sizeof(double));
+    compress_rows(G, dtype, P_idx, P_val, Q_idx, Q_val, 0, m, n, r, d, row, S);
+    double num = 0.0, den = 0.0;
+    for (int64_t i = 0; i < m; ++i) {
+        for (int b = 0; b < r; ++b) row[b] = 0.0;
+        for (int k = 0; k < d; ++k) {
+            double pv = (double)P_val[i * d + k];
+            const double *Srow = S + (int64_t)P_idx[i * d + k] * r;
+            for (int b = 0; b < r; ++b) row[b] += pv * Srow[b];
+        }
+        for (int64_t j = 0; j < n; ++j) {
+            double rij = 0.0;
+            for (int k = 0; k < d; ++k) rij += row[Q_idx[j * d + k]] * (double)Q_val[j * d + k];
+            double g = load_elem(G, i * n + j, dtype);
+            num += (rij - g) * (rij - g);
+            den += g * g;
+        }
+    }
+    out[0] = num; out[1] = den;
+    free(S); free(row);
     return 0;
 }
 

@@ -356,3 +356,91 @@ def test_generators_are_deterministic_and_shaped():
     pb = syn.make_problem("t", 200, 64, 8, 2, "f16", 3, heavy_row_frac=0.01)
     rowmax = np.abs(pb.G.astype(np.float64)).max(axis=1)
     assert np.sum(rowmax > 0.02) == 2                                    # ceil(1% of 200) heavy rows
+
+
+# ---------------------------------------------------------------- estimation bias (Def. 2)
+def _bias(G, dtype, P_idx, P_val, Q_idx, Q_val, r, **kw):
+    num, den = oracle.estimation_bias(G, dtype, P_idx, P_val, Q_idx, Q_val, r, **kw)
+    return num, den
+
+
+@pytest.mark.parametrize("m,n,r,d,dist,dtype", [
+    (5, 7, 3, 2, "uniform", "f32"),
+    (12, 9, 6, 3, "uniform", "f32"),
+    (6, 6, 5, 3, "zipf", "f32"),           # duplicates certain
+    (9, 5, 6, 2, "uniform", "bf16"),
+    (8, 11, 4, 1, "uniform", "f16"),
+])
+def test_bias_working_form_equals_definition_and_numpy(m, n, r, d, dist, dtype):
+    """The working form (S = P^T G Q first, then P S Q^T) against Def. 2 with P P^T and Q Q^T formed
+    first, and both against numpy's dense products."""
+    pb = syn.make_problem("t", m, n, r, d, dtype, seed=300 + m * n, g_std=1.0, index_dist=dist)
+    nw, dw = _bias(pb.G, dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r)
+    nd, dd = _bias(pb.G, dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r, dense=True)
+    Ph, Qh = _dense(pb.P_idx, pb.P_val, r), _dense(pb.Q_idx, pb.Q_val, r)
+    G64 = syn.storage_to_f64(pb.G, dtype)
+    R = Ph @ Ph.T @ G64 @ Qh @ Qh.T
+    ref_n, ref_d = float(((R - G64) ** 2).sum()), float((G64 ** 2).sum())
+    for got_n, got_d in ((nw, dw), (nd, dd)):
+        assert abs(got_n - ref_n) <= 1e-11 * max(1.0, ref_n) and abs(got_d - ref_d) <= 1e-12 * ref_d
+
+
+def test_bias_of_selection_projectors_is_the_dropped_energy():
+    """Projectors that select rows and columns (one unit entry per row, distinct targets; the other
+    rows zero) have orthonormal columns, so P P^T G Q Q^T keeps the selected block of G and zeroes
+    the rest: the squared bias is the energy outside the block over the total energy."""
+    rng = _rng(21)
+    m, n, r = 23, 31, 7
+    G = syn.integer_matrix(m, n, -8, 8, "f32", rng)
+    rows = rng.permutation(m)[:r]; cols = rng.permutation(n)[:r]
+    P_idx = np.zeros((m, 1), dtype=np.int32); P_val = np.zeros((m, 1), dtype=np.float32)
+    Q_idx = np.zeros((n, 1), dtype=np.int32); Q_val = np.zeros((n, 1), dtype=np.float32)
+    P_idx[rows, 0] = np.arange(r); P_val[rows, 0] = 1.0
+    Q_idx[cols, 0] = rng.permutation(r); Q_val[cols, 0] = 1.0
+    num, den = _bias(G, "f32", P_idx, P_val, Q_idx, Q_val, r)
+    G64 = G.astype(np.float64)
+    kept = float((G64[np.ix_(rows, cols)] ** 2).sum())
+    assert den == float((G64 ** 2).sum())
+    assert num == den - kept                    # integers: exact
+
+
+def test_bias_closed_forms():
+    rng = _rng(22)
+    m, n = 9, 13
+    G = syn.integer_matrix(m, n, -8, 8, "f32", rng)
+    # identity projectors (r = m = n would be needed on both sides; use a square case): bias 0
+    Gs = syn.integer_matrix(6, 6, -8, 8, "f32", rng)
+    eye_i = np.arange(6, dtype=np.int32).reshape(6, 1); eye_v = np.ones((6, 1), dtype=np.float32)
+    num, den = _bias(Gs, "f32", eye_i, eye_v, eye_i, eye_v, 6)
+    assert num == 0.0 and den == float((Gs.astype(np.float64) ** 2).sum())
+    # a projector of zeros reconstructs nothing: bias exactly 1
+    r, d = 4, 2
+    P_idx = rng.integers(0, r, size=(m, d)).astype(np.int32); Q_idx = rng.integers(0, r, size=(n, d)).astype(np.int32)
+    Q_val = rng.standard_normal((n, d)).astype(np.float32)
+    num, den = _bias(G, "f32", P_idx, np.zeros((m, d), dtype=np.float32), Q_idx, Q_val, r)
+    assert num == den > 0
+    # rank one (r = 1): P P^T G Q Q^T = (p^T G q) p q^T
+    p = rng.standard_normal((m, 1)).astype(np.float32); q = rng.standard_normal((n, 1)).astype(np.float32)
+    z_m = np.zeros((m, 1), dtype=np.int32); z_n = np.zeros((n, 1), dtype=np.int32)
+    num, den = _bias(G, "f32", z_m, p, z_n, q, 1)
+    G64, p64, q64 = G.astype(np.float64), p.astype(np.float64)[:, 0], q.astype(np.float64)[:, 0]
+    s = p64 @ G64 @ q64
+    ref = float(((s * np.outer(p64, q64) - G64) ** 2).sum())
+    assert abs(num - ref) <= 1e-12 * ref
+    # the bias does not change when G is scaled (by a power of two: exactly)
+    G4 = (G * np.float32(4.0)).astype(np.float32)
+    P_val = rng.standard_normal((m, d)).astype(np.float32)
+    n1, d1 = _bias(G, "f32", P_idx, P_val, Q_idx, Q_val, r)
+    n4, d4 = _bias(G4, "f32", P_idx, P_val, Q_idx, Q_val, r)
+    assert n4 == 16.0 * n1 and d4 == 16.0 * d1
+
+
+def test_bias_a_transposed_reconstruction_is_detected():
+    """With m != n a reconstruction that swapped the roles of P and Q could not even be formed; on a
+    square case it can, and gives a different number: the pin above is not blind to it."""
+    pb = syn.make_problem("t", 8, 8, 4, 2, "f32", seed=5, g_std=1.0)
+    num, den = _bias(pb.G, "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, 4)
+    Ph, Qh = _dense(pb.P_idx, pb.P_val, 4), _dense(pb.Q_idx, pb.Q_val, 4)
+    G64 = pb.G.astype(np.float64)
+    wrong = Qh @ Qh.T @ G64 @ Ph @ Ph.T
+    assert abs(float(((wrong - G64) ** 2).sum()) - num) > 1e-3 * num
