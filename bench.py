@@ -185,6 +185,19 @@ def main():
     ms_gcomp1 = timed(lambda: grouped_pass("c", 1), sub)
     ms_gdeco1 = timed(lambda: grouped_pass("d", 1), sub)
 
+    # widening beyond the step: the estimation-bias pass (Def. 2) over every gradient of the stack,
+    # one call per matrix on one stream; S holds P^T G Q from the compress passes above
+    bias_ws_bytes = max(L.lsp_estimation_bias_workspace_bytes(e["m"], e["n"], r, d) for e in mats)
+    bias_ws = torch.empty(bias_ws_bytes, dtype=torch.uint8, device=dev)
+    bias_out = torch.zeros(3, dtype=torch.float32, device=dev)
+
+    def bias_all():
+        for e in mats:
+            L.lsp_estimation_bias(e["G"], e["S"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], e["m"], e["n"], r, d,
+                                  bias_out, bias_ws, bias_ws_bytes, code, stream)
+    ms_bias = timed(bias_all, sub)
+    bbytes = sum(e["cb"] for e in mats)             # one read of G, the projector arrays and S: as for compress
+
     cbytes = sum(e["cb"] for e in mats)
     dbytes = sum(e["db"] for e in mats)
     value = (cbytes + dbytes) / (ms_step * 1e-3) / 1e9
@@ -241,6 +254,11 @@ def main():
                                 "algorithmic_bytes_per_launch_avg": int(dbytes / len(layers)),
                                 "per_matrix_calls": {"achieved": round(deco_gbs, 1), "frac": round(deco_gbs / HBM_PEAK_GBS, 4),
                                                      "avg_launch_us": round(ms_deco * 1e3 / nlaunch, 2), "traffic": traffic_d}},
+        # next row beyond the step (not part of `value`): the bias pass of Def. 2, one call per matrix
+        "estimation_bias": {"kernel": "k_decompress<..., NORMS> + k_bias_finish (one lsp_estimation_bias call per matrix)",
+                            "ms_per_pass": round(ms_bias, 4), "GB/s": round(bbytes / (ms_bias * 1e-3) / 1e9, 1),
+                            "frac_of_hbm_peak": round(bbytes / (ms_bias * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                            "avg_call_us": round(ms_bias * 1e3 / nlaunch, 2)},
         "setup_s": round(setup_s, 1),
     }
 

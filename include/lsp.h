@@ -186,6 +186,32 @@ int lsp_decompress_apply_grouped(const lsp_apply_item* items, int32_t count,
                                  int32_t r, int32_t d, lsp_dtype dtype, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Estimation bias of the projector pair on a gradient (Def. 2):
+ *     b(P, Q; G) = || P P^T G Q Q^T - G ||_F / || G ||_F ,
+ * the quantity MaybeUpdate in Alg. 1 compares with its threshold alpha to decide whether the
+ * projectors are fitted again.  It composes the two steps above: the caller first compresses G
+ * (lsp_compress or lsp_compress_planned: S = P^T G Q, which the training step computes anyway),
+ * then this call rebuilds P S Q^T tile by tile in registers in one more streaming pass over G,
+ * subtracts G and adds up the squares; no m x n temporary exists.  fp32 arithmetic; the
+ * workgroups' sums are added in a fixed order in fp64, so the result is bit-reproducible.
+ *
+ *   G          device, m*n elements of `dtype`, row-major, read only
+ *   S          device, r*r fp32: P^T G Q of the same G and projectors, read only
+ *   out        device, 3 floats, overwritten: out[0] = || P S Q^T - G ||_F^2,
+ *              out[1] = || G ||_F^2, out[2] = sqrt(out[0] / out[1]) (NaN by IEEE rules if G = 0)
+ *   workspace  device scratch of at least lsp_estimation_bias_workspace_bytes(m,n,r,d) bytes,
+ *              16-byte aligned; contents undefined afterwards
+ * Errors as for lsp_decompress_apply, plus LSP_ERR_WORKSPACE.  Asynchronous on `stream`.
+ */
+int lsp_estimation_bias(const void* G, const float* S,
+                        const int32_t* P_idx, const float* P_val,
+                        const int32_t* Q_idx, const float* Q_val,
+                        int64_t m, int64_t n, int32_t r, int32_t d, float* out,
+                        void* workspace, size_t workspace_bytes,
+                        lsp_dtype dtype, void* stream);
+size_t lsp_estimation_bias_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+
+/* ------------------------------------------------------------------------------------------
  * Utilities.
  */
 

@@ -1,5 +1,6 @@
 """MI355X (gfx950) library for the GPU hot path of LSP-Offload: compress S = P^T G Q and
-decompress-and-apply W <- W - P S Q^T with (d,r)-sparse ELL projectors (Alg. 1 / Alg. 3, Def. 1).
+decompress-and-apply W <- W - P S Q^T with (d,r)-sparse ELL projectors (Alg. 1 / Alg. 3, Def. 1),
+and the estimation bias of Def. 2 built from the two.
 
 This package is a thin binding: it marshals torch device pointers into the C ABI declared in
 ``include/lsp.h``.  Every step of the path runs in the HIP kernels of ``liblsp_hip.so``; there is
@@ -11,6 +12,7 @@ from .binding import (  # noqa: F401
     lsp_plan_bytes, lsp_plan_build, lsp_plan_build_host,
     lsp_compress_planned, lsp_compress_planned_workspace_bytes,
     lsp_decompress_apply, lsp_compress_planned_grouped, lsp_decompress_apply_grouped,
+    lsp_estimation_bias, lsp_estimation_bias_workspace_bytes,
     lsp_compress_item, lsp_apply_item, compress_items, apply_items, lsp_validate_projector, lsp_strerror, lsp_version,
     torch_dtype_code,
 )

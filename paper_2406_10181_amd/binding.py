@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.lsp_compress_planned_grouped.restype = ctypes.c_int
         L.lsp_decompress_apply_grouped.argtypes = [vp, i32, i32, i32, i32, vp]
         L.lsp_decompress_apply_grouped.restype = ctypes.c_int
+        L.lsp_estimation_bias.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, ctypes.c_size_t, i32, vp]
+        L.lsp_estimation_bias.restype = ctypes.c_int
+        L.lsp_estimation_bias_workspace_bytes.argtypes = [i64, i64, i32, i32]
+        L.lsp_estimation_bias_workspace_bytes.restype = ctypes.c_size_t
         L.lsp_validate_projector.argtypes = [vp, i64, i32, i32, vp, vp]
         L.lsp_validate_projector.restype = ctypes.c_int
         L.lsp_strerror.argtypes = [ctypes.c_int]
@@ -168,6 +172,19 @@ def lsp_decompress_apply(W, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, dtype: in
                                     m, n, r, d, dtype, _stream(stream))
     if check:
         _check(rc, "lsp_decompress_apply")
+    return rc
+
+
+def lsp_estimation_bias_workspace_bytes(m, n, r, d) -> int:
+    return int(lib().lsp_estimation_bias_workspace_bytes(m, n, r, d))
+
+
+def lsp_estimation_bias(G, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, out, workspace, workspace_bytes,
+                        dtype: int, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_estimation_bias(_ptr(G), _ptr(S), _ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val),
+                                   m, n, r, d, _ptr(out), _ptr(workspace), workspace_bytes, dtype, _stream(stream))
+    if check:
+        _check(rc, "lsp_estimation_bias")
     return rc
 
 

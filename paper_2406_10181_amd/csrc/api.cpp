@@ -197,6 +197,34 @@ int lsp_decompress_apply(void* W, const float* S, const int32_t* P_idx, const fl
     return lsp_decompress_apply_grouped(&it, 1, r, d, dtype, stream);
 }
 
+size_t lsp_estimation_bias_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
+    if (check_shape(m, n, r, d) != LSP_OK) return 0;
+    return lsp::align_up((size_t)lsp::bias_blocks(m, r) * 2 * sizeof(float), 256);
+}
+
+int lsp_estimation_bias(const void* G, const float* S, const int32_t* P_idx, const float* P_val,
+                        const int32_t* Q_idx, const float* Q_val,
+                        int64_t m, int64_t n, int32_t r, int32_t d, float* out,
+                        void* workspace, size_t workspace_bytes, lsp_dtype dtype, void* stream) {
+    if (!G || !S || !P_idx || !P_val || !Q_idx || !Q_val || !out) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    rc = check_dtype(dtype);
+    if (rc != LSP_OK) return rc;
+    if (!workspace || workspace_bytes < lsp_estimation_bias_workspace_bytes(m, n, r, d) || !aligned16(workspace))
+        return LSP_ERR_WORKSPACE;
+    if (!aligned16(G) || !aligned16(S) || !aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val))
+        return LSP_ERR_ALIGN;
+    lsp::ApplyGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.count = 1;
+    g.W[0] = const_cast<void*>(G);                 // read only: the kernels built for the norms store nothing
+    g.S[0] = S; g.P_idx[0] = P_idx; g.P_val[0] = P_val; g.Q_idx[0] = Q_idx; g.Q_val[0] = Q_val;
+    g.m[0] = (int32_t)m; g.n[0] = (int32_t)n;
+    hipError_t e = lsp::launch_bias(g, r, d, dtype, static_cast<float*>(workspace), out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
 int lsp_validate_projector(const int32_t* idx, int64_t rows, int32_t d, int32_t r, int32_t* flag, void* stream) {
     if (!idx || !flag) return LSP_ERR_NULL;
     if (rows <= 0 || d <= 0 || r <= 0) return LSP_ERR_SHAPE;

@@ -6,6 +6,11 @@
 //            their rows of Q in registers, and for each 4-row plane gathers U with one 128-bit
 //            LDS read per pair; W is read, updated in fp32 and rounded once.
 // Bandwidth-bound (read + write of W); no matrix cores (sparse gather + fp32 FMA).
+//
+// The same kernels, built with NORMS, serve the estimation bias of Def. 2 (the test MaybeUpdate
+// makes in Alg. 1): with S = P^T G Q they rebuild P S Q^T tile by tile in registers, read G where
+// the apply step reads W, and instead of storing anything add up (P S Q^T - G)^2 and G^2; every
+// workgroup leaves its two sums in a list that k_bias_finish adds in a fixed order.
 #include "lsp_internal.h"
 
 namespace lsp {
@@ -51,6 +56,25 @@ template <typename D, int CPT> __device__ __forceinline__ Vec<D, CPT> vec_narrow
         if constexpr (CPT == 4) o.y = pair_narrow<D>(in[2], in[3]);
     }
     return o;
+}
+
+// Sums x and y over the workgroup (NT threads) and lets thread 0 store them; `red` is LDS nobody
+// else uses any more.  Fixed order: the result does not depend on timing.
+template <int NT>
+__device__ __forceinline__ void block_sum2(float x, float y, float2* red, float2* dst) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        x += __shfl_down(x, off);
+        y += __shfl_down(y, off);
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = make_float2(x, y);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float2 t = red[0];
+        for (int w = 1; w < NT / 64; ++w) { t.x += red[w].x; t.y += red[w].y; }
+        *dst = t;
+    }
 }
 
 // phase 1 (generic kernel):  Us[plane][b] (float4 = 4 rows) = sum_k P_val[i][k] S[P_idx[i][k]][b]
@@ -119,8 +143,8 @@ __device__ __forceinline__ void build_u_tile_fast(uint8_t* smem, int2* pent, con
 // folds into the immediate offset of the LDS read and a gather costs no address arithmetic.
 // All loads of a pass (the thread's rows of Q and its R x CPT patch of W) are issued before the
 // gathers start, so one pass costs one HBM round trip; many waves per CU overlap the passes.
-template <typename D, int RG, int DD, int PS, int NT, int CPT, int kDepth>
-__global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r) {
+template <typename D, int RG, int DD, int PS, int NT, int CPT, int kDepth, bool NORMS>
+__global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, float2* __restrict__ partial) {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int R = 4 * RG;
     constexpr int NE = CPT * DD;                                    // entries owned by a thread in one pass
@@ -175,6 +199,7 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r) 
         if (q >= npass) q -= npass;
         return (int64_t)q * step + (int64_t)threadIdx.x * CPT;
     };
+    float num = 0.0f, den = 0.0f;                                   // NORMS: this thread's sums of squares
     auto compute_pass = [&](const Pass& cur, int64_t j0) {
 #pragma unroll
         for (int g = 0; g < RG; ++g) {
@@ -200,9 +225,18 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r) 
                 if (i < m) {
                     float w[CPT];
                     vec_widen<D, CPT>(cur.wv[g * 4 + t], w);
+                    if constexpr (NORMS) {
 #pragma unroll
-                    for (int c = 0; c < CPT; ++c) w[c] -= acc[t][c];
-                    stream_store(reinterpret_cast<Vec<D, CPT>*>(W + i * (int64_t)n + j0), vec_narrow<D, CPT>(w));
+                        for (int c = 0; c < CPT; ++c) {
+                            const float diff = acc[t][c] - w[c];
+                            num = fmaf(diff, diff, num);
+                            den = fmaf(w[c], w[c], den);
+                        }
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < CPT; ++c) w[c] -= acc[t][c];
+                        stream_store(reinterpret_cast<Vec<D, CPT>*>(W + i * (int64_t)n + j0), vec_narrow<D, CPT>(w));
+                    }
                 }
             }
         }
@@ -234,20 +268,22 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r) 
             compute_if(p + k, slot[k]);
         }
     }
+    if constexpr (NORMS) block_sum2<NT>(num, den, reinterpret_cast<float2*>(smem), partial + blockIdx.x);
 }
 
 // Generic kernel: any n and d, one column per thread.
-template <typename D, int RG>
+template <typename D, int RG, bool NORMS>
 __global__ __launch_bounds__(kThreadsD) void k_decompress_any(typename D::elem* __restrict__ W, const float* __restrict__ S,
                                                              const int32_t* __restrict__ P_idx, const float* __restrict__ P_val,
                                                              const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
-                                                             int m, int n, int r, int d) {
+                                                             int m, int n, int r, int d, float2* __restrict__ partial) {
     extern __shared__ __align__(16) uint8_t smem[];
     float4* Us = reinterpret_cast<float4*>(smem);
     constexpr int R = 4 * RG;
     const int64_t i0 = (int64_t)blockIdx.x * R;
     build_u_tile<RG>(Us, S, P_idx, P_val, i0, m, r, d, r);
     __syncthreads();
+    float num = 0.0f, den = 0.0f;                                   // NORMS: this thread's sums of squares
     for (int64_t j = threadIdx.x; j < n; j += kThreadsD) {
         float acc[RG][4];
 #pragma unroll
@@ -269,9 +305,37 @@ __global__ __launch_bounds__(kThreadsD) void k_decompress_any(typename D::elem* 
                 const int64_t i = i0 + g * 4 + t;
                 if (i < m) {
                     typename D::elem* p = W + i * (int64_t)n + j;
-                    *p = narrow<D>(widen<D>(*p) - acc[g][t]);
+                    if constexpr (NORMS) {
+                        const float w = widen<D>(*p), diff = acc[g][t] - w;
+                        num = fmaf(diff, diff, num);
+                        den = fmaf(w, w, den);
+                    } else {
+                        *p = narrow<D>(widen<D>(*p) - acc[g][t]);
+                    }
                 }
             }
+    }
+    if constexpr (NORMS) {
+        __syncthreads();                                            // the tile of U is no longer read
+        block_sum2<kThreadsD>(num, den, reinterpret_cast<float2*>(smem), partial + blockIdx.x);
+    }
+}
+
+// Adds the workgroups' sums in order (in double) and forms the bias:
+// out[0] = ||P S Q^T - G||_F^2, out[1] = ||G||_F^2, out[2] = sqrt(out[0] / out[1]).
+__global__ __launch_bounds__(256) void k_bias_finish(const float2* __restrict__ partial, int count, float* __restrict__ out) {
+    __shared__ double sx[256], sy[256];
+    double x = 0.0, y = 0.0;
+    for (int k = threadIdx.x; k < count; k += 256) { x += (double)partial[k].x; y += (double)partial[k].y; }
+    sx[threadIdx.x] = x; sy[threadIdx.x] = y;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) { sx[threadIdx.x] += sx[threadIdx.x + off]; sy[threadIdx.x] += sy[threadIdx.x + off]; }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out[0] = (float)sx[0]; out[1] = (float)sy[0];
+        out[2] = (float)sqrt(sx[0] / sy[0]);
     }
 }
 
@@ -286,8 +350,8 @@ bool apply_group_uniform(const ApplyGroup& g, int32_t r, int32_t d) {
     return g.count == 1 || fast_shape(g.n[0], r, d);                // the generic kernel takes one problem at a time
 }
 
-template <typename D, int RG, int PS, int NT, int CPT, int DEPTH>
-static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st) {
+template <typename D, int RG, int PS, int NT, int CPT, int DEPTH, bool NORMS = false>
+static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st, float2* partial = nullptr) {
     using E = typename D::elem;
     g.first[0] = 0;
     for (int p = 0; p < g.count; ++p) g.first[p + 1] = g.first[p] + (g.m[p] + RG * 4 - 1) / (RG * 4);
@@ -296,19 +360,19 @@ static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st) 
     // d = 16: a pass holds 32 (column, value) pairs per thread, so only one pass fits the registers
 #define LSP_LAUNCH_FAST(DDV)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, (DDV == 16 ? 1 : DEPTH)>;                            \
+        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, (DDV == 16 ? 1 : DEPTH), NORMS>;                            \
         const size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                              \
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         if (e != hipSuccess) return e;                                                                         \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, g, (int)r);                                    \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, g, (int)r, partial);                           \
     } while (0)
     if (!fast_shape(g.n[0], r, d)) {
-        auto kern = k_decompress_any<D, RG>;
+        auto kern = k_decompress_any<D, RG, NORMS>;
         const size_t lds = (size_t)RG * r * 16;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsD), lds, st, static_cast<E*>(g.W[0]), g.S[0], g.P_idx[0], g.P_val[0],
-                           g.Q_idx[0], g.Q_val[0], (int)g.m[0], (int)g.n[0], (int)r, (int)d);
+                           g.Q_idx[0], g.Q_val[0], (int)g.m[0], (int)g.n[0], (int)r, (int)d, partial);
     }
     else if (d == 2) LSP_LAUNCH_FAST(2);
     else if (d == 4) LSP_LAUNCH_FAST(4);
@@ -341,6 +405,30 @@ static hipError_t launch_d_shape(ApplyGroup& g, int32_t r, int32_t d, hipStream_
     if (r <= 1024) LSP_D_CASE(4, 16384);
     LSP_D_CASE(2, 32768);
 #undef LSP_D_CASE
+}
+
+// Estimation bias: one problem, 16 (or 8) rows per workgroup, two passes deep.
+int64_t bias_blocks(int64_t m, int32_t r) { return r <= 1024 ? (m + 15) / 16 : (m + 7) / 8; }
+
+template <typename D>
+static hipError_t launch_bias_shape(ApplyGroup& g, int32_t r, int32_t d, float2* partial, hipStream_t st) {
+    if (r <= 256)  return launch_d<D, 4, 4096, 512, 2, 2, true>(g, r, d, st, partial);
+    if (r <= 512)  return launch_d<D, 4, 8192, 512, 2, 2, true>(g, r, d, st, partial);
+    if (r <= 1024) return launch_d<D, 4, 16384, 512, 2, 2, true>(g, r, d, st, partial);
+    return launch_d<D, 2, 32768, 512, 2, 2, true>(g, r, d, st, partial);
+}
+
+hipError_t launch_bias(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, float* partial, float* out, hipStream_t st) {
+    float2* part = reinterpret_cast<float2*>(partial);
+    hipError_t e;
+    switch (dtype) {
+        case LSP_F32:  e = launch_bias_shape<F32>(g, r, d, part, st); break;
+        case LSP_F16:  e = launch_bias_shape<F16>(g, r, d, part, st); break;
+        default:       e = launch_bias_shape<BF16>(g, r, d, part, st); break;
+    }
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_bias_finish, dim3(1), dim3(256), 0, st, part, (int)bias_blocks(g.m[0], r), out);
+    return hipGetLastError();
 }
 
 hipError_t launch_decompress(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {

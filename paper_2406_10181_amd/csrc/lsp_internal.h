@@ -179,6 +179,9 @@ hipError_t launch_compress_raw(const void* G, const int32_t* P_idx, const float*
                                int64_t m, int64_t n, int32_t r, int32_t d,
                                float* S, lsp_dtype dtype, float* T, hipStream_t st);
 hipError_t launch_decompress(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
+// Estimation bias (Def. 2): `partial` holds bias_blocks(m, r) pairs of floats, `out` three floats.
+int64_t    bias_blocks(int64_t m, int32_t r);
+hipError_t launch_bias(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, float* partial, float* out, hipStream_t st);
 hipError_t launch_validate(const int32_t* idx, int64_t count, int32_t r, int32_t* flag, hipStream_t st);
 
 // ------------------------------------------------------------------------------------------

@@ -75,6 +75,25 @@ class DeviceProblem:
         return to_host(Wd, pb.dtype)
 
 
+    def estimation_bias(self, planned: bool = True) -> np.ndarray:
+        """Compress G, then the bias pass over G: returns the three floats of lsp_estimation_bias.
+        G must come back untouched."""
+        pb = self.pb
+        before = self.G.clone()
+        if planned:
+            self.compress_planned()
+        else:
+            self.compress_raw()
+        nb = L.lsp_estimation_bias_workspace_bytes(pb.m, pb.n, pb.r, pb.d)
+        ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        out = torch.full((3,), float("nan"), dtype=torch.float32, device="cuda")
+        L.lsp_estimation_bias(self.G, self.S, self.P_idx, self.P_val, self.Q_idx, self.Q_val, pb.m, pb.n, pb.r, pb.d,
+                              out, ws, nb, self.code, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert torch.equal(before.view(torch.uint8), self.G.view(torch.uint8)), "the bias pass must not write G"
+        return out.cpu().numpy()
+
+
 # ------------------------------------------------------------------ parity criteria
 def check_compress(S_gpu: np.ndarray, S_ora: np.ndarray, what: str, tight: float = 5e-5):
     """Norm-wise bar of the task: max |S_gpu - S_o| <= 1e-3 max |S_o|.  fp32 accumulation of a few

@@ -255,3 +255,64 @@ def test_validate_projector_and_plan_index_error():
     plan = torch.empty(L.lsp_plan_bytes(64, 64, 16, 2), dtype=torch.uint8, device="cuda")
     rc = L.lsp_plan_build(dp.P_idx, dp.P_val, bad, dp.Q_val, 64, 64, 16, 2, plan, plan.numel(), check=False)
     assert rc == -6
+
+
+# ------------------------------------------------------------------ estimation bias (Def. 2)
+def _bias_check(pb, tol=1e-3):
+    print(f"[case] bias {pb.name} m={pb.m} n={pb.n} r={pb.r} d={pb.d} {pb.dtype}", flush=True)
+    num, den = oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    got = _dp(pb).estimation_bias()
+    assert abs(got[1] - den) <= 1e-5 * den, f"{pb.name}: ||G||^2 {got[1]} vs {den}"
+    assert abs(got[0] - num) <= tol * max(num, den), f"{pb.name}: numerator {got[0]} vs {num}"
+    want = np.sqrt(num / den)
+    assert abs(got[2] - want) <= tol * max(want, 1.0), f"{pb.name}: bias {got[2]} vs {want}"
+    print(f"[ok]   bias {pb.name}: {got[2]:.6f} (oracle {want:.6f})", flush=True)
+    return got
+
+
+@pytest.mark.parametrize("m,n,r,d,dtype,dist", [
+    (256, 256, 16, 2, "f32", "distinct"),        # config 1
+    (512, 2048, 256, 4, "f16", "uniform"),
+    (203, 3000, 512, 8, "bf16", "uniform"),      # ragged last row block, several passes over the columns
+    (100, 1030, 64, 3, "bf16", "uniform"),       # generic kernel (d = 3, n % 4 != 0)
+    (96, 1024, 1500, 2, "bf16", "uniform"),      # 8 rows per workgroup
+    (64, 2048, 256, 16, "f16", "zipf"),          # d = 16: one pass in registers
+])
+def test_estimation_bias_against_oracle(m, n, r, d, dtype, dist):
+    _bias_check(syn.make_problem("bias", m, n, r, d, dtype, seed=4000 + m + n, g_std=1.0, index_dist=dist))
+
+
+def test_estimation_bias_config4_shape():
+    _bias_check(syn.config4_matrix(31, 3))         # 4096 x 4096 bf16, r = 512, d = 8
+
+
+def test_estimation_bias_exact_on_integers():
+    """Small integers and selection projectors: every sum is an integer below 2^24, so the two
+    squared norms are exact, and the reconstruction keeps exactly the selected block."""
+    rng = np.random.default_rng(77)
+    m, n, r = 203, 1000, 7
+    G = syn.integer_matrix(m, n, -8, 8, "bf16", rng)
+    rows = rng.permutation(m)[:r]; cols = rng.permutation(n)[:r]
+    P_idx = np.zeros((m, 1), dtype=np.int32); P_val = np.zeros((m, 1), dtype=np.float32)
+    Q_idx = np.zeros((n, 1), dtype=np.int32); Q_val = np.zeros((n, 1), dtype=np.float32)
+    P_idx[rows, 0] = np.arange(r); P_val[rows, 0] = 1.0
+    Q_idx[cols, 0] = rng.permutation(r); Q_val[cols, 0] = 1.0
+    pb = syn.make_problem("sel", m, n, r, 1, "bf16", seed=1)
+    pb.G, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val = G, P_idx, P_val, Q_idx, Q_val
+    num, den = oracle.estimation_bias(G, "bf16", P_idx, P_val, Q_idx, Q_val, r)
+    got = _dp(pb).estimation_bias(planned=False)
+    assert den < 2 ** 24 and float(got[0]) == num and float(got[1]) == den
+
+
+def test_estimation_bias_is_reproducible_and_checks_arguments():
+    import torch
+    import paper_2406_10181_amd as L
+    pb = syn.make_problem("rep", 300, 2048, 128, 4, "bf16", seed=9, g_std=1.0)
+    dp = _dp(pb)
+    a, b = dp.estimation_bias(), dp.estimation_bias()
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    nb = L.lsp_estimation_bias_workspace_bytes(pb.m, pb.n, pb.r, pb.d)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda"); out = torch.zeros(3, device="cuda")
+    args = (dp.G, dp.S, dp.P_idx, dp.P_val, dp.Q_idx, dp.Q_val, pb.m, pb.n, pb.r, pb.d, out)
+    assert L.lsp_estimation_bias(*args, ws, nb - 1, dp.code, None, check=False) == -4
+    assert L.lsp_estimation_bias(*args, ws, nb, 7, None, check=False) == -3

@@ -58,6 +58,17 @@ def test_argument_errors_without_gpu():
     # alignment of data pointers
     assert L.lsp_compress(fake + 2, fake, fake, fake, fake, 64, 64, 16, 2, fake, 0, fake, need, check=False) == -7
     assert L.lsp_decompress_apply(fake, fake + 8, fake, fake, fake, fake, 64, 64, 16, 2, 0, check=False) == -7
+    # the estimation-bias call checks its arguments the same way
+    bias = lambda *a, **k: L.lsp_estimation_bias(*a, check=False, **k)
+    bneed = L.lsp_estimation_bias_workspace_bytes(**ok)
+    assert bneed >= (64 // 16) * 8 and L.lsp_estimation_bias_workspace_bytes(0, 64, 16, 2) == 0
+    assert bias(None, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed, 0) == -1
+    assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, None, fake, bneed, 0) == -1
+    assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 4, 8, fake, fake, bneed, 0) == -2
+    assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed, 9) == -3
+    assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed - 1, 0) == -4
+    assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, None, bneed, 0) == -4
+    assert bias(fake, fake + 4, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed, 0) == -7
     assert "NULL" in L.lsp_strerror(-1) and L.lsp_strerror(0) == "ok"
     with pytest.raises(L.LspError):
         L.lsp_compress(None, fake, fake, fake, fake, 64, 64, 16, 2, fake, 0, fake, big)
