@@ -583,6 +583,130 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
     }
 }
 
+// Several columns per lane (r > 512, or columns used so unevenly that they were split), 16-bit
+// storage: the same staging, plan ring and block walk as gq16_one_slot, the lane's columns taken
+// slot by slot inside each chunk.  A lane keeps its columns for all chunks (no dealing by length:
+// the sums of NS columns per lane would not fit through LDS cheaply).
+template <typename D, int NS>
+__device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+                                                const uint8_t* __restrict__ plan, PlanHeaderPtr H,
+                                                float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
+                                                int tid, int lane, int wave) {
+    const int nchunks = H->nchunks, nslots = H->nslots;
+    const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
+    const u32x4* rp0 = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+    const u32x4* rp = rp0;
+    const auto* vcol = as_const<uint16_t>(plan + H->off_q_vcol);
+    const bool shared = H->q_any_shared != 0;
+
+    u32x4 ring[kPrefetch][kBatchLoads];                               // fixed register slots (see gq_one_slot)
+    auto ring_restart = [&]() {
+        rp = rp0;
+#pragma unroll
+        for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+            for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
+        rp += (size_t)kPrefetch * kBatchLoads * kWave;
+    };
+    ring_restart();
+
+    float acc[NS][kRowsGQ];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int t = 0; t < kRowsGQ; ++t) acc[s][t] = 0.0f;
+
+    const uint8_t* buf = smem;
+    auto step = [&](u32x4 (&slot)[kBatchLoads], float (&a)[kRowsGQ]) {
+        u32x4 x[2][2][kPlanes16];
+        gather_pair16(buf, slot[0], x[0]);
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) {
+            if (q + 1 < kBatchLoads) gather_pair16(buf, slot[q + 1], x[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            fma_pair16<D>(slot[q], x[q & 1], a);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) slot[q] = rp[(size_t)q * kWave];
+        rp += (size_t)kBatchLoads * kWave;
+    };
+    static_assert(kPrefetch == 4, "the rotation below is written for four slots");
+    auto unrotate = [&](int rot) {                                    // slot 0 holds the oldest batch again
+        if (rot != 0) {
+            u32x4 t[kPrefetch][kBatchLoads];
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) {
+                    t[k][q] = ring[(k + 1) % kPrefetch][q];
+                    if (rot == 2) t[k][q] = ring[(k + 2) % kPrefetch][q];
+                    if (rot == 3) t[k][q] = ring[(k + 3) % kPrefetch][q];
+                }
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = t[k][q];
+        }
+    };
+
+    stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
+    __syncthreads();
+    int rot = 0, c = 0, blk = 0;
+    const int units = nblk * nchunks;
+    for (int u = 0; u < units; ++u) {
+        const bool last_chunk = c + 1 == nchunks;
+        const bool more = u + 1 < units;
+        if (more)
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * kRowsGQ, m, n, last_chunk ? 0 : c + 1, tid);
+        buf = smem + (u & 1) * kBufStride16;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s < nslots) {
+                unrotate(rot);
+                const int nb = (int)(seg[(c * nslots + s) * kWavesGQ] / kSegBatch);
+                for (int g = nb / kPrefetch; g > 0; --g) {
+                    step(ring[0], acc[s]); step(ring[1], acc[s]); step(ring[2], acc[s]); step(ring[3], acc[s]);
+                }
+                rot = nb % kPrefetch;
+                if (rot > 0) step(ring[0], acc[s]);
+                if (rot > 1) step(ring[1], acc[s]);
+                if (rot > 2) step(ring[2], acc[s]);
+            }
+        }
+        if (last_chunk) {                                             // the block's 16 sums per column are complete
+            const int64_t ib = i0 + (int64_t)blk * kRowsGQ;
+            if (more) { ring_restart(); rot = 0; }                    // the stream starts over; in flight during the stores
+            if (shared) {
+                write_tile_shared<NS>(smem, plan, H, T, acc, nslots, ib, m, r, tid);   // uses the LDS of both chunk buffers
+                if (more) {
+                    __syncthreads();                                  // before that LDS is staged into again
+                    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const uint32_t col = s < nslots ? (uint32_t)vcol[s * kThreadsGQ + tid] : kNoColumn;
+                    if (col != kNoColumn) {
+#pragma unroll
+                        for (int t = 0; t < kRowsGQ; ++t)
+                            if (ib + t < m) stream_store(&T[(ib + t) * (int64_t)r + col], acc[s][t]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+#pragma unroll
+                for (int t = 0; t < kRowsGQ; ++t) acc[s][t] = 0.0f;
+            c = 0; ++blk;
+        } else {
+            ++c;
+        }
+        if (more) stg.stage(smem, (u + 1) & 1, tid);                  // the other buffer: nobody reads it now
+        __syncthreads();                                              // the next chunk is staged; this one is no longer read
+    }
+}
+
 // Kernel A for fp16 / bf16 with n % 8 == 0.
 template <typename D>
 __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r, int blocks_per_wg) {
@@ -607,22 +731,11 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
         for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
     }
     if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    if (H->nslots == 1) {
-        ChunkStager16 stg;
-        stg.fetch(G, i0, m, n, 0, tid);
-        gq16_one_slot<D>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
-    } else {
-        for (int b = 0; b < nblk; ++b) {                              // the general path takes one block at a time
-            if (b > 0) {
-                __syncthreads();
-                if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            }
-            const int64_t ib = i0 + (int64_t)b * kRowsGQ;
-            ChunkStager<D, true> stg;
-            stg.fetch(G, ib, m, n, 0, tid);
-            gq_any_slots<D, true>(stg, smem, G, plan, H, T, ib, m, n, r, tid, lane, wave);
-        }
-    }
+    ChunkStager16 stg;
+    stg.fetch(G, i0, m, n, 0, tid);
+    if (H->nslots == 1)      gq16_one_slot<D>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else if (H->nslots == 2) gq16_multi_slot<D, 2>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else                     gq16_multi_slot<D, kMaxSlots>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
 }
 
 template <typename D, bool VEC>

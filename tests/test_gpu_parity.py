@@ -215,6 +215,27 @@ def test_big_grid_with_ragged_last_row_block():
     _full_check(pb, raw=False)
 
 
+@pytest.mark.parametrize("n,r,d,dist", [
+    (1024, 1024, 2, "uniform"),       # two columns per lane, none shared
+    (2048, 600, 4, "zipf"),           # hot columns split between lanes: several slots and the ordered merge
+])
+def test_big_grid_with_several_columns_per_lane(n, r, d, dist):
+    # a workgroup walks two row blocks while every lane owns several columns of T
+    pb = syn.make_problem("big_slots", 16 * 1030 + 3, n, r, d, "bf16", seed=930 + d, index_dist=dist)
+    _full_check(pb, tight=2e-4, raw=False)
+
+
+@pytest.mark.parametrize("m,n,r,d,dtype", [
+    (4096, 4096, 2048, 8, "bf16"),    # subspace 2048 with 8 entries per row on a 4096-wide layer
+    (2048, 2048, 1280, 4, "f16"),     # subspace 1280 with 4 entries per row on a 2048-wide layer
+])
+def test_paper_sized_subspaces(m, n, r, d, dtype):
+    """The subspace sizes the paper trained with (its experiments section), at full matrix size."""
+    pb = syn.make_problem("paper_r", m, n, r, d, dtype, seed=940 + d)
+    _full_check(pb, raw=False)
+    _bias_check(syn.make_problem("paper_r_bias", m, n, r, d, dtype, seed=950 + d, g_std=1.0))
+
+
 def test_grouped_layer_of_config4():
     # the seven matrices of one layer of the 6.7B-style stack, at full size, as bench.py launches them:
     # sampled rows against the oracle, everything bit for bit against the single calls
