@@ -54,6 +54,7 @@ def _load():
         lib.lsp_oracle_compress_entries.argtypes = [vp, i32] + proj + [i64, i64, i32, i32, vp, vp, i64, vp]
         lib.lsp_oracle_bias.argtypes = [vp, i32] + proj + [i64, i64, i32, i32, vp]
         lib.lsp_oracle_bias_dense.argtypes = lib.lsp_oracle_bias.argtypes
+        lib.lsp_oracle_reproject.argtypes = proj + proj + [i64, i64, i32, i32, vp, vp, vp, vp]
         lib.lsp_oracle_round_to_storage.argtypes = [ctypes.c_double, i32]
         lib.lsp_oracle_round_to_storage.restype = ctypes.c_double
         lib.lsp_oracle_widen.argtypes = [vp, i64, i32]
@@ -150,6 +151,30 @@ def estimation_bias(G, dtype, P_idx, P_val, Q_idx, Q_val, r: int, *, dense: bool
     if rc != 0:
         raise RuntimeError(f"oracle estimation_bias failed rc={rc}")
     return float(out[0]), float(out[1])
+
+
+def reproject_state(P_idx, P_val, Pp_idx, Pp_val, Q_idx, Q_val, Qp_idx, Qp_val, r: int, M, V):
+    """Last two assignments of MaybeUpdate (Alg. 1): M' = (P^T P_prev) M (Q_prev^T Q) and
+    V' = (P^T P_prev)^2 V (Q_prev^T Q)^2 with element-wise squares, in float64.  P, P_prev are [m][d]
+    ELL pairs, Q, Q_prev [n][d]; M, V float32 [r][r]."""
+    lib = _load()
+    m, d = P_idx.shape
+    n = Q_idx.shape[0]
+    P_idx, P_val = _proj(P_idx, P_val, m, r, d)
+    Pp_idx, Pp_val = _proj(Pp_idx, Pp_val, m, r, d)
+    Q_idx, Q_val = _proj(Q_idx, Q_val, n, r, d)
+    Qp_idx, Qp_val = _proj(Qp_idx, Qp_val, n, r, d)
+    M = np.ascontiguousarray(M, dtype=np.float32)
+    V = np.ascontiguousarray(V, dtype=np.float32)
+    if M.shape != (r, r) or V.shape != (r, r):
+        raise ValueError("M and V must be [r][r]")
+    Mo = np.empty((r, r), dtype=np.float64)
+    Vo = np.empty((r, r), dtype=np.float64)
+    rc = lib.lsp_oracle_reproject(_p(P_idx), _p(P_val), _p(Pp_idx), _p(Pp_val), _p(Q_idx), _p(Q_val),
+                                  _p(Qp_idx), _p(Qp_val), m, n, r, d, _p(M), _p(V), _p(Mo), _p(Vo))
+    if rc != 0:
+        raise RuntimeError(f"oracle reproject_state failed rc={rc}")
+    return Mo, Vo
 
 
 def decompress_rows(W, dtype, S, P_idx, P_val, Q_idx, Q_val, rows: Sequence[int]) -> np.ndarray:

@@ -17,6 +17,16 @@
  *   estimation bias   b = ||P P^T G Q Q^T - G||_F / ||G||_F
  *                                             -- Def. 2; the quantity MaybeUpdate in Alg. 1
  *                                                compares with its threshold alpha
+ *   state re-projection  M <- (P^T P_prev) M (Q_prev^T Q),
+ *                        V <- (P^T P_prev)^2 V (Q_prev^T Q)^2
+ *                                             -- last two assignments of MaybeUpdate in Alg. 1:
+ *                                                the optimiser's moments follow a change of
+ *                                                projectors.  The squares are taken element by
+ *                                                element (the second moment of a linear
+ *                                                combination of independent terms weights their
+ *                                                second moments with the squared coefficients,
+ *                                                and V stays non-negative); a matrix square
+ *                                                would do neither.
  *
  * P (m x r) and Q (n x r) are (d,r)-sparse projectors in the sense of Def. 1: exactly d
  * stored entries per row, kept in ELL layout as idx[row][k] (int32 column in [0,r)) and
@@ -220,6 +230,56 @@ int lsp_oracle_bias_dense(const void *G, int dtype,
     out[0] = num; out[1] = den;
     free(Ph); free(Qh); free(PP); free(QQ); free(A);
     return 0;
+}
+
+/* Optimiser-state re-projection, written out on densified projectors (all r x r, fp64):
+ *   A = Phat^T Pprev_hat,  B = Qprev_hat^T Qhat,
+ *   M_out = A M B,   V_out = (A o A) V (B o B)   with "o" the element-wise product.
+ * M and V are fp32 inputs; M_out and V_out may alias nothing. */
+int lsp_oracle_reproject(const int32_t *P_idx, const float *P_val,
+                         const int32_t *Pp_idx, const float *Pp_val,
+                         const int32_t *Q_idx, const float *Q_val,
+                         const int32_t *Qp_idx, const float *Qp_val,
+                         int64_t m, int64_t n, int r, int d,
+                         const float *M, const float *V, double *M_out, double *V_out) {
+    double *Ph = densify(P_idx, P_val, m, r, d), *Pp = densify(Pp_idx, Pp_val, m, r, d);
+    double *Qh = densify(Q_idx, Q_val, n, r, d), *Qp = densify(Qp_idx, Qp_val, n, r, d);
+    size_t rr = (size_t)r * (size_t)r;
+    double *A = (double *)calloc(rr, sizeof(double)), *B = (double *)calloc(rr, sizeof(double));
+    double *X = (double *)calloc(rr, sizeof(double)), *Y = (double *)calloc(rr, sizeof(double));
+    int rc = -1;
+    if (Ph && Pp && Qh && Qp && A && B && X && Y) {
+        for (int a = 0; a < r; ++a)
+            for (int b = 0; b < r; ++b) {
+                double sa = 0.0, sb = 0.0;
+                for (int64_t i = 0; i < m; ++i) sa += Ph[i * r + a] * Pp[i * r + b];     /* A = P^T P_prev */
+                for (int64_t j = 0; j < n; ++j) sb += Qp[j * r + a] * Qh[j * r + b];     /* B = Q_prev^T Q */
+                A[(size_t)a * r + b] = sa; B[(size_t)a * r + b] = sb;
+            }
+        for (int a = 0; a < r; ++a)
+            for (int b = 0; b < r; ++b) {
+                double x = 0.0, y = 0.0;
+                for (int c = 0; c < r; ++c) {
+                    double aac = A[(size_t)a * r + c];
+                    x += aac * (double)M[(size_t)c * r + b];
+                    y += aac * aac * (double)V[(size_t)c * r + b];
+                }
+                X[(size_t)a * r + b] = x; Y[(size_t)a * r + b] = y;
+            }
+        for (int a = 0; a < r; ++a)
+            for (int b = 0; b < r; ++b) {
+                double x = 0.0, y = 0.0;
+                for (int c = 0; c < r; ++c) {
+                    double bcb = B[(size_t)c * r + b];
+                    x += X[(size_t)a * r + c] * bcb;
+                    y += Y[(size_t)a * r + c] * bcb * bcb;
+                }
+                M_out[(size_t)a * r + b] = x; V_out[(size_t)a * r + b] = y;
+            }
+        rc = 0;
+    }
+    free(Ph); free(Pp); free(Qh); free(Qp); free(A); free(B); free(X); free(Y);
+    return rc;
 }
 
 /* ---------------------------------------------------------------- working form */

@@ -444,3 +444,53 @@ def test_bias_a_transposed_reconstruction_is_detected():
     G64 = pb.G.astype(np.float64)
     wrong = Qh @ Qh.T @ G64 @ Ph @ Ph.T
     assert abs(float(((wrong - G64) ** 2).sum()) - num) > 1e-3 * num
+
+
+# ---------------------------------------------------------------- optimiser-state re-projection (Alg. 1, MaybeUpdate)
+def _two_projector_pairs(m, n, r, d, seed, dist="uniform"):
+    rng = _rng(seed)
+    return [syn.ell_projector(rows, r, d, rng, dist) for rows in (m, m, n, n)]      # P, P_prev, Q, Q_prev
+
+
+@pytest.mark.parametrize("m,n,r,d,dist", [(9, 7, 4, 2, "uniform"), (20, 33, 6, 3, "zipf"), (5, 5, 5, 1, "distinct")])
+def test_reproject_against_numpy(m, n, r, d, dist):
+    (P_idx, P_val), (Pp_idx, Pp_val), (Q_idx, Q_val), (Qp_idx, Qp_val) = _two_projector_pairs(m, n, r, d, 500 + m, dist)
+    rng = _rng(501 + m)
+    M = rng.standard_normal((r, r)).astype(np.float32)
+    V = (rng.standard_normal((r, r)) ** 2).astype(np.float32)
+    Mo, Vo = oracle.reproject_state(P_idx, P_val, Pp_idx, Pp_val, Q_idx, Q_val, Qp_idx, Qp_val, r, M, V)
+    A = _dense(P_idx, P_val, r).T @ _dense(Pp_idx, Pp_val, r)
+    B = _dense(Qp_idx, Qp_val, r).T @ _dense(Q_idx, Q_val, r)
+    refM = A @ M.astype(np.float64) @ B
+    refV = (A * A) @ V.astype(np.float64) @ (B * B)
+    np.testing.assert_allclose(Mo, refM, rtol=0, atol=1e-12 * max(1.0, np.abs(refM).max()))
+    np.testing.assert_allclose(Vo, refV, rtol=0, atol=1e-12 * max(1.0, np.abs(refV).max()))
+    assert Vo.min() >= 0.0                                  # a second moment stays non-negative
+
+
+def test_reproject_closed_forms():
+    rng = _rng(510)
+    m = n = r = 6
+    M = rng.standard_normal((r, r)).astype(np.float32)
+    V = (rng.standard_normal((r, r)) ** 2).astype(np.float32)
+    one = np.ones((m, 1), dtype=np.float32)
+    ident = np.arange(r, dtype=np.int32).reshape(r, 1)
+    # unchanged orthonormal projectors: P^T P_prev = I on both sides, the state is kept
+    Mo, Vo = oracle.reproject_state(ident, one, ident, one, ident, one, ident, one, r, M, V)
+    assert np.array_equal(Mo, M.astype(np.float64)) and np.array_equal(Vo, V.astype(np.float64))
+    # the new projectors are a relabelling of the old columns: the state is permuted the same way
+    pa, pb = rng.permutation(r).astype(np.int32), rng.permutation(r).astype(np.int32)
+    Mo, Vo = oracle.reproject_state(pa.reshape(r, 1), one, ident, one, pb.reshape(r, 1), one, ident, one, r, M, V)
+    # A[pa[i], i] = 1 and B[j, pb[j]] = 1:  M'[pa[i], pb[j]] = M[i, j]
+    refM = np.zeros((r, r)); refV = np.zeros((r, r))
+    refM[np.ix_(pa, pb)] = M; refV[np.ix_(pa, pb)] = V
+    assert np.array_equal(Mo, refM) and np.array_equal(Vo, refV)
+    # doubling the new P doubles M' and quadruples V' (element-wise squares; a matrix square would not)
+    (P_idx, P_val), (Pp_idx, Pp_val), (Q_idx, Q_val), (Qp_idx, Qp_val) = _two_projector_pairs(8, 9, 4, 2, 511)
+    M4 = rng.standard_normal((4, 4)).astype(np.float32); V4 = (rng.standard_normal((4, 4)) ** 2).astype(np.float32)
+    M1, V1 = oracle.reproject_state(P_idx, P_val, Pp_idx, Pp_val, Q_idx, Q_val, Qp_idx, Qp_val, 4, M4, V4)
+    M2, V2 = oracle.reproject_state(P_idx, 2 * P_val, Pp_idx, Pp_val, Q_idx, Q_val, Qp_idx, Qp_val, 4, M4, V4)
+    assert np.array_equal(M2, 2 * M1) and np.array_equal(V2, 4 * V1)
+    # the roles of the old and the new projector are not interchangeable
+    M3, _ = oracle.reproject_state(Pp_idx, Pp_val, P_idx, P_val, Q_idx, Q_val, Qp_idx, Qp_val, 4, M4, V4)
+    assert np.abs(M3 - M1).max() > 1e-6 * np.abs(M1).max()
