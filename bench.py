@@ -204,6 +204,17 @@ def main():
     ms_bias = timed(bias_all, sub)
     bbytes = sum(e["cb"] for e in mats)             # one read of G, the projector arrays and S: as for compress
 
+    # state re-projection after a change of projectors (MaybeUpdate, Alg. 1): one 4096 x 4096 matrix, the
+    # projectors of two consecutive entries of the stack standing in for (new, previous)
+    sq = [e for e in mats if e["m"] == 4096 and e["n"] == 4096][:2]
+    rp_bytes = L.lsp_reproject_state_workspace_bytes(r)
+    rp_ws = torch.empty(rp_bytes, dtype=torch.uint8, device=dev)
+    rp_M = torch.randn(r, r, device=dev, dtype=torch.float32)
+    rp_V = torch.rand(r, r, device=dev, dtype=torch.float32)
+    ms_rep = timed(lambda: L.lsp_reproject_state(sq[0]["P_idx"], sq[0]["P_val"], sq[1]["P_idx"], sq[1]["P_val"],
+                                                 sq[0]["Q_idx"], sq[0]["Q_val"], sq[1]["Q_idx"], sq[1]["Q_val"],
+                                                 4096, 4096, r, d, rp_M, rp_V, rp_ws, rp_bytes, stream), 10)
+
     cbytes = sum(e["cb"] for e in mats)
     dbytes = sum(e["db"] for e in mats)
     value = (cbytes + dbytes) / (ms_step * 1e-3) / 1e9
@@ -265,6 +276,10 @@ def main():
                             "ms_per_pass": round(ms_bias, 4), "GB/s": round(bbytes / (ms_bias * 1e-3) / 1e9, 1),
                             "frac_of_hbm_peak": round(bbytes / (ms_bias * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                             "avg_call_us": round(ms_bias * 1e3 / nlaunch, 2)},
+        # once per change of projectors: 4 dense r x r x r products on the matrix cores (fp32) + 2 sparse-sparse ones
+        "reproject_state": {"kernel": "k_gram x2 + k_gemm_rr x4 (one lsp_reproject_state call, 4096 x 4096, r=512, d=8)",
+                            "us_per_call": round(ms_rep * 1e3, 1), "bound": "mfma", "dense_flop": 8 * r ** 3,
+                            "TFLOP/s": round(8 * r ** 3 / (ms_rep * 1e-3) / 1e12, 2), "peak_fp32_TFLOP/s": 157.3},
         "setup_s": round(setup_s, 1),
     }
 

@@ -212,6 +212,34 @@ int lsp_estimation_bias(const void* G, const float* S,
 size_t lsp_estimation_bias_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
 
 /* ------------------------------------------------------------------------------------------
+ * Optimiser-state re-projection: the last two assignments of MaybeUpdate in Alg. 1.  When the
+ * projectors (P_prev, Q_prev) of a matrix are replaced by (P, Q), the first and second moments
+ * kept in the subspace follow:
+ *     M := (P^T P_prev) M (Q_prev^T Q)         V := (P^T P_prev)^2 V (Q_prev^T Q)^2
+ * with the squares taken element by element (the reading under which V is the second moment of
+ * the re-projected first-moment terms and stays non-negative).  Runs once per change of
+ * projectors, on the device copy of the moments.
+ *
+ *   P_*, Pprev_*   device, [m][d] ELL pairs of the new and the previous left projector
+ *   Q_*, Qprev_*   device, [n][d] ELL pairs of the new and the previous right projector
+ *   M              device, r*r fp32, row-major, read and overwritten
+ *   V              device, r*r fp32, read and overwritten; may be NULL (no second moment); not M
+ *   workspace      device scratch of at least lsp_reproject_state_workspace_bytes(r) bytes,
+ *                  16-byte aligned; contents undefined afterwards
+ * The two r x r products of sparse matrices are accumulated with fp32 atomics: the result can
+ * differ in the last bits from run to run.  The dense r x r products run in fp32 on the matrix
+ * cores.  Errors as for the other calls; asynchronous on `stream`.
+ */
+int lsp_reproject_state(const int32_t* P_idx, const float* P_val,
+                        const int32_t* Pprev_idx, const float* Pprev_val,
+                        const int32_t* Q_idx, const float* Q_val,
+                        const int32_t* Qprev_idx, const float* Qprev_val,
+                        int64_t m, int64_t n, int32_t r, int32_t d,
+                        float* M, float* V,
+                        void* workspace, size_t workspace_bytes, void* stream);
+size_t lsp_reproject_state_workspace_bytes(int32_t r);
+
+/* ------------------------------------------------------------------------------------------
  * Utilities.
  */
 

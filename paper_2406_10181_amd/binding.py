@@ -69,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.lsp_decompress_apply_grouped.restype = ctypes.c_int
         L.lsp_estimation_bias.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, ctypes.c_size_t, i32, vp]
         L.lsp_estimation_bias.restype = ctypes.c_int
+        L.lsp_reproject_state.argtypes = [vp] * 8 + [i64, i64, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.lsp_reproject_state.restype = ctypes.c_int
+        L.lsp_reproject_state_workspace_bytes.argtypes = [i32]
+        L.lsp_reproject_state_workspace_bytes.restype = ctypes.c_size_t
         L.lsp_estimation_bias_workspace_bytes.argtypes = [i64, i64, i32, i32]
         L.lsp_estimation_bias_workspace_bytes.restype = ctypes.c_size_t
         L.lsp_validate_projector.argtypes = [vp, i64, i32, i32, vp, vp]
@@ -185,6 +189,20 @@ def lsp_estimation_bias(G, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, out, works
                                    m, n, r, d, _ptr(out), _ptr(workspace), workspace_bytes, dtype, _stream(stream))
     if check:
         _check(rc, "lsp_estimation_bias")
+    return rc
+
+
+def lsp_reproject_state_workspace_bytes(r) -> int:
+    return int(lib().lsp_reproject_state_workspace_bytes(r))
+
+
+def lsp_reproject_state(P_idx, P_val, Pprev_idx, Pprev_val, Q_idx, Q_val, Qprev_idx, Qprev_val, m, n, r, d, M, V,
+                        workspace, workspace_bytes, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_reproject_state(_ptr(P_idx), _ptr(P_val), _ptr(Pprev_idx), _ptr(Pprev_val), _ptr(Q_idx), _ptr(Q_val),
+                                   _ptr(Qprev_idx), _ptr(Qprev_val), m, n, r, d, _ptr(M), _ptr(V),
+                                   _ptr(workspace), workspace_bytes, _stream(stream))
+    if check:
+        _check(rc, "lsp_reproject_state")
     return rc
 
 

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblsp_hip.so")
-SOURCES = ["api.cpp", "plan.cpp", "compress.hip", "decompress.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "compress.hip", "decompress.hip", "reproject.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

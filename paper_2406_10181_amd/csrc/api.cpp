@@ -225,6 +225,26 @@ int lsp_estimation_bias(const void* G, const float* S, const int32_t* P_idx, con
     return e == hipSuccess ? LSP_OK : fail_launch(e);
 }
 
+size_t lsp_reproject_state_workspace_bytes(int32_t r) {
+    if (r <= 0 || r > LSP_MAX_R) return 0;
+    return lsp::align_up((size_t)3 * (size_t)r * (size_t)r * sizeof(float), 256);
+}
+
+int lsp_reproject_state(const int32_t* P_idx, const float* P_val, const int32_t* Pprev_idx, const float* Pprev_val,
+                        const int32_t* Q_idx, const float* Q_val, const int32_t* Qprev_idx, const float* Qprev_val,
+                        int64_t m, int64_t n, int32_t r, int32_t d, float* M, float* V,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (!P_idx || !P_val || !Pprev_idx || !Pprev_val || !Q_idx || !Q_val || !Qprev_idx || !Qprev_val || !M) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    if (!workspace || workspace_bytes < lsp_reproject_state_workspace_bytes(r) || !aligned16(workspace)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(M) || (V && !aligned16(V))) return LSP_ERR_ALIGN;
+    if (M == V) return LSP_ERR_SHAPE;
+    hipError_t e = lsp::launch_reproject(P_idx, P_val, Pprev_idx, Pprev_val, Q_idx, Q_val, Qprev_idx, Qprev_val,
+                                         m, n, r, d, M, V, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
 int lsp_validate_projector(const int32_t* idx, int64_t rows, int32_t d, int32_t r, int32_t* flag, void* stream) {
     if (!idx || !flag) return LSP_ERR_NULL;
     if (rows <= 0 || d <= 0 || r <= 0) return LSP_ERR_SHAPE;

@@ -182,6 +182,11 @@ hipError_t launch_decompress(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtyp
 // Estimation bias (Def. 2): `partial` holds bias_blocks(m, r) pairs of floats, `out` three floats.
 int64_t    bias_blocks(int64_t m, int32_t r);
 hipError_t launch_bias(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, float* partial, float* out, hipStream_t st);
+// Optimiser-state re-projection (MaybeUpdate, Alg. 1): workspace holds 3 r^2 floats; V may be null.
+hipError_t launch_reproject(const int32_t* P_idx, const float* P_val, const int32_t* Pp_idx, const float* Pp_val,
+                            const int32_t* Q_idx, const float* Q_val, const int32_t* Qp_idx, const float* Qp_val,
+                            int64_t m, int64_t n, int32_t r, int32_t d, float* M, float* V, float* workspace,
+                            hipStream_t st);
 hipError_t launch_validate(const int32_t* idx, int64_t count, int32_t r, int32_t* flag, hipStream_t st);
 
 // ------------------------------------------------------------------------------------------

@@ -69,6 +69,17 @@ def test_argument_errors_without_gpu():
     assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed - 1, 0) == -4
     assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, None, bneed, 0) == -4
     assert bias(fake, fake + 4, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed, 0) == -7
+    # and so does the state re-projection
+    rep = lambda *a, **k: L.lsp_reproject_state(*a, check=False, **k)
+    rneed = L.lsp_reproject_state_workspace_bytes(16)
+    assert rneed >= 3 * 16 * 16 * 4 and L.lsp_reproject_state_workspace_bytes(0) == 0
+    eight = (fake,) * 8
+    assert rep(None, *eight[1:], 64, 64, 16, 2, fake, fake + 1024, fake, rneed) == -1
+    assert rep(*eight, 64, 64, 16, 2, None, fake, fake, rneed) == -1
+    assert rep(*eight, 64, 64, 16, 32, fake, fake + 1024, fake, rneed) == -2
+    assert rep(*eight, 64, 64, 16, 2, fake, fake, fake, rneed) == -2           # M and V the same buffer
+    assert rep(*eight, 64, 64, 16, 2, fake, fake + 1024, fake, rneed - 1) == -4
+    assert rep(*eight, 64, 64, 16, 2, fake + 4, None, fake, rneed) == -7
     assert "NULL" in L.lsp_strerror(-1) and L.lsp_strerror(0) == "ok"
     with pytest.raises(L.LspError):
         L.lsp_compress(None, fake, fake, fake, fake, 64, 64, 16, 2, fake, 0, fake, big)
