@@ -36,7 +36,8 @@ __global__ __launch_bounds__(256) void k_gram(const int32_t* __restrict__ L_idx,
 // A workgroup of four waves makes a 64 x 64 tile of C, each wave a 32 x 32 quarter with
 // v_mfma_f32_32x32x2_f32: lane l supplies A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32],
 // and holds C[8 (v / 4) + 4 (l / 32) + v % 4][l % 32] in accumulator register v.
-constexpr int kTileMN = 64, kTileK = 16;
+constexpr int kTileMN = 64, kTileK = 64;
+constexpr int kTileElems = kTileMN * kTileK / 256;                  // elements of each tile a thread stages
 template <bool SQA, bool SQB>
 __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, const float* __restrict__ B,
                                                  float* __restrict__ C, int r) {
@@ -48,18 +49,30 @@ __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, co
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    for (int k0 = 0; k0 < r; k0 += kTileK) {
+    // the next pair of tiles is fetched into registers while the matrix cores work on the current one
+    float an[kTileElems], bn[kTileElems];
+    auto fetch = [&](int k0) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {                               // 64 x 16 and 16 x 64 elements, four per thread each
+        for (int e = 0; e < kTileElems; ++e) {
             const int q = tid + e * 256;
             const int ar = q / kTileK, ak = q % kTileK;
-            float a = (row0 + ar < r && k0 + ak < r) ? A[(int64_t)(row0 + ar) * r + k0 + ak] : 0.0f;
-            As[ar][ak] = SQA ? a * a : a;
+            const float a = (row0 + ar < r && k0 + ak < r) ? A[(int64_t)(row0 + ar) * r + k0 + ak] : 0.0f;
+            an[e] = SQA ? a * a : a;
             const int bk = q / kTileMN, bc = q % kTileMN;
-            float b = (k0 + bk < r && col0 + bc < r) ? B[(int64_t)(k0 + bk) * r + col0 + bc] : 0.0f;
-            Bs[bk][bc] = SQB ? b * b : b;
+            const float b = (k0 + bk < r && col0 + bc < r) ? B[(int64_t)(k0 + bk) * r + col0 + bc] : 0.0f;
+            bn[e] = SQB ? b * b : b;
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < r; k0 += kTileK) {
+#pragma unroll
+        for (int e = 0; e < kTileElems; ++e) {
+            const int q = tid + e * 256;
+            As[q / kTileK][q % kTileK] = an[e];
+            Bs[q / kTileMN][q % kTileMN] = bn[e];
         }
         __syncthreads();
+        if (k0 + kTileK < r) fetch(k0 + kTileK);
 #pragma unroll
         for (int kk = 0; kk < kTileK; kk += 2)
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[wr + (lane & 31)][kk + (lane >> 5)],
