@@ -33,19 +33,22 @@ __global__ __launch_bounds__(256) void k_gram(const int32_t* __restrict__ L_idx,
 }
 
 // C = op(A) op(B), all r x r row-major fp32; op squares every element when the flag is set.
-// A workgroup of four waves makes a 64 x 64 tile of C, each wave a 32 x 32 quarter with
-// v_mfma_f32_32x32x2_f32: lane l supplies A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32],
-// and holds C[8 (v / 4) + 4 (l / 32) + v % 4][l % 32] in accumulator register v.
-constexpr int kTileMN = 64, kTileK = 64;
+// A workgroup of four waves makes a 32 x 32 tile of C (many small tiles: r is a few hundred, and
+// every CU should get one).  The K range goes by in 64-wide tiles staged through LDS; inside a
+// tile the four waves take 16 consecutive k each with v_mfma_f32_32x32x2_f32 -- lane l supplies
+// A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32] and holds
+// C[8 (v / 4) + 4 (l / 32) + v % 4][l % 32] in accumulator register v -- and their four partial
+// tiles are added through LDS at the end, in wave order.
+constexpr int kTileMN = 32, kTileK = 64;
 constexpr int kTileElems = kTileMN * kTileK / 256;                  // elements of each tile a thread stages
 template <bool SQA, bool SQB>
 __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, const float* __restrict__ B,
                                                  float* __restrict__ C, int r) {
     __shared__ float As[kTileMN][kTileK + 1];
     __shared__ float Bs[kTileK][kTileMN + 1];
+    __shared__ float Cs[4][16][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row0 = blockIdx.y * kTileMN, col0 = blockIdx.x * kTileMN;
-    const int wr = (wave >> 1) * 32, wc = (wave & 1) * 32;
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
@@ -74,16 +77,22 @@ __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, co
         __syncthreads();
         if (k0 + kTileK < r) fetch(k0 + kTileK);
 #pragma unroll
-        for (int kk = 0; kk < kTileK; kk += 2)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[wr + (lane & 31)][kk + (lane >> 5)],
-                                                       Bs[kk + (lane >> 5)][wc + (lane & 31)], acc, 0, 0, 0);
+        for (int kk = wave * (kTileK / 4); kk < (wave + 1) * (kTileK / 4); kk += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[lane & 31][kk + (lane >> 5)],
+                                                       Bs[kk + (lane >> 5)][lane & 31], acc, 0, 0, 0);
         __syncthreads();
     }
-    const int j = col0 + wc + (lane & 31);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int i = row0 + wr + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (i < r && j < r) C[(int64_t)i * r + j] = acc[v];
+    for (int v = 0; v < 16; ++v) Cs[wave][v][lane] = acc[v];
+    __syncthreads();
+    if (wave == 0) {
+        const int j = col0 + (lane & 31);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = row0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const float sum = ((Cs[0][v][lane] + Cs[1][v][lane]) + Cs[2][v][lane]) + Cs[3][v][lane];
+            if (i < r && j < r) C[(int64_t)i * r + j] = sum;
+        }
     }
 }
 
