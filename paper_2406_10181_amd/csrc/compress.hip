@@ -6,9 +6,12 @@
 //                  column and group of rows (8 rows in storage precision for fp16 / bf16, 4 rows
 //                  widened to fp32 otherwise), so one 128-bit LDS read serves 8 (4) rows; each
 //                  lane owns one column b of T and walks the plan's list of (column of G, value)
-//                  pairs of b, accumulating in registers.
+//                  pairs of b, accumulating in registers.  With one column per lane the plan deals
+//                  the lists of every chunk to the waves by length, and the partial sums change
+//                  lanes between chunks (swap_owner).
 //   B  S = P^T T   one wave per piece of a row of P^T and 1/8 of the columns; reads rows of T.
-// The path is bandwidth-bound (one pass over G); no matrix cores are involved because the
+// The path streams G once; its main loop is bound by vector-ALU issue (16 widenings and 16 FMAs
+// per pair and 16 rows for bf16), not by HBM.  No matrix cores are involved because the
 // projectors are sparse (d entries per row, Def. 1) and the work is gather + fp32 FMA.
 
 #include "lsp_internal.h"

@@ -146,23 +146,12 @@ __device__ __forceinline__ CompressProblem group_pick(const CompressGroup& g, in
     }
     return o;
 }
-// index of the problem that owns workgroup `block` (uniform; count <= kMaxGroup)
+// index of the problem that owns workgroup `block` (uniform; count <= kMaxGroup); the decompress
+// kernels use this run-time index: they have no small uniform loads to protect, and measured faster
 __device__ __forceinline__ int group_find(const int32_t* first, int count, int block) {
     int p = 0;
     while (p + 1 < count && block >= first[p + 1]) ++p;
     return p;
-}
-struct ApplyProblem { void* W; const float* S; const int32_t* P_idx; const float* P_val; const int32_t* Q_idx; const float* Q_val; int32_t m, n, block; };
-__device__ __forceinline__ ApplyProblem group_pick(const ApplyGroup& g, int block) {
-    ApplyProblem o{g.W[0], g.S[0], g.P_idx[0], g.P_val[0], g.Q_idx[0], g.Q_val[0], g.m[0], g.n[0], block};
-#pragma unroll
-    for (int p = 1; p < kMaxGroup; ++p) {
-        if (p < g.count && block >= g.first[p]) {
-            o.W = g.W[p]; o.S = g.S[p]; o.P_idx = g.P_idx[p]; o.P_val = g.P_val[p]; o.Q_idx = g.Q_idx[p]; o.Q_val = g.Q_val[p];
-            o.m = g.m[p]; o.n = g.n[p]; o.block = block - g.first[p];
-        }
-    }
-    return o;
 }
 #endif
 
