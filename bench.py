@@ -217,6 +217,7 @@ def main():
 
     cbytes = sum(e["cb"] for e in mats)
     dbytes = sum(e["db"] for e in mats)
+    cflop = sum(2 * e["m"] * e["n"] * d + 2 * e["m"] * d * r for e in mats)
     value = (cbytes + dbytes) / (ms_step * 1e-3) / 1e9
     comp_gbs = cbytes / (ms_comp * 1e-3) / 1e9
     deco_gbs = dbytes / (ms_deco * 1e-3) / 1e9
@@ -259,6 +260,10 @@ def main():
                      "bound": "hbm", "achieved": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "traffic": traffic_gc,
+                     # the same launches against the vector-ALU roofline (useful flop only: one FMA per stored
+                     # projector entry and element, 2 m n d + 2 m d r per matrix; widening bf16 is not counted)
+                     "alu": {"TFLOP/s": round(cflop / (ms_gcomp1 * 1e-3) / 1e12, 2), "peak_fp32_vector_TFLOP/s": 157.3,
+                             "frac": round(cflop / (ms_gcomp1 * 1e-3) / 1e12 / 157.3, 4)},
                      "launches": len(layers), "avg_launch_us": round(ms_gcomp1 * 1e3 / len(layers), 2),
                      "algorithmic_bytes_per_launch_avg": int(cbytes / len(layers)),
                      "per_matrix_calls": {"achieved": round(comp_gbs, 1), "frac": round(comp_gbs / HBM_PEAK_GBS, 4),
