@@ -571,7 +571,7 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
             } else if (mycol != kNoColumn) {
 #pragma unroll
                 for (int t = 0; t < kRowsGQ; ++t)
-                    if (ib + t < m) stream_store(&T[(ib + t) * (int64_t)r + mycol], acc[0][t]);
+                    if (ib + t < m) T[(ib + t) * (int64_t)r + mycol] = acc[0][t];
             }
         }
         if (last_chunk) {                                             // the block's sums are out
