@@ -374,7 +374,14 @@ def cpu_baseline(syn, r, d):
         if layer == 31:
             names.append(f"{pb.m}x{pb.n}")
         del S
-    return {"value": round(total_bytes / total_s / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+    # the oracle of the estimation-bias row beyond the step, one 4096 x 4096 matrix (single-threaded as it stands)
+    pb = syn.config4_matrix(31, 3)
+    t = time.time()
+    oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    bias_s = time.time() - t
+    next_rows = {"estimation_bias_s_per_call": round(bias_s, 2),
+                 "sample": "one 4096x4096 bf16 matrix, r=512, d=8, one host thread"}
+    return {"value": round(total_bytes / total_s / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle", "next_rows": next_rows,
             "sample": "compress + decompress-apply of the 14 matrices of two layers (each: " + ", ".join(names) +
                       f"), 1/16 of a step, bf16, r={r}, d={d}; fp64 plain loops, rows split over threads",
             "seconds": round(total_s, 2)}
