@@ -208,7 +208,7 @@ __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* 
                 for (int t = 0; t < kRowsGQ; ++t) {
                     float sum = Tl[t * V + v];
                     for (int o = 1; o < owners; ++o) sum += Tl[t * V + v + o];
-                    if (i0 + t < m) stream_store(&T[(i0 + t) * (int64_t)r + bb], sum);
+                    if (i0 + t < m) T[(i0 + t) * (int64_t)r + bb] = sum;
                 }
             }
         }
@@ -326,7 +326,7 @@ __device__ __forceinline__ void gq_one_slot(ChunkStager<D, VEC>& stg, uint8_t* s
         for (int g = 0; g < kPlanes; ++g)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                if (i0 + g * 4 + t < m) stream_store(&T[(i0 + g * 4 + t) * (int64_t)r + mycol], acc[0][g][t]);
+                if (i0 + g * 4 + t < m) T[(i0 + g * 4 + t) * (int64_t)r + mycol] = acc[0][g][t];
     }
 }
 
@@ -693,7 +693,7 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
                     if (col != kNoColumn) {
 #pragma unroll
                         for (int t = 0; t < kRowsGQ; ++t)
-                            if (ib + t < m) stream_store(&T[(ib + t) * (int64_t)r + col], acc[s][t]);
+                            if (ib + t < m) T[(ib + t) * (int64_t)r + col] = acc[s][t];
                     }
                 }
             }
