@@ -392,3 +392,39 @@ def test_reproject_state_exact_on_relabelled_projectors():
     L.lsp_reproject_state(*dev, r, r, r, 1, Md, Vd, ws, nb, torch.cuda.current_stream())
     torch.cuda.synchronize()
     assert np.array_equal(Md.cpu().numpy().astype(np.float64), Mo) and np.array_equal(Vd.cpu().numpy().astype(np.float64), Vo)
+
+
+# ------------------------------------------------------------------ seeded sweep over odd shapes
+def _sweep_cases():
+    rng = np.random.default_rng(20240611)
+    cases = []
+    for k in range(40):
+        r = int(rng.choice([1, 3, 16, 50, 128, 300, 512, 513, 700, 1100]))
+        d = int(min(r, rng.choice([1, 2, 3, 4, 8, 16])))
+        m = int(rng.integers(1, 180)) if k < 24 else int(rng.choice([15, 16, 17, 31, 33, 255, 257, 640]))
+        n = int(rng.choice([1, 7, 8, 64, 1000, 2048, 2056, 4100, 4104, 6200]))
+        dtype = str(rng.choice(["f32", "f16", "bf16"]))
+        dist = str(rng.choice(["uniform", "zipf"]))
+        cases.append((m, n, r, d, dtype, dist, 7000 + k))
+    return cases
+
+
+@pytest.mark.parametrize("m,n,r,d,dtype,dist,seed", _sweep_cases())
+def test_seeded_shape_sweep(m, n, r, d, dtype, dist, seed):
+    """Shapes nobody would pick by hand: one column, one row, r = 1, chunk boundaries +-8, more columns of T than
+    lanes, every storage type; compress (plan), decompress-apply and the estimation bias against the oracle."""
+    import gpu_util as gu
+    import paper_2406_10181_amd as L
+    pb = syn.make_problem("sweep", m, n, r, d, dtype, seed=seed, g_std=1.0, w_std=1.0, s_std=1.0, index_dist=dist)
+    try:
+        _full_check(pb, tight=2e-4, raw=False)
+    except L.LspError as e:
+        # columns used too unevenly for a plan: the raw entry point is the documented way out
+        assert "unevenly" in str(e), e
+        S_o = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r, threads=THREADS)
+        gu.check_compress(_dp(pb).compress_raw(), S_o, "sweep raw", 2e-4)
+        got = _dp(pb).estimation_bias(planned=False)
+        num, den = oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+        assert abs(got[0] - num) <= 1e-3 * max(num, den) and abs(got[1] - den) <= 1e-5 * den
+        return
+    _bias_check(pb)
