@@ -1,7 +1,9 @@
 /*
  * lsp.h -- C ABI of the MI355X (gfx950) library for the GPU hot path of LSP-Offload
  * (arXiv 2406.10181): compressing a weight gradient through two learned sparse projectors
- * and expanding the CPU-computed subspace update back onto the weight.
+ * and expanding the CPU-computed subspace update back onto the weight; beside the per-step
+ * calls, the two GPU-side pieces of the projector refresh (MaybeUpdate, Alg. 1): the estimation
+ * bias of Def. 2 and the re-projection of the optimiser state.
  *
  * Letters.  G and W are m x n, row-major, leading dimension n.  r is the subspace size
  * (number of columns of P and Q; S is r x r).  d is the number of stored entries per
