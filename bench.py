@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the LSP hot path on one MI355X.
 
-A step is one pass of the whole hot path over the 6.7B-style layer stack (BASELINE config 4):
+A step is one pass of the whole hot path over the 6.7B-style layer stack (benchmark configuration 4):
 32 layers x {down 11008x4096, gate/up 4096x11008, o/v/k/q 4096x4096}, bf16, r = 512, d = 8,
 visited layer by layer in backward order; every matrix gets one lsp_compress_planned
 (S = P^T G Q) and one lsp_decompress_apply (W -= P S Q^T).  The seven matrices of a layer are

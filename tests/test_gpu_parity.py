@@ -36,7 +36,7 @@ def _full_check(pb, tight=5e-5, raw=True):
     return dp
 
 
-# ------------------------------------------------------------------ BASELINE configurations
+# ------------------------------------------------------------------ the five benchmark configurations
 def test_config1_fp32_small():
     dp = _full_check(syn.config1(), tight=2e-6)
     # round trip: decompress the compressed gradient (what MaybeUpdate's bias test composes)
