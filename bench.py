@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--dense-ablation", action="store_true",
                     help="instead of the step: the sparse compress path at d = 2..16 against the same contraction "
                          "with dense bf16 projectors through the vendor GEMM (prints its own JSON line)")
+    ap.add_argument("--other-configs", action="store_true",
+                    help="instead of the step: one-call timings of the other benchmark configurations and of the "
+                         "paper-sized subspaces (prints its own JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path is single-GPU by construction (no collectives are built); run with --gpus 1",
@@ -70,6 +73,9 @@ def main():
     stream = torch.cuda.current_stream()
     if args.dense_ablation:
         print(json.dumps(dense_ablation(torch, syn, L, dev, stream)), flush=True)
+        return
+    if args.other_configs:
+        print(json.dumps(other_configs(torch, syn, L, dev, stream)), flush=True)
         return
     r, d, dtype, code, sz = 512, 8, "bf16", syn.DTYPE_CODE["bf16"], 2
 
@@ -291,6 +297,55 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(syn, r, d)
     print(json.dumps(out), flush=True)
+
+
+def other_configs(torch, syn, L, dev, stream):
+    """One lsp_compress_planned and one lsp_decompress_apply call per matrix, on one stream, for the shapes of the
+    benchmark configurations other than the timed one and for the subspace sizes the paper trained with; uniform
+    projector columns, buffers rotating so that G / W come from HBM.  Times in us per call; percentages are the
+    call's algorithmic bytes per second over the 8 TB/s HBM peak."""
+    cases = [("cfg2", "f16", 2048, 2048, 256, 4), ("cfg3", "f16", 2048, 8192, 512, 4), ("cfg3", "f16", 8192, 2048, 512, 4)]
+    cases += [("cfg5", "bf16", 4096, 16384, r, d) for r, d in ((256, 2), (256, 16), (512, 4), (512, 8), (1024, 2), (1024, 16))]
+    cases += [("fp32", "f32", 4096, 4096, 512, 8), ("paper-sized subspace", "bf16", 4096, 4096, 2048, 8),
+              ("paper-sized subspace", "f16", 2048, 2048, 1280, 4)]
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
+    rows = []
+    for name, dt, m, n, r, d in cases:
+        code, esz = syn.DTYPE_CODE[dt], (4 if dt == "f32" else 2)
+        nbuf = max(3, min(12, int(1.5e9 // (m * n * esz))))
+        rng = np.random.default_rng(1)
+        P_idx, P_val = syn.ell_projector(m, r, d, rng)
+        Q_idx, Q_val = syn.ell_projector(n, r, d, rng)
+        P_idx, P_val, Q_idx, Q_val = [torch.from_numpy(x).to(dev) for x in (P_idx, P_val, Q_idx, Q_val)]
+        Gs = [(torch.randn(m, n, device=dev) * 1e-3).to(tdt[dt]) for _ in range(nbuf)]
+        S = torch.empty(r, r, device=dev)
+        Su = torch.randn(r, r, device=dev) * 1e-3
+        pbytes = L.lsp_plan_bytes(m, n, r, d)
+        plan = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+        L.lsp_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan, pbytes, stream)
+        wb = L.lsp_compress_planned_workspace_bytes(m, n, r, d)
+        ws = torch.empty(wb, dtype=torch.uint8, device=dev)
+        cb, db = algorithmic_bytes(m, n, r, d, esz)
+
+        def run(fn, reps=3):
+            for G in Gs[:2]:
+                fn(G)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(reps):
+                for G in Gs:
+                    fn(G)
+            b.record(stream)
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) * 1e3 / (reps * nbuf)
+        tc = run(lambda G: L.lsp_compress_planned(G, plan, m, n, r, d, S, code, ws, wb, stream))
+        td = run(lambda G: L.lsp_decompress_apply(G, Su, P_idx, P_val, Q_idx, Q_val, m, n, r, d, code, stream))
+        rows.append({"config": name, "dtype": dt, "m": m, "n": n, "r": r, "d": d,
+                     "compress_us": round(tc, 1), "compress_pct_of_hbm_peak": round(cb / tc / 1e3 / HBM_PEAK_GBS * 100, 1),
+                     "decompress_us": round(td, 1), "decompress_pct_of_hbm_peak": round(db / td / 1e3 / HBM_PEAK_GBS * 100, 1)})
+        del Gs, plan, ws
+    return {"what": "one call per matrix on one stream, other configurations", "unit": "us per call", "rows": rows}
 
 
 def dense_ablation(torch, syn, L, dev, stream):
