@@ -98,6 +98,11 @@ def main():
                      S=torch.empty(r, r, device=dev, dtype=torch.float32),
                      P_idx=torch.from_numpy(P_idx).to(dev), P_val=torch.from_numpy(P_val).to(dev),
                      Q_idx=torch.from_numpy(Q_idx).to(dev), Q_val=torch.from_numpy(Q_val).to(dev))
+            # the expand side (decompress-apply, estimation bias) gets the copy of Q whose rows are ordered against
+            # LDS bank conflicts: the same projector, prepared once per change of projectors like the plan
+            qi, qv = np.empty_like(Q_idx), np.empty_like(Q_val)
+            L.lsp_projector_reorder_host(Q_idx, Q_val, n, d, r, qi, qv)
+            e["Qx_idx"], e["Qx_val"] = torch.from_numpy(qi).to(dev), torch.from_numpy(qv).to(dev)
             pbytes = L.lsp_plan_bytes(m, n, r, d)
             e["plan"] = torch.empty(pbytes, dtype=torch.uint8, device=dev)
             L.lsp_plan_build(e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], m, n, r, d, e["plan"], pbytes, stream)
@@ -120,7 +125,7 @@ def main():
     def decompress_all(ms, ns=1):
         for k, e in enumerate(ms):
             q = k % ns
-            L.lsp_decompress_apply(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"],
+            L.lsp_decompress_apply(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Qx_idx"], e["Qx_val"],
                                    e["m"], e["n"], r, d, code, lanes[q])
 
     # grouped mode: the seven matrices of a layer in one call (own S and workspace each); layers
@@ -130,7 +135,7 @@ def main():
             for e in layers[0]] for _ in lanes]
     citems = [L.compress_items([(e["G"], e["plan"], e["S"], gws[li % nstreams][k], gws[li % nstreams][k].numel(),
                                  e["m"], e["n"]) for k, e in enumerate(ly)]) for li, ly in enumerate(layers)]
-    aitems = [L.apply_items([(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], e["m"], e["n"])
+    aitems = [L.apply_items([(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Qx_idx"], e["Qx_val"], e["m"], e["n"])
                              for e in ly]) for ly in layers]
 
     def step_grouped():
@@ -205,7 +210,7 @@ def main():
 
     def bias_all():
         for e in mats:
-            L.lsp_estimation_bias(e["G"], e["S"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], e["m"], e["n"], r, d,
+            L.lsp_estimation_bias(e["G"], e["S"], e["P_idx"], e["P_val"], e["Qx_idx"], e["Qx_val"], e["m"], e["n"], r, d,
                                   bias_out, bias_ws, bias_ws_bytes, code, stream)
     ms_bias = timed(bias_all, sub)
     bbytes = sum(e["cb"] for e in mats)             # one read of G, the projector arrays and S: as for compress

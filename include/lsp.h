@@ -187,6 +187,18 @@ int lsp_compress_planned_grouped(const lsp_compress_item* items, int32_t count,
 int lsp_decompress_apply_grouped(const lsp_apply_item* items, int32_t count,
                                  int32_t r, int32_t d, lsp_dtype dtype, void* stream);
 
+/* Optional preparation for the expand side (lsp_decompress_apply*, lsp_estimation_bias): a copy
+ * of an ELL projector in which the d entries of every row are put in an order that makes the
+ * kernels' LDS gathers collide less.  The projector is the same matrix (Def. 1 fixes which entries
+ * a row has, not their order; they are summed), so the copy can be passed wherever Q is expected;
+ * results differ only by the order of fp32 additions.  Meant for Q (the kernels gather by the
+ * rows of Q); harmless for P.  Like the plan it is made once per change of projectors.
+ *   idx, val           HOST, [rows][d]
+ *   idx_out, val_out   HOST, [rows][d], distinct from the inputs
+ * Returns LSP_OK, LSP_ERR_NULL, LSP_ERR_SHAPE or LSP_ERR_INDEX (an index outside [0, r)). */
+int lsp_projector_reorder_host(const int32_t* idx, const float* val, int64_t rows, int32_t d, int32_t r,
+                               int32_t* idx_out, float* val_out);
+
 /* ------------------------------------------------------------------------------------------
  * Estimation bias of the projector pair on a gradient (Def. 2):
  *     b(P, Q; G) = || P P^T G Q Q^T - G ||_F / || G ||_F ,

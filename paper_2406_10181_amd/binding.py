@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.lsp_decompress_apply_grouped.restype = ctypes.c_int
         L.lsp_estimation_bias.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, ctypes.c_size_t, i32, vp]
         L.lsp_estimation_bias.restype = ctypes.c_int
+        L.lsp_projector_reorder_host.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+        L.lsp_projector_reorder_host.restype = ctypes.c_int
         L.lsp_reproject_state.argtypes = [vp] * 8 + [i64, i64, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         L.lsp_reproject_state.restype = ctypes.c_int
         L.lsp_reproject_state_workspace_bytes.argtypes = [i32]
@@ -189,6 +191,14 @@ def lsp_estimation_bias(G, S, P_idx, P_val, Q_idx, Q_val, m, n, r, d, out, works
                                    m, n, r, d, _ptr(out), _ptr(workspace), workspace_bytes, dtype, _stream(stream))
     if check:
         _check(rc, "lsp_estimation_bias")
+    return rc
+
+
+def lsp_projector_reorder_host(idx, val, rows, d, r, idx_out, val_out, check: bool = True) -> int:
+    """Host arrays (numpy int32 / float32, [rows][d]) in and out."""
+    rc = lib().lsp_projector_reorder_host(_ptr(idx), _ptr(val), rows, d, r, _ptr(idx_out), _ptr(val_out))
+    if check:
+        _check(rc, "lsp_projector_reorder_host")
     return rc
 
 

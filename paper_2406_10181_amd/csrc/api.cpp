@@ -225,6 +225,14 @@ int lsp_estimation_bias(const void* G, const float* S, const int32_t* P_idx, con
     return e == hipSuccess ? LSP_OK : fail_launch(e);
 }
 
+int lsp_projector_reorder_host(const int32_t* idx, const float* val, int64_t rows, int32_t d, int32_t r,
+                               int32_t* idx_out, float* val_out) {
+    if (!idx || !val || !idx_out || !val_out) return LSP_ERR_NULL;
+    if (rows <= 0 || d <= 0 || r <= 0 || d > r || r > LSP_MAX_R || d > LSP_MAX_D || rows * d > INT32_MAX) return LSP_ERR_SHAPE;
+    if (idx == idx_out || val == val_out) return LSP_ERR_SHAPE;
+    return lsp::reorder_rows_host(idx, val, rows, d, r, idx_out, val_out);
+}
+
 size_t lsp_reproject_state_workspace_bytes(int32_t r) {
     if (r <= 0 || r > LSP_MAX_R) return 0;
     return lsp::align_up((size_t)3 * (size_t)r * (size_t)r * sizeof(float), 256);

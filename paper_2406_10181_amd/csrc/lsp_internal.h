@@ -86,6 +86,11 @@ constexpr size_t   kPlanHeaderBytes = 256;
 
 struct RowItem   { int32_t a; int32_t start; int32_t len; int32_t atomic; };
 
+// Copy of an ELL projector with the entries of each row ordered against LDS bank conflicts in the
+// decompress kernels (host arrays; the matrix itself is unchanged).
+int reorder_rows_host(const int32_t* idx, const float* val, int64_t rows, int32_t d, int32_t r,
+                      int32_t* idx_out, float* val_out);
+
 // Upper bounds (depend on shapes only) used to size the plan buffer.
 int    plan_list_cap(int32_t r, int32_t d);
 size_t plan_max_rows(int64_t n, int32_t r, int32_t d);

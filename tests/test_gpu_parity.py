@@ -428,3 +428,34 @@ def test_seeded_shape_sweep(m, n, r, d, dtype, dist, seed):
         assert abs(got[0] - num) <= 1e-3 * max(num, den) and abs(got[1] - den) <= 1e-5 * den
         return
     _bias_check(pb)
+
+
+# ------------------------------------------------------------------ reordered projector rows on the expand side
+@pytest.mark.parametrize("m,n,r,d,dtype", [(100, 3000, 512, 8, "bf16"), (64, 1030, 64, 3, "f16"), (40, 2048, 2048, 8, "bf16")])
+def test_decompress_with_reordered_projector_rows(m, n, r, d, dtype):
+    """The copy of Q made by lsp_projector_reorder_host is the same projector: decompress-apply and the bias with
+    it meet the oracle's result for the original arrays."""
+    import dataclasses
+    import paper_2406_10181_amd as L
+    import gpu_util as gu
+    pb = syn.make_problem("reord", m, n, r, d, dtype, seed=8100 + n, g_std=1.0)
+    qi, qv = np.empty_like(pb.Q_idx), np.empty_like(pb.Q_val)
+    L.lsp_projector_reorder_host(pb.Q_idx, pb.Q_val, n, d, r, qi, qv)
+    pb2 = dataclasses.replace(pb, Q_idx=qi, Q_val=qv)
+    Wp, Wr = oracle.decompress_apply(pb.W, pb.dtype, pb.S_in, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, threads=THREADS)
+    mism = gu.check_decompress(_dp(pb2).decompress(pb.S_in), pb.W, Wp, Wr, pb.dtype, "reordered Q")
+    assert pb.dtype == "f32" or mism < 0.02
+    num, den = oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    got = _dp(pb2).estimation_bias()
+    assert abs(got[0] - num) <= 1e-3 * max(num, den) and abs(got[1] - den) <= 1e-5 * den
+
+
+def test_decompress_with_reordered_rows_exact_on_integers():
+    import dataclasses
+    import paper_2406_10181_amd as L
+    pb = syn.make_integer_problem("reord_int", 70, 2100, 48, 4, "bf16", seed=8200, index_dist="zipf")
+    qi, qv = np.empty_like(pb.Q_idx), np.empty_like(pb.Q_val)
+    L.lsp_projector_reorder_host(pb.Q_idx, pb.Q_val, pb.n, pb.d, pb.r, qi, qv)
+    a = _dp(pb).decompress(pb.S_in)
+    b = _dp(dataclasses.replace(pb, Q_idx=qi, Q_val=qv)).decompress(pb.S_in)
+    assert np.array_equal(a, b)

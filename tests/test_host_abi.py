@@ -291,3 +291,40 @@ def test_plan_build_reports_unplannable_skew():
     Q_idx[:, 0] = 0                      # every row of Q also hits column 0
     assert L.lsp_plan_build_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, buf, nbytes, check=False) == -8
     assert "unevenly" in L.lsp_strerror(-8)
+
+
+# ------------------------------------------------------------------ entry order inside projector rows
+def _gather_cost(idx):
+    """Modelled cycles of the decompress kernels' 128-bit LDS gathers: lane l of a wave owns columns 2l, 2l+1 of a
+    128-column tile; a gather (one entry slot of one of the two columns) is served in four groups of 16 lanes
+    (lane >= 32, parity of lane bits 2..4), each costing its most used bank group (index mod 16)."""
+    groups = [[l for l in range(64) if ((l >= 32) * 2 + (bin((l % 32) // 4).count("1") & 1)) == g] for g in range(4)]
+    n, d = idx.shape
+    total, steps = 0, 0
+    for tile in range(0, n - 127, 128):
+        for c in (0, 1):
+            for k in range(d):
+                total += sum(np.bincount([int(idx[tile + 2 * l + c, k]) % 16 for l in g], minlength=16).max() for g in groups)
+                steps += 1
+    return total / steps
+
+
+@pytest.mark.parametrize("rows,r,d,dist", [(1024, 512, 8, "uniform"), (640, 256, 4, "uniform"), (300, 96, 16, "zipf"), (5, 3, 2, "uniform")])
+def test_projector_reorder_keeps_the_matrix_and_spreads_the_banks(rows, r, d, dist):
+    rng = np.random.default_rng(31 + rows)
+    idx, val = syn.ell_projector(rows, r, d, rng, dist)
+    oi, ov = np.full_like(idx, -1), np.zeros_like(val)
+    L.lsp_projector_reorder_host(idx, val, rows, d, r, oi, ov)
+    # every row keeps its (index, value) pairs, as a multiset
+    for i in range(rows):
+        assert sorted(zip(idx[i].tolist(), val[i].tolist())) == sorted(zip(oi[i].tolist(), ov[i].tolist()))
+    if rows >= 128:
+        before, after = _gather_cost(idx), _gather_cost(oi)
+        assert after <= before
+        if dist == "uniform" and d >= 4:
+            assert after < 0.85 * before, (before, after)
+    # argument errors
+    assert L.lsp_projector_reorder_host(idx, val, rows, d, r, idx, ov, check=False) == -2      # in place is refused
+    assert L.lsp_projector_reorder_host(None, val, rows, d, r, oi, ov, check=False) == -1
+    bad = idx.copy(); bad[0, 0] = r
+    assert L.lsp_projector_reorder_host(bad, val, rows, d, r, oi, ov, check=False) == -6
