@@ -321,6 +321,9 @@ def other_configs(torch, syn, L, dev, stream):
         rng = np.random.default_rng(1)
         P_idx, P_val = syn.ell_projector(m, r, d, rng)
         Q_idx, Q_val = syn.ell_projector(n, r, d, rng)
+        qi, qv = np.empty_like(Q_idx), np.empty_like(Q_val)
+        L.lsp_projector_reorder_host(Q_idx, Q_val, n, d, r, qi, qv)          # the expand side gets the reordered copy of Q
+        Qx_idx, Qx_val = torch.from_numpy(qi).to(dev), torch.from_numpy(qv).to(dev)
         P_idx, P_val, Q_idx, Q_val = [torch.from_numpy(x).to(dev) for x in (P_idx, P_val, Q_idx, Q_val)]
         Gs = [(torch.randn(m, n, device=dev) * 1e-3).to(tdt[dt]) for _ in range(nbuf)]
         S = torch.empty(r, r, device=dev)
@@ -345,7 +348,7 @@ def other_configs(torch, syn, L, dev, stream):
             torch.cuda.synchronize()
             return a.elapsed_time(b) * 1e3 / (reps * nbuf)
         tc = run(lambda G: L.lsp_compress_planned(G, plan, m, n, r, d, S, code, ws, wb, stream))
-        td = run(lambda G: L.lsp_decompress_apply(G, Su, P_idx, P_val, Q_idx, Q_val, m, n, r, d, code, stream))
+        td = run(lambda G: L.lsp_decompress_apply(G, Su, P_idx, P_val, Qx_idx, Qx_val, m, n, r, d, code, stream))
         rows.append({"config": name, "dtype": dt, "m": m, "n": n, "r": r, "d": d,
                      "compress_us": round(tc, 1), "compress_pct_of_hbm_peak": round(cb / tc / 1e3 / HBM_PEAK_GBS * 100, 1),
                      "decompress_us": round(td, 1), "decompress_pct_of_hbm_peak": round(db / td / 1e3 / HBM_PEAK_GBS * 100, 1)})
