@@ -198,6 +198,11 @@ int lsp_decompress_apply_grouped(const lsp_apply_item* items, int32_t count,
  * Returns LSP_OK, LSP_ERR_NULL, LSP_ERR_SHAPE or LSP_ERR_INDEX (an index outside [0, r)). */
 int lsp_projector_reorder_host(const int32_t* idx, const float* val, int64_t rows, int32_t d, int32_t r,
                                int32_t* idx_out, float* val_out);
+/* The same for DEVICE arrays: a set-up call like lsp_plan_build -- it waits for `stream`, copies the
+ * arrays to the host (allocating host memory), reorders there and copies the result into the
+ * device arrays idx_out / val_out; synchronous.  Adds LSP_ERR_LAUNCH to the errors above. */
+int lsp_projector_reorder(const int32_t* idx, const float* val, int64_t rows, int32_t d, int32_t r,
+                          int32_t* idx_out, float* val_out, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Estimation bias of the projector pair on a gradient (Def. 2):

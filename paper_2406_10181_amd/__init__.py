@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     lsp_compress_planned, lsp_compress_planned_workspace_bytes,
     lsp_decompress_apply, lsp_compress_planned_grouped, lsp_decompress_apply_grouped,
     lsp_estimation_bias, lsp_estimation_bias_workspace_bytes,
-    lsp_reproject_state, lsp_reproject_state_workspace_bytes, lsp_projector_reorder_host,
+    lsp_reproject_state, lsp_reproject_state_workspace_bytes, lsp_projector_reorder_host, lsp_projector_reorder,
     lsp_compress_item, lsp_apply_item, compress_items, apply_items, lsp_validate_projector, lsp_strerror, lsp_version,
     torch_dtype_code,
 )

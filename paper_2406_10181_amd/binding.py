@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.lsp_estimation_bias.restype = ctypes.c_int
         L.lsp_projector_reorder_host.argtypes = [vp, vp, i64, i32, i32, vp, vp]
         L.lsp_projector_reorder_host.restype = ctypes.c_int
+        L.lsp_projector_reorder.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        L.lsp_projector_reorder.restype = ctypes.c_int
         L.lsp_reproject_state.argtypes = [vp] * 8 + [i64, i64, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         L.lsp_reproject_state.restype = ctypes.c_int
         L.lsp_reproject_state_workspace_bytes.argtypes = [i32]
@@ -199,6 +201,14 @@ def lsp_projector_reorder_host(idx, val, rows, d, r, idx_out, val_out, check: bo
     rc = lib().lsp_projector_reorder_host(_ptr(idx), _ptr(val), rows, d, r, _ptr(idx_out), _ptr(val_out))
     if check:
         _check(rc, "lsp_projector_reorder_host")
+    return rc
+
+
+def lsp_projector_reorder(idx, val, rows, d, r, idx_out, val_out, stream=None, check: bool = True) -> int:
+    """Device arrays in and out; waits for the stream."""
+    rc = lib().lsp_projector_reorder(_ptr(idx), _ptr(val), rows, d, r, _ptr(idx_out), _ptr(val_out), _stream(stream))
+    if check:
+        _check(rc, "lsp_projector_reorder")
     return rc
 
 

@@ -233,6 +233,27 @@ int lsp_projector_reorder_host(const int32_t* idx, const float* val, int64_t row
     return lsp::reorder_rows_host(idx, val, rows, d, r, idx_out, val_out);
 }
 
+int lsp_projector_reorder(const int32_t* idx, const float* val, int64_t rows, int32_t d, int32_t r,
+                          int32_t* idx_out, float* val_out, void* stream) {
+    if (!idx || !val || !idx_out || !val_out) return LSP_ERR_NULL;
+    if (rows <= 0 || d <= 0 || r <= 0 || d > r || r > LSP_MAX_R || d > LSP_MAX_D || rows * d > INT32_MAX) return LSP_ERR_SHAPE;
+    if (idx == idx_out || val == val_out) return LSP_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Order after whatever produced the arrays on this stream, bring them to the host, reorder, send back.
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail_launch(e);
+    const size_t count = (size_t)rows * (size_t)d;
+    std::vector<int32_t> hi(count), ho(count);
+    std::vector<float> hv(count), hw(count);
+    if ((e = hipMemcpy(hi.data(), idx, count * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
+    if ((e = hipMemcpy(hv.data(), val, count * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
+    const int rc = lsp::reorder_rows_host(hi.data(), hv.data(), rows, d, r, ho.data(), hw.data());
+    if (rc != LSP_OK) return rc;
+    if ((e = hipMemcpy(idx_out, ho.data(), count * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail_launch(e);
+    if ((e = hipMemcpy(val_out, hw.data(), count * 4, hipMemcpyHostToDevice)) != hipSuccess) return fail_launch(e);
+    return LSP_OK;
+}
+
 size_t lsp_reproject_state_workspace_bytes(int32_t r) {
     if (r <= 0 || r > LSP_MAX_R) return 0;
     return lsp::align_up((size_t)3 * (size_t)r * (size_t)r * sizeof(float), 256);

@@ -450,6 +450,20 @@ def test_decompress_with_reordered_projector_rows(m, n, r, d, dtype):
     assert abs(got[0] - num) <= 1e-3 * max(num, den) and abs(got[1] - den) <= 1e-5 * den
 
 
+def test_projector_reorder_on_device_arrays_equals_host():
+    import torch
+    import paper_2406_10181_amd as L
+    rng = np.random.default_rng(8300)
+    idx, val = syn.ell_projector(1000, 300, 8, rng, "uniform")
+    hi, hv = np.empty_like(idx), np.empty_like(val)
+    L.lsp_projector_reorder_host(idx, val, 1000, 8, 300, hi, hv)
+    di, dv = torch.from_numpy(idx).cuda(), torch.from_numpy(val).cuda()
+    oi, ov = torch.empty_like(di), torch.empty_like(dv)
+    L.lsp_projector_reorder(di, dv, 1000, 8, 300, oi, ov, torch.cuda.current_stream())
+    assert np.array_equal(oi.cpu().numpy(), hi) and np.array_equal(ov.cpu().numpy(), hv)
+    assert L.lsp_projector_reorder(di, dv, 1000, 8, 300, di, ov, None, check=False) == -2
+
+
 def test_decompress_with_reordered_rows_exact_on_integers():
     import dataclasses
     import paper_2406_10181_amd as L

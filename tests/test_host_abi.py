@@ -326,5 +326,7 @@ def test_projector_reorder_keeps_the_matrix_and_spreads_the_banks(rows, r, d, di
     # argument errors
     assert L.lsp_projector_reorder_host(idx, val, rows, d, r, idx, ov, check=False) == -2      # in place is refused
     assert L.lsp_projector_reorder_host(None, val, rows, d, r, oi, ov, check=False) == -1
+    assert L.lsp_projector_reorder(None, 0x1000, rows, d, r, 0x2000, 0x3000, None, check=False) == -1     # checked before any HIP call
+    assert L.lsp_projector_reorder(0x1000, 0x1000, rows, r + 1, r, 0x2000, 0x3000, None, check=False) == -2
     bad = idx.copy(); bad[0, 0] = r
     assert L.lsp_projector_reorder_host(bad, val, rows, d, r, oi, ov, check=False) == -6
