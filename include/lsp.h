@@ -27,8 +27,12 @@
  * void*; NULL = the default stream) and return; work on one stream runs in call order
  * (Alg. 3 issues these per layer, in backward order, asynchronously).
  *
- * Errors.  Every call returns LSP_OK (0) or a negative lsp_status.  On error nothing has
- * been enqueued and no output has been touched.
+ * Errors.  Every call returns LSP_OK (0) or a negative lsp_status.  All argument checks are
+ * made before the first HIP call: on LSP_ERR_NULL / SHAPE / DTYPE / WORKSPACE / ALIGN nothing has
+ * been enqueued and no output has been touched.  LSP_ERR_LAUNCH means the HIP runtime refused a
+ * launch (or, in the set-up calls, a copy); a call that consists of several kernels, or a grouped
+ * call that serves its problems one by one, may then have enqueued part of its work already, and
+ * its outputs are undefined.
  */
 #ifndef LSP_H
 #define LSP_H
@@ -93,6 +97,11 @@ int lsp_compress(const void* G,
 /* Bytes of device scratch lsp_compress needs (0 on invalid shapes). */
 size_t lsp_compress_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
 
+/* One size that serves every call of this header on an (m, n, r, d) problem: the largest of the
+ * per-call workspace queries below (0 on invalid shapes or dtype).  The library holds no
+ * workspace of its own: scratch is always an argument of the call that uses it. */
+size_t lsp_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype);
+
 /* ------------------------------------------------------------------------------------------
  * Projector plan: a device-resident, column-sorted copy of P and Q for one (m, n, r, d)
  * problem, valid until the projector arrays change (every CheckFreq steps at most, Alg. 1).
@@ -120,7 +129,11 @@ int lsp_plan_build_host(const int32_t* P_idx, const float* P_val,
  * atomics unless a row of P^T has more than 256 entries (heavily skewed projectors), and
  * bit-reproducible from run to run whenever no row of P^T had to be cut for that reason
  * (columns of Q that are shared among several lanes are summed in a fixed order).
- * workspace: at least lsp_compress_planned_workspace_bytes(m,n,r,d) bytes. */
+ * workspace: at least lsp_compress_planned_workspace_bytes(m,n,r,d) bytes.
+ * The plan lives in device memory, so the host cannot check it: the kernels compare the (m, n, r,
+ * d) recorded in the plan with those of the call, and when they differ (a plan built for another
+ * problem, or a buffer that holds no plan) they follow none of its offsets, touch nothing but S
+ * and fill S with NaN -- the call still returns LSP_OK, the mistake shows in S. */
 int lsp_compress_planned(const void* G, const void* plan,
                          int64_t m, int64_t n, int32_t r, int32_t d,
                          float* S, lsp_dtype dtype,

@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.lsp_compress.restype = ctypes.c_int
         L.lsp_compress_workspace_bytes.argtypes = [i64, i64, i32, i32]
         L.lsp_compress_workspace_bytes.restype = sz
+        L.lsp_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
+        L.lsp_workspace_bytes.restype = sz
         L.lsp_plan_bytes.argtypes = [i64, i64, i32, i32]
         L.lsp_plan_bytes.restype = sz
         L.lsp_plan_build.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
@@ -130,6 +132,10 @@ def lsp_version() -> int:
 
 def lsp_compress_workspace_bytes(m, n, r, d) -> int:
     return lib().lsp_compress_workspace_bytes(m, n, r, d)
+
+
+def lsp_workspace_bytes(m, n, r, d, dtype: int) -> int:
+    return int(lib().lsp_workspace_bytes(m, n, r, d, dtype))
 
 
 def lsp_compress_planned_workspace_bytes(m, n, r, d) -> int:

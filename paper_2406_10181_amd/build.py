@@ -1,6 +1,10 @@
-"""Builds the HIP library in-tree with hipcc for gfx950 (cross-compiles without a GPU)."""
+"""Builds the HIP library in-tree with hipcc for gfx950 (cross-compiles without a GPU).
+
+Every source is compiled to an object of its own (in parallel) and the objects are linked into
+liblsp_hip.so beside this file."""
 from __future__ import annotations
 
+import concurrent.futures
 import os
 import subprocess
 import sys
@@ -9,10 +13,12 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblsp_hip.so")
-SOURCES = ["api.cpp", "plan.cpp", "compress.hip", "decompress.hip", "reproject.hip"]
+OBJDIR = os.path.join(PKG, "_build")
+SOURCES = ["api.cpp", "plan.cpp", "plan_device.hip", "compress.hip", "decompress.hip", "reproject.hip", "fitgrad.hip",
+           "noalloc.hip"]
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-munsafe-fp-atomics",
     # no packed-fp32 instructions: the compiler would otherwise form them from plain float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -20,17 +26,30 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, defines=()) -> str:
+def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, defines=(), sources=None, jobs: int = 8) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    for s in SOURCES:
-        cmd += ["-x", "hip", os.path.join(CSRC, s)]
-    cmd += [f"-D{x}" for x in defines] + ["-o", out]
-    if save_temps:
-        cmd += ["-save-temps=obj"]
+    sources = [s for s in (sources or SOURCES) if os.path.exists(os.path.join(CSRC, s))]
+    tag = os.path.splitext(os.path.basename(out))[0]
+    objdir = os.path.join(OBJDIR, tag)
+    os.makedirs(objdir, exist_ok=True)
+    base = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC] + [f"-D{x}" for x in defines]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+        cmd = base + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        if save_temps:
+            cmd += ["-save-temps=obj"]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd, cwd=objdir)
+        return obj
+
+    with concurrent.futures.ThreadPoolExecutor(max_workers=max(1, min(jobs, len(sources)))) as pool:
+        objs = list(pool.map(compile_one, sources))
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", out]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd, cwd=PKG)
+        print(" ".join(link), flush=True)
+    subprocess.check_call(link, cwd=objdir)
     return out
 
 

@@ -1,17 +1,25 @@
 // extern "C" entry points: argument checks, workspace carving, kernel launches.
+#include <algorithm>
 #include <cstring>
 #include <vector>
 
 #include "lsp_internal.h"
 
 namespace {
-
 thread_local int g_last_hip_error = 0;
+}
 
-int fail_launch(hipError_t e) {
+namespace lsp {
+// Remembers the raw HIP error for lsp_last_hip_error() and returns LSP_ERR_LAUNCH.
+int note_hip_error(hipError_t e) {
     g_last_hip_error = (int)e;
     return LSP_ERR_LAUNCH;
 }
+}  // namespace lsp
+
+namespace {
+
+int fail_launch(hipError_t e) { return lsp::note_hip_error(e); }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -40,6 +48,14 @@ size_t lsp_compress_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) 
 size_t lsp_compress_planned_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
     if (check_shape(m, n, r, d) != LSP_OK) return 0;
     return t_bytes(m, r);
+}
+
+size_t lsp_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype dtype) {
+    if (check_shape(m, n, r, d) != LSP_OK || check_dtype(dtype) != LSP_OK) return 0;
+    size_t need = t_bytes(m, r);                                                    // both compress entries
+    need = std::max(need, lsp_estimation_bias_workspace_bytes(m, n, r, d));
+    need = std::max(need, lsp_reproject_state_workspace_bytes(r));
+    return need;
 }
 
 size_t lsp_plan_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {

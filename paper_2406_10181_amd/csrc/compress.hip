@@ -21,6 +21,18 @@ namespace lsp {
 constexpr int kPlaneStride = kChunk * 16 + 16;   // bytes; last 16 bytes of a plane stay zero
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// A plan is only followed when its header names this very problem: the offsets and counts in it
+// index S and T with the call's r and m, so a plan built for other sizes (or a buffer that holds no
+// plan at all) must not be walked.  Kernel A then fills S with NaN, which is how the caller sees
+// the mistake, and kernel B does nothing; all kernels exit normally.
+__device__ __forceinline__ bool plan_matches(PlanHeaderPtr H, int m, int n, int r, int d) {
+    return H->magic == kPlanMagic && H->m == m && H->n == n && H->r == r && H->d == d;
+}
+__device__ __forceinline__ void poison_s(float* __restrict__ S, int r, int block, int nblocks, int tid, int nthreads) {
+    const int64_t total = (int64_t)r * r;
+    for (int64_t k = (int64_t)block * nthreads + tid; k < total; k += (int64_t)nblocks * nthreads) S[k] = __builtin_nanf("");
+}
+
 // ----------------------------------------------------------------------------------------------
 // eight consecutive elements of one row, as loaded
 template <typename D> struct Oct;
@@ -712,7 +724,7 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
 
 // Kernel A for fp16 / bf16 with n % 8 == 0.
 template <typename D>
-__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r, int blocks_per_wg) {
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r, int d, int blocks_per_wg) {
     extern __shared__ __align__(16) uint8_t smem[];
     const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
     const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
@@ -728,7 +740,10 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
     const int nblk = min(blocks_per_wg, (int)((m - i0 + kRowsGQ - 1) / kRowsGQ));   // row blocks of this workgroup
 
     PlanHeaderPtr H = as_const<PlanHeader>(plan);
-    if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
+    if (!plan_matches(H, m, n, r, d)) {                               // not a plan for this problem
+        poison_s(S, r, block, nblocks, tid, kThreadsGQ);
+        return;
+    }
     if (H->p_any_split) {
         const int64_t total = (int64_t)r * r;
         for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
@@ -742,7 +757,7 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
 }
 
 template <typename D, bool VEC>
-__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup grp, int r) {
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup grp, int r, int d) {
     extern __shared__ __align__(16) uint8_t smem[];
     const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
     const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
@@ -760,7 +775,10 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup 
     stg.fetch(G, i0, m, n, 0, tid);                                   // depends on nothing but the arguments
 
     PlanHeaderPtr H = as_const<PlanHeader>(plan);
-    if (H->magic != kPlanMagic || H->r != r || H->n != n) return;     // not a plan for this problem: do nothing
+    if (!plan_matches(H, m, n, r, d)) {                               // not a plan for this problem
+        poison_s(S, r, block, nblocks, tid, kThreadsGQ);
+        return;
+    }
     // S must start at zero only when some row of P^T was cut into pieces (kernel B then adds).
     if (H->p_any_split) {
         const int64_t total = (int64_t)r * r;
@@ -776,13 +794,14 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq(const CompressGroup 
 // row of P^T and one stripe of 256 columns, one column per thread.
 constexpr int kThreadsB = 256;
 constexpr int kStripeQuads = 64;                              // column quads (float4) per stripe
-__global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup grp, int r, int nstripes) {
+__global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup grp, int r, int d, int nstripes) {
     const CompressProblem pr = group_pick(grp, (int)blockIdx.x, true);
     const uint8_t* __restrict__ plan = pr.plan;
     const float* __restrict__ T = pr.T;
     float* __restrict__ S = pr.S;
     const int block = pr.block_pt;
     PlanHeaderPtr H = as_const<PlanHeader>(plan);
+    if (!plan_matches(H, pr.m, pr.n, r, d)) return;                   // kernel A has filled S with NaN
     const int stripe = block % nstripes, item = block / nstripes;
     if (item >= H->p_nitems) return;
     const auto* itp = as_const<int32_t>(plan + H->off_p_item) + 4 * item;    // RowItem, field by field
@@ -807,7 +826,7 @@ __global__ __launch_bounds__(kThreadsB) void k_compress_pt(const CompressGroup g
 // per stripe), group g takes entries g, g + groups, ...; the groups' sums meet through lane
 // exchanges in a fixed order.
 template <int LG>
-__global__ __launch_bounds__(kThreadsB) void k_compress_pt8(const CompressGroup grp, int r, int sq) {
+__global__ __launch_bounds__(kThreadsB) void k_compress_pt8(const CompressGroup grp, int r, int d, int sq) {
     constexpr int NG = kWave / LG;                            // entry groups per wave
     const CompressProblem pr = group_pick(grp, (int)blockIdx.x, true);
     const uint8_t* __restrict__ plan = pr.plan;
@@ -815,6 +834,7 @@ __global__ __launch_bounds__(kThreadsB) void k_compress_pt8(const CompressGroup 
     float* __restrict__ S = pr.S;
     const int block = pr.block_pt;
     PlanHeaderPtr H = as_const<PlanHeader>(plan);
+    if (!plan_matches(H, pr.m, pr.n, r, d)) return;                   // kernel A has filled S with NaN
     const int stripe = block & 7;
     const int item = (block >> 3) * (kThreadsB / kWave) + (int)(threadIdx.x >> 6);
     if (item >= H->p_nitems) return;
@@ -931,24 +951,25 @@ static int gq_blocks_per_wg(const CompressGroup& g, lsp_dtype dtype) {
 }
 
 template <typename D>
-static hipError_t launch_gq(const CompressGroup& g, int32_t r, int blocks_per_wg, hipStream_t st) {
-    const size_t lds = (size_t)kPlanes * kPlaneStride;       // >= 64 r bytes for every supported r
+static hipError_t launch_gq(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st) {
+    constexpr size_t lds = (size_t)kPlanes * kPlaneStride;   // >= 64 r bytes for every supported r
     const bool vec = (g.n[0] % 8) == 0;
     const unsigned grid = (unsigned)g.first_gq[g.count];
     hipError_t e;
     if constexpr (D::size == 2) {
         if (vec) {
-            auto kern = k_compress_gq16<D>;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsGQ), lds, st, g, (int)r, blocks_per_wg);
+            if ((e = allow_dynamic_lds<k_compress_gq16<D>>(lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL(k_compress_gq16<D>, dim3(grid), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d, blocks_per_wg);
             return hipGetLastError();
         }
     }
-    auto kern = vec ? k_compress_gq<D, true> : k_compress_gq<D, false>;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsGQ), lds, st, g, (int)r);
+    if (vec) {
+        if ((e = allow_dynamic_lds<k_compress_gq<D, true>>(lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((k_compress_gq<D, true>), dim3(grid), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d);
+    } else {
+        if ((e = allow_dynamic_lds<k_compress_gq<D, false>>(lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((k_compress_gq<D, false>), dim3(grid), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d);
+    }
     return hipGetLastError();
 }
 
@@ -964,20 +985,20 @@ hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_d
     }
     hipError_t e;
     switch (dtype) {
-        case LSP_F32:  e = launch_gq<F32>(g, r, bpw, st); break;
-        case LSP_F16:  e = launch_gq<F16>(g, r, bpw, st); break;
-        default:       e = launch_gq<BF16>(g, r, bpw, st); break;
+        case LSP_F32:  e = launch_gq<F32>(g, r, d, bpw, st); break;
+        case LSP_F16:  e = launch_gq<F16>(g, r, d, bpw, st); break;
+        default:       e = launch_gq<BF16>(g, r, d, bpw, st); break;
     }
     if (e != hipSuccess) return e;
     const unsigned blocks = (unsigned)g.first_pt[g.count];
     if (striped) {
         const int sq = ((r >> 2) + 7) / 8;
-        if (sq <= 16)      hipLaunchKernelGGL(k_compress_pt8<16>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, sq);
-        else if (sq <= 32) hipLaunchKernelGGL(k_compress_pt8<32>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, sq);
-        else               hipLaunchKernelGGL(k_compress_pt8<64>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, sq);
+        if (sq <= 16)      hipLaunchKernelGGL(k_compress_pt8<16>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, (int)d, sq);
+        else if (sq <= 32) hipLaunchKernelGGL(k_compress_pt8<32>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, (int)d, sq);
+        else               hipLaunchKernelGGL(k_compress_pt8<64>, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, (int)d, sq);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(k_compress_pt, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, nstripes);
+    hipLaunchKernelGGL(k_compress_pt, dim3(blocks), dim3(kThreadsB), 0, st, g, (int)r, (int)d, nstripes);
     return hipGetLastError();
 }
 
@@ -985,10 +1006,9 @@ template <typename D>
 static hipError_t launch_raw_gq(const void* G, const int32_t* Q_idx, const float* Q_val, float* T,
                                 int64_t m, int64_t n, int32_t r, int32_t d, hipStream_t st) {
     const size_t lds = (size_t)kRawRows * r * sizeof(float);
-    auto kern = k_raw_gq<D>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds<k_raw_gq<D>>((size_t)kRawRows * LSP_MAX_R * sizeof(float));
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((m + kRawRows - 1) / kRawRows)), dim3(256), lds, st,
+    hipLaunchKernelGGL(k_raw_gq<D>, dim3((unsigned)((m + kRawRows - 1) / kRawRows)), dim3(256), lds, st,
                        reinterpret_cast<const typename D::elem*>(G), Q_idx, Q_val, T, (int)m, (int)n, (int)r, (int)d);
     return hipGetLastError();
 }

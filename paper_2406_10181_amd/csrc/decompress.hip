@@ -360,17 +360,15 @@ static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st, 
     // d = 16: a pass holds 32 (column, value) pairs per thread, so only one pass fits the registers
 #define LSP_LAUNCH_FAST(DDV)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, (DDV == 16 ? 1 : DEPTH), NORMS>;                            \
-        const size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                              \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        if (e != hipSuccess) return e;                                                                         \
+        constexpr auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, (DDV == 16 ? 1 : DEPTH), NORMS>;                  \
+        constexpr size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                          \
+        if ((e = allow_dynamic_lds<kern>(lds)) != hipSuccess) return e;                                        \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, g, (int)r, partial);                           \
     } while (0)
     if (!fast_shape(g.n[0], r, d)) {
-        auto kern = k_decompress_any<D, RG, NORMS>;
+        constexpr auto kern = k_decompress_any<D, RG, NORMS>;
         const size_t lds = (size_t)RG * r * 16;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        if ((e = allow_dynamic_lds<kern>((size_t)RG * LSP_MAX_R * 16)) != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreadsD), lds, st, static_cast<E*>(g.W[0]), g.S[0], g.P_idx[0], g.P_val[0],
                            g.Q_idx[0], g.Q_val[0], (int)g.m[0], (int)g.n[0], (int)r, (int)d, partial);
     }

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "lsp.h"
 
 namespace lsp {
@@ -25,6 +27,9 @@ constexpr uint32_t kNoColumn = 0xFFFFu;      // virtual column slot without a co
 constexpr uint32_t kSharedColumn = 0x8000u;  // flag: the column is owned by several lanes
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Remembers the raw HIP error for lsp_last_hip_error() and returns LSP_ERR_LAUNCH.
+int note_hip_error(hipError_t e);
 
 // LDS byte offset, inside one 4-row plane, of local column j of a staged chunk.
 // Columns are stored as [j & 7][j >> 3] in units of 16 bytes (4 rows x fp32), so that the 64
@@ -191,6 +196,21 @@ struct F16 { using elem = uint16_t; static constexpr int size = 2; };
 struct BF16{ using elem = uint16_t; static constexpr int size = 2; };
 
 #if defined(__HIPCC__)
+// Lets kernel `Kern` use up to `bytes` of dynamic LDS.  The attribute belongs to the (kernel, device)
+// pair and does not change afterwards, so the runtime is asked once per pair, not on every launch of
+// the per-step path.
+template <auto Kern>
+static inline hipError_t allow_dynamic_lds(size_t bytes) {
+    static std::atomic<uint64_t> done{0};                   // bit k: set on device k (devices >= 64: always asked)
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 64 && ((done.load(std::memory_order_acquire) >> dev) & 1u)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev < 64) done.fetch_or((uint64_t)1 << dev, std::memory_order_release);
+    return e;
+}
+
 // Streaming accesses to the big matrices (each byte of G and W is touched once per call): marked
 // non-temporal so that they do not evict the small, heavily re-read operands (S, the projector
 // arrays, the plan) from the XCD's L2.

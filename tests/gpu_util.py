@@ -38,6 +38,14 @@ class DeviceProblem:
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
         self.plan = None
         self.plan_bytes = 0
+        self.Qx_idx, self.Qx_val = self.Q_idx, self.Q_val        # what the expand side (decompress, bias) is handed
+
+    def use_reordered_q(self):
+        """The expand side gets the copy of Q with each row's entries ordered against LDS bank conflicts."""
+        pb = self.pb
+        qi, qv = np.empty_like(pb.Q_idx), np.empty_like(pb.Q_val)
+        L.lsp_projector_reorder_host(pb.Q_idx, pb.Q_val, pb.n, pb.d, pb.r, qi, qv)
+        self.Qx_idx, self.Qx_val = to_device(qi), to_device(qv)
 
     def build_plan(self):
         pb = self.pb
@@ -69,7 +77,7 @@ class DeviceProblem:
         pb = self.pb
         Wd = self.W.clone()
         Sd = torch.from_numpy(np.ascontiguousarray(S_in, dtype=np.float32)).cuda()
-        L.lsp_decompress_apply(Wd, Sd, self.P_idx, self.P_val, self.Q_idx, self.Q_val, pb.m, pb.n, pb.r, pb.d,
+        L.lsp_decompress_apply(Wd, Sd, self.P_idx, self.P_val, self.Qx_idx, self.Qx_val, pb.m, pb.n, pb.r, pb.d,
                                self.code, torch.cuda.current_stream())
         torch.cuda.synchronize()
         return to_host(Wd, pb.dtype)
@@ -87,7 +95,7 @@ class DeviceProblem:
         nb = L.lsp_estimation_bias_workspace_bytes(pb.m, pb.n, pb.r, pb.d)
         ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
         out = torch.full((3,), float("nan"), dtype=torch.float32, device="cuda")
-        L.lsp_estimation_bias(self.G, self.S, self.P_idx, self.P_val, self.Q_idx, self.Q_val, pb.m, pb.n, pb.r, pb.d,
+        L.lsp_estimation_bias(self.G, self.S, self.P_idx, self.P_val, self.Qx_idx, self.Qx_val, pb.m, pb.n, pb.r, pb.d,
                               out, ws, nb, self.code, torch.cuda.current_stream())
         torch.cuda.synchronize()
         assert torch.equal(before.view(torch.uint8), self.G.view(torch.uint8)), "the bias pass must not write G"

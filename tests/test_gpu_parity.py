@@ -61,7 +61,7 @@ def test_config4_bf16_layer_shapes(which):
     _full_check(syn.config4_matrix(31, which), raw=(which == 3))
 
 
-@pytest.mark.parametrize("r,d", [(256, 16), (512, 8), (1024, 2), (1024, 16)])
+@pytest.mark.parametrize("r,d", [(r, d) for r in (256, 512, 1024) for d in (2, 4, 8, 16)])
 def test_config5_bf16_zipf_wide(r, d):
     # skewed columns: lists are cut into pieces and summed with atomics; accumulation error grows
     # with the number of terms per entry (up to ~2.6e5), still far below the bar
@@ -154,13 +154,51 @@ def test_planned_path_is_reproducible_and_plan_reusable():
     gu.check_compress(S2, S2_o, "cfg2 second gradient")
 
 
-def _grouped_case(pbs, tight=5e-5):
-    """Grouped calls against the oracle, and bit for bit against the single calls."""
+def test_plan_of_another_problem_is_not_followed():
+    """A plan built for other sizes, or a buffer that holds no plan: the kernels follow none of its offsets,
+    write nothing but S, and S comes back filled with NaN; the next correct call works."""
+    import torch
+    import gpu_util as gu
+    import paper_2406_10181_amd as L
+    pb = syn.make_problem("mismatch", 200, 2304, 128, 4, "bf16", seed=77)
+    dp = _dp(pb)
+    stream = torch.cuda.current_stream()
+    others = [(264, 2304, 128, 4), (200, 4096, 128, 4), (200, 2304, 256, 4), (200, 2304, 128, 8)]   # m, n, r, d differ in turn
+    plans = []
+    for (m2, n2, r2, d2) in others:
+        rng = np.random.default_rng(m2 + n2 + r2 + d2)
+        pi, pv = syn.ell_projector(m2, r2, d2, rng)
+        qi, qv = syn.ell_projector(n2, r2, d2, rng)
+        nb = L.lsp_plan_bytes(m2, n2, r2, d2)
+        host = np.zeros(nb, dtype=np.uint8)
+        L.lsp_plan_build_host(pi, pv, qi, qv, m2, n2, r2, d2, host, nb)
+        plans.append(torch.from_numpy(host).cuda())
+    plans.append(torch.zeros(4096, dtype=torch.uint8, device="cuda"))          # no plan at all
+    for k, plan in enumerate(plans):
+        print(f"[case] foreign plan {k}", flush=True)
+        dp.S.fill_(1.0)
+        dp.ws.fill_(0x5A)
+        rc = L.lsp_compress_planned(dp.G, plan, pb.m, pb.n, pb.r, pb.d, dp.S, dp.code, dp.ws, dp.ws_bytes, stream, check=False)
+        torch.cuda.synchronize()
+        assert rc == 0
+        assert torch.isnan(dp.S).all(), "S must be NaN-filled when the plan does not belong to the problem"
+        assert (dp.ws == 0x5A).all(), "nothing but S may be written"
+    S_o = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    gu.check_compress(dp.compress_planned(), S_o, "after the foreign plans")
+
+
+def _grouped_case(pbs, tight=5e-5, reordered_q=False):
+    """Grouped calls against the oracle, and bit for bit against the single calls.  reordered_q: the expand
+    side gets the copy of Q made by lsp_projector_reorder_host (the same projector, so the oracle keeps the
+    original arrays)."""
     import torch
     import gpu_util as gu
     import paper_2406_10181_amd as L
     r, d, code = pbs[0].r, pbs[0].d, syn.DTYPE_CODE[pbs[0].dtype]
     dps = [_dp(pb) for pb in pbs]
+    if reordered_q:
+        for dp in dps:
+            dp.use_reordered_q()
     for dp in dps:
         dp.build_plan()
     singles = [dp.compress_planned() for dp in dps]
@@ -180,7 +218,7 @@ def _grouped_case(pbs, tight=5e-5):
     W_single = [dp.decompress(dp.pb.S_in) for dp in dps]
     Wd = [dp.W.clone() for dp in dps]
     Sd = [torch.from_numpy(np.ascontiguousarray(dp.pb.S_in, dtype=np.float32)).cuda() for dp in dps]
-    aitems = L.apply_items([(w, s, dp.P_idx, dp.P_val, dp.Q_idx, dp.Q_val, dp.pb.m, dp.pb.n)
+    aitems = L.apply_items([(w, s, dp.P_idx, dp.P_val, dp.Qx_idx, dp.Qx_val, dp.pb.m, dp.pb.n)
                             for w, s, dp in zip(Wd, Sd, dps)])
     L.lsp_decompress_apply_grouped(aitems, len(dps), r, d, code, stream)
     torch.cuda.synchronize()
@@ -236,14 +274,13 @@ def test_paper_sized_subspaces(m, n, r, d, dtype):
     _bias_check(syn.make_problem("paper_r_bias", m, n, r, d, dtype, seed=950 + d, g_std=1.0))
 
 
-def test_grouped_layer_of_config4():
-    # the seven matrices of one layer of the 6.7B-style stack, at full size, as bench.py launches them:
-    # sampled rows against the oracle, everything bit for bit against the single calls
-    import torch
-    import gpu_util as gu
-    import paper_2406_10181_amd as L
-    pbs = [syn.config4_matrix(31, which) for which in (0, 1, 3)]       # down, gate, o: one of each shape
-    _grouped_case(pbs)
+@pytest.mark.parametrize("layer", [31, 16, 0])
+def test_grouped_layer_of_config4(layer):
+    # all seven matrices of a layer of the 6.7B-style stack, at full size, in one grouped call per kernel family
+    # with the reordered copy of Q on the expand side -- the launches bench.py times: every element against
+    # the oracle, and bit for bit against the single calls
+    pbs = [syn.config4_matrix(layer, which) for which in range(7)]
+    _grouped_case(pbs, reordered_q=True)
 
 
 def test_fp16_subnormals_are_not_flushed():
@@ -279,14 +316,20 @@ def test_validate_projector_and_plan_index_error():
 
 
 # ------------------------------------------------------------------ estimation bias (Def. 2)
-def _bias_check(pb, tol=1e-3):
+BIAS_NUM_RTOL = 2e-4      # on || P S Q^T - G ||_F^2, relative to itself
+BIAS_NUM_FLOOR = 2e-6     # plus this fraction of || G ||_F^2
+
+
+def _bias_check(pb, tol=2e-4):
     print(f"[case] bias {pb.name} m={pb.m} n={pb.n} r={pb.r} d={pb.d} {pb.dtype}", flush=True)
     num, den = oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
     got = _dp(pb).estimation_bias()
     assert abs(got[1] - den) <= 1e-5 * den, f"{pb.name}: ||G||^2 {got[1]} vs {den}"
-    assert abs(got[0] - num) <= tol * max(num, den), f"{pb.name}: numerator {got[0]} vs {num}"
+    # relative to the numerator itself (it is small when the projectors fit well), with a floor for the fp32
+    # evaluation of P S Q^T - G, whose absolute error scales with G, not with the difference
+    assert abs(got[0] - num) <= BIAS_NUM_RTOL * num + BIAS_NUM_FLOOR * den, f"{pb.name}: numerator {got[0]} vs {num}"
     want = np.sqrt(num / den)
-    assert abs(got[2] - want) <= tol * max(want, 1.0), f"{pb.name}: bias {got[2]} vs {want}"
+    assert abs(got[2] - want) <= tol * want + 1e-6, f"{pb.name}: bias {got[2]} vs {want}"
     print(f"[ok]   bias {pb.name}: {got[2]:.6f} (oracle {want:.6f})", flush=True)
     return got
 
@@ -425,7 +468,7 @@ def test_seeded_shape_sweep(m, n, r, d, dtype, dist, seed):
         gu.check_compress(_dp(pb).compress_raw(), S_o, "sweep raw", 2e-4)
         got = _dp(pb).estimation_bias(planned=False)
         num, den = oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
-        assert abs(got[0] - num) <= 1e-3 * max(num, den) and abs(got[1] - den) <= 1e-5 * den
+        assert abs(got[0] - num) <= BIAS_NUM_RTOL * num + BIAS_NUM_FLOOR * den and abs(got[1] - den) <= 1e-5 * den
         return
     _bias_check(pb)
 
@@ -447,7 +490,7 @@ def test_decompress_with_reordered_projector_rows(m, n, r, d, dtype):
     assert pb.dtype == "f32" or mism < 0.02
     num, den = oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
     got = _dp(pb2).estimation_bias()
-    assert abs(got[0] - num) <= 1e-3 * max(num, den) and abs(got[1] - den) <= 1e-5 * den
+    assert abs(got[0] - num) <= BIAS_NUM_RTOL * num + BIAS_NUM_FLOOR * den and abs(got[1] - den) <= 1e-5 * den
 
 
 def test_projector_reorder_on_device_arrays_equals_host():
