@@ -59,12 +59,14 @@ typedef enum {
     LSP_ERR_LAUNCH    = -5,  /* the HIP runtime refused a launch or a copy (see lsp_last_hip_error) */
     LSP_ERR_INDEX     = -6,  /* lsp_validate_projector found an index outside [0, r) */
     LSP_ERR_ALIGN     = -7,  /* a base pointer is not 16-byte aligned */
-    LSP_ERR_SKEW      = -8   /* lsp_plan_build: the columns of Q are used too unevenly for a plan; use lsp_compress */
+    LSP_ERR_SKEW      = -8,  /* lsp_plan_build: the columns of Q are used too unevenly for a plan; use lsp_compress */
+    LSP_ERR_TOO_LARGE = -9   /* lsp_compress_planned_static: the problem needs more than LSP_STATIC_SCRATCH_BYTES of scratch */
 } lsp_status;
 
 #define LSP_MAX_R 2048       /* largest supported subspace size (the paper's largest setting) */
 #define LSP_MAX_D 64         /* largest supported number of entries per projector row */
 #define LSP_MAX_GROUP 16     /* most problems in one grouped call */
+#define LSP_STATIC_SCRATCH_BYTES (24u << 20)   /* scratch held inside the library image, per GPU (lsp_compress_planned_static) */
 
 /* ------------------------------------------------------------------------------------------
  * Compress:  S := P^T G Q.
@@ -140,6 +142,22 @@ int lsp_compress_planned(const void* G, const void* plan,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 size_t lsp_compress_planned_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+
+/* lsp_compress_planned for callers that cannot allocate device memory or hand in scratch: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results (bit for bit) and errors as lsp_compress_planned, without the workspace: the
+ * m x r fp32 intermediate lives in an array of LSP_STATIC_SCRATCH_BYTES (24 MiB) that is part of
+ * the library image; every GPU the library runs on holds one copy of it until the process ends.
+ * The call makes no allocation of any kind.  A problem whose intermediate does not fit (m * r * 4
+ * bytes, rounded up to 256, above the limit; 11008 x 512 fits) is refused with LSP_ERR_TOO_LARGE
+ * and nothing is enqueued.
+ * All calls on one GPU share the array: calls on one stream are ordered and safe, calls whose
+ * kernels can overlap in time (different streams, different host threads' streams) race on it and
+ * give undefined S.  The array keeps the previous call's contents; nothing in it needs clearing. */
+int lsp_compress_planned_static(const void* G, const void* plan,
+                                int64_t m, int64_t n, int32_t r, int32_t d,
+                                float* S, lsp_dtype dtype, void* stream);
+size_t lsp_static_scratch_bytes(void);   /* LSP_STATIC_SCRATCH_BYTES */
 
 /* ------------------------------------------------------------------------------------------
  * Decompress and apply:  W := rn( W - P S Q^T ), in place.

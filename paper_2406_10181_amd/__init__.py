@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     LspError, DTYPE_CODE, lib, lib_path,
     lsp_compress, lsp_compress_workspace_bytes, lsp_workspace_bytes,
     lsp_plan_bytes, lsp_plan_build, lsp_plan_build_host,
-    lsp_compress_planned, lsp_compress_planned_workspace_bytes,
+    lsp_compress_planned, lsp_compress_planned_workspace_bytes, lsp_compress_planned_static, lsp_static_scratch_bytes,
     lsp_decompress_apply, lsp_compress_planned_grouped, lsp_decompress_apply_grouped,
     lsp_estimation_bias, lsp_estimation_bias_workspace_bytes,
     lsp_reproject_state, lsp_reproject_state_workspace_bytes, lsp_projector_reorder_host, lsp_projector_reorder,

@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.lsp_plan_build_host.restype = ctypes.c_int
         L.lsp_compress_planned.argtypes = [vp, vp, i64, i64, i32, i32, vp, i32, vp, sz, vp]
         L.lsp_compress_planned.restype = ctypes.c_int
+        L.lsp_compress_planned_static.argtypes = [vp, vp, i64, i64, i32, i32, vp, i32, vp]
+        L.lsp_compress_planned_static.restype = ctypes.c_int
+        L.lsp_static_scratch_bytes.argtypes = []
+        L.lsp_static_scratch_bytes.restype = sz
         L.lsp_compress_planned_workspace_bytes.argtypes = [i64, i64, i32, i32]
         L.lsp_compress_planned_workspace_bytes.restype = sz
         L.lsp_decompress_apply.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, vp]
@@ -177,6 +181,17 @@ def lsp_compress_planned(G, plan, m, n, r, d, S, dtype: int, workspace, workspac
                                     workspace_bytes, _stream(stream))
     if check:
         _check(rc, "lsp_compress_planned")
+    return rc
+
+
+def lsp_static_scratch_bytes() -> int:
+    return int(lib().lsp_static_scratch_bytes())
+
+
+def lsp_compress_planned_static(G, plan, m, n, r, d, S, dtype: int, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_compress_planned_static(_ptr(G), _ptr(plan), m, n, r, d, _ptr(S), dtype, _stream(stream))
+    if check:
+        _check(rc, "lsp_compress_planned_static")
     return rc
 
 

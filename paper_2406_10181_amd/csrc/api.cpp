@@ -313,6 +313,8 @@ const char* lsp_strerror(int code) {
         case LSP_ERR_INDEX:     return "projector index outside [0, r)";
         case LSP_ERR_ALIGN:     return "a base pointer is not 16-byte aligned";
         case LSP_ERR_SKEW:      return "projector columns used too unevenly for a plan (use lsp_compress)";
+        case LSP_ERR_TOO_LARGE: return "problem needs more scratch than the library's static array holds (lsp_static_scratch_bytes); "
+                                       "use the entry that takes a workspace";
         default:                return "unknown lsp_status";
     }
 }
