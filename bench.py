@@ -6,11 +6,12 @@ A step is one pass of the whole hot path over the 6.7B-style layer stack (benchm
 visited layer by layer in backward order; every matrix gets one lsp_compress_planned
 (S = P^T G Q) and one lsp_decompress_apply (W -= P S Q^T).  The seven matrices of a layer are
 independent: by default they go out as one grouped call per kernel family
-(lsp_compress_planned_grouped, lsp_decompress_apply_grouped), layers alternating over --streams HIP
-streams (default priority), joined at the end of the step; --grouped 0 issues one call per matrix
-instead.  The roofline legs time each kernel family alone on one stream: the grouped calls of the
-step back to back, and (reported beside them) one call per matrix.  All inputs are resident in
-HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
+(lsp_compress_planned_grouped, lsp_decompress_apply_grouped), all on ONE stream, layer after layer (the
+named workload); --grouped 0 issues one call per matrix instead, --streams N deals the layers to N HIP
+streams (default priority, joined at the end of the step).  The reported value is the one-stream step; the
+same step on two streams is timed beside it and labelled.  The roofline legs time each kernel family alone
+on one stream: the grouped calls of the step back to back, and (reported beside them) one call per matrix.
+All inputs are resident in HBM before the timed region; all 224 G / W / S / projector buffers are distinct.
 
 Prints ONE JSON line: throughput in algorithmic GB/s (the bytes the method must move: G once for
 compress, W read and written for decompress-apply, plus the projector arrays and S) with a roofline object for the dominant kernel and the CPU oracle timed on a bounded
@@ -47,8 +48,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--grouped", type=int, default=1,
                     help="1: one grouped call per layer and kernel family; 0: one call per matrix")
-    ap.add_argument("--streams", type=int, default=2,
-                    help="HIP streams the matrices of a layer are dealt to (default priority; joined at step end)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the layers are dealt to (default priority; joined at step end); 1 = the named workload")
     ap.add_argument("--dense-ablation", action="store_true",
                     help="instead of the step: the sparse compress path at d = 2..16 against the same contraction "
                          "with dense bf16 projectors through the vendor GEMM (prints its own JSON line)")
@@ -81,6 +82,7 @@ def main():
 
     # ------------------------------------------------------------------ inputs, resident in HBM
     t0 = time.time()
+    plan_ms = {}    # shape -> wall times of lsp_plan_build (a set-up call, once per projector refresh)
     mats = []       # backward order: layer L-1 .. 0; within a layer: down, gate, up, o, v, k, q
     ws_bytes = 0
     gen = torch.Generator(device=dev)
@@ -105,12 +107,16 @@ def main():
             e["Qx_idx"], e["Qx_val"] = torch.from_numpy(qi).to(dev), torch.from_numpy(qv).to(dev)
             pbytes = L.lsp_plan_bytes(m, n, r, d)
             e["plan"] = torch.empty(pbytes, dtype=torch.uint8, device=dev)
+            torch.cuda.synchronize()
+            tp = time.perf_counter()
             L.lsp_plan_build(e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], m, n, r, d, e["plan"], pbytes, stream)
+            plan_ms.setdefault(f"{m}x{n}", []).append((time.perf_counter() - tp) * 1e3)      # the call is synchronous
             ws_bytes = max(ws_bytes, L.lsp_compress_planned_workspace_bytes(m, n, r, d))
             e["cb"], e["db"] = algorithmic_bytes(m, n, r, d, sz)
             mats.append(e)
     nstreams = max(1, args.streams)
-    lanes = [stream] + [torch.cuda.Stream(device=dev) for _ in range(nstreams - 1)]   # default priority
+    nlanes = max(2, nstreams)                                                          # a second stream for the labelled two-stream leg
+    lanes = [stream] + [torch.cuda.Stream(device=dev) for _ in range(nlanes - 1)]     # default priority
     wss = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in lanes]       # one workspace per stream
     fork = torch.cuda.Event()
     joins = [torch.cuda.Event() for _ in lanes]
@@ -133,14 +139,15 @@ def main():
     layers = [mats[k:k + 7] for k in range(0, len(mats), 7)]
     gws = [[torch.empty(L.lsp_compress_planned_workspace_bytes(e["m"], e["n"], r, d), dtype=torch.uint8, device=dev)
             for e in layers[0]] for _ in lanes]
-    citems = [L.compress_items([(e["G"], e["plan"], e["S"], gws[li % nstreams][k], gws[li % nstreams][k].numel(),
+    citems = [L.compress_items([(e["G"], e["plan"], e["S"], gws[li % nlanes][k], gws[li % nlanes][k].numel(),
                                  e["m"], e["n"]) for k, e in enumerate(ly)]) for li, ly in enumerate(layers)]
     aitems = [L.apply_items([(e["W"], e["S_upd"], e["P_idx"], e["P_val"], e["Qx_idx"], e["Qx_val"], e["m"], e["n"])
                              for e in ly]) for ly in layers]
 
-    def step_grouped():
+    def step_grouped(ns=None):
+        ns = nstreams if ns is None else ns
         for li in range(len(layers)):
-            q = lanes[li % nstreams]
+            q = lanes[li % ns]
             L.lsp_compress_planned_grouped(citems[li], 7, r, d, code, q)
             L.lsp_decompress_apply_grouped(aitems[li], 7, r, d, code, q)
 
@@ -153,50 +160,62 @@ def main():
             else:
                 L.lsp_decompress_apply_grouped(aitems[li], 7, r, d, code, q)
 
-    def forked(fn):
+    def forked(fn, ns=None):
         # side streams start after everything already queued on the main stream and are joined
         # back into it, so events recorded on the main stream bracket all the work
-        if nstreams == 1:
+        ns = nstreams if ns is None else ns
+        if ns == 1:
             return fn()
         fork.record(stream)
-        for s in lanes[1:]:
+        for s in lanes[1:ns]:
             s.wait_event(fork)
         fn()
-        for s, ev in zip(lanes[1:], joins[1:]):
+        for s, ev in zip(lanes[1:ns], joins[1:ns]):
             ev.record(s)
             stream.wait_event(ev)
 
-    def step_body():
+    def step_body(ns=None):
         # layer by layer: the layer's compress calls, then its decompress-apply calls; a matrix
         # stays on one stream, so its two calls are ordered
+        ns = nstreams if ns is None else ns
         for k in range(0, len(mats), 7):
-            compress_all(mats[k:k + 7], nstreams)
-            decompress_all(mats[k:k + 7], nstreams)
+            compress_all(mats[k:k + 7], ns)
+            decompress_all(mats[k:k + 7], ns)
 
     def step():
         forked(step_grouped if args.grouped else step_body)
 
-    def timed(fn, reps):
+    def timed(fn, reps, each=None):
+        """ms per repetition over `reps` back-to-back repetitions between two events on the working stream;
+        each: a list that receives the individual repetitions' times (events between them, no host sync)."""
         torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        for _ in range(reps):
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        marks[0].record(stream)
+        for k in range(reps):
             fn()
-        b.record(stream)
+            if each is not None or k == reps - 1:
+                marks[k + 1].record(stream)
         torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps            # ms per repetition
+        if each is not None:
+            each.extend(marks[k].elapsed_time(marks[k + 1]) for k in range(reps))
+        return marks[0].elapsed_time(marks[reps]) / reps
 
     for _ in range(args.warmup):
         step()
-    ms_step = timed(step, args.steps)
+    step_times = []
+    ms_step = timed(step, args.steps, step_times)
+    # the same step with the layers alternating over two streams (not the named workload: reported beside it)
+    step2 = lambda: forked(lambda: step_grouped(2) if args.grouped else step_body(2), 2)
+    step2()
+    ms_step2 = timed(step2, max(3, min(args.steps, 10)))
     # per-kernel passes for the roofline: one stream, launches back to back, so the time per launch
     # is the kernel's own duration (same buffers, still cold: 26 GB is swept between two visits)
     sub = max(3, min(args.steps, 10))
     ms_comp = timed(lambda: compress_all(mats), sub)
     ms_deco = timed(lambda: decompress_all(mats), sub)
 
-    ms_gcomp = timed(lambda: forked(lambda: grouped_pass("c")), sub)
-    ms_gdeco = timed(lambda: forked(lambda: grouped_pass("d")), sub)
+    ms_gcomp = timed(lambda: forked(lambda: grouped_pass("c", 2), 2), sub)
+    ms_gdeco = timed(lambda: forked(lambda: grouped_pass("d", 2), 2), sub)
     # roofline legs: the grouped launches of the step, back to back on one stream, so that the time
     # per launch is the kernels' own duration
     ms_gcomp1 = timed(lambda: grouped_pass("c", 1), sub)
@@ -226,6 +245,32 @@ def main():
                                                  sq[0]["Q_idx"], sq[0]["Q_val"], sq[1]["Q_idx"], sq[1]["Q_val"],
                                                  4096, 4096, r, d, rp_M, rp_V, rp_ws, rp_bytes, stream), 10)
 
+    # what a kernel with nothing but the stream in it reaches here: a read-only pass and y -= c over 1 GiB (fp32),
+    # same run, same stream; the buffer is four times the memory-side cache, so every pass comes from HBM
+    probe_bytes = 1 << 30
+    probe = torch.zeros(probe_bytes // 4, dtype=torch.float32, device=dev)
+    pws_bytes = L.lsp_hbm_probe_workspace_bytes(probe_bytes)
+    pws = torch.empty(pws_bytes, dtype=torch.uint8, device=dev)
+    L.lsp_hbm_probe_read(probe, probe_bytes, pws, pws_bytes, stream)
+    L.lsp_hbm_probe_rmw(probe, probe_bytes, 1.0, stream)
+    ms_pread = timed(lambda: L.lsp_hbm_probe_read(probe, probe_bytes, pws, pws_bytes, stream), 10)
+    ms_prmw = timed(lambda: L.lsp_hbm_probe_rmw(probe, probe_bytes, 1.0, stream), 10)
+    read_gbs = probe_bytes / (ms_pread * 1e-3) / 1e9
+    rmw_gbs = 2 * probe_bytes / (ms_prmw * 1e-3) / 1e9
+    del probe
+
+    # the call shape of the benchmark spec, lsp_compress on raw ELL arrays (scatter form, no plan), on the seven
+    # matrices of the first layer visited
+    raw_ws = torch.empty(max(L.lsp_compress_workspace_bytes(e["m"], e["n"], r, d) for e in layers[0]), dtype=torch.uint8, device=dev)
+
+    def raw_layer():
+        for e in layers[0]:
+            L.lsp_compress(e["G"], e["P_idx"], e["P_val"], e["Q_idx"], e["Q_val"], e["m"], e["n"], r, d, e["S"], code,
+                           raw_ws, raw_ws.numel(), stream)
+    raw_layer()
+    ms_raw = timed(raw_layer, 3)
+    raw_gbs = sum(e["cb"] for e in layers[0]) / (ms_raw * 1e-3) / 1e9
+
     cbytes = sum(e["cb"] for e in mats)
     dbytes = sum(e["db"] for e in mats)
     cflop = sum(2 * e["m"] * e["n"] * d + 2 * e["m"] * d * r for e in mats)
@@ -249,7 +294,7 @@ def main():
         "metric": "compress+decompress GB/s per layer and % of MI355X HBM peak",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg4: 6.7B-style stack, {args.layers} layers x 7 matrices, bf16 G/W, r=512, d=8, "
                                f"uniform projector columns, backward order, {nstreams} stream(s), " +
                                ("one grouped call per layer and kernel family" if args.grouped else "one call per matrix"),
@@ -257,6 +302,19 @@ def main():
                    "algorithmic_GB_per_step": round((cbytes + dbytes) / 1e9, 3)},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "per_layer_us": round(ms_step * 1e3 / args.layers, 2),
+        "ms_per_step_median": round(float(np.median(step_times)), 4), "ms_per_step_min": round(min(step_times), 4),
+        # plain streaming kernels of this library over 1 GiB in the same run: the practical ceilings of the two calls
+        "achievable_read_GBs": round(read_gbs, 1), "achievable_rmw_GBs": round(rmw_gbs, 1),
+        # time the two plain streams would need for the step's algorithmic bytes, over the step's time
+        "pct_of_achievable": round(100.0 * (cbytes / read_gbs + dbytes / rmw_gbs) / 1e9 / (ms_step * 1e-3), 2),
+        # not the named workload: the same step with the layers alternating over two HIP streams
+        "two_streams": {"ms_per_step": round(ms_step2, 4), "GB/s": round((cbytes + dbytes) / (ms_step2 * 1e-3) / 1e9, 1),
+                        "pct_of_hbm_peak": round(100.0 * (cbytes + dbytes) / (ms_step2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)},
+        # set-up side, outside the step: lsp_plan_build once per projector refresh (synchronous; host wall time), and
+        # the raw-ELL entry that needs no plan
+        "plan_build_ms_per_matrix": {k: round(float(np.median(v)), 2) for k, v in plan_ms.items()},
+        "raw_lsp_compress": {"GB/s": round(raw_gbs, 1), "pct_of_hbm_peak": round(100 * raw_gbs / HBM_PEAK_GBS, 2),
+                             "us_per_layer": round(ms_raw * 1e3, 1), "sample": "the seven matrices of one layer, one call each"},
         "compress": {"GB/s": round(comp_gbs, 1), "pct_of_hbm_peak": round(100 * comp_gbs / HBM_PEAK_GBS, 2),
                      "ms_per_pass": round(ms_comp, 4)},
         "decompress_apply": {"GB/s": round(deco_gbs, 1), "pct_of_hbm_peak": round(100 * deco_gbs / HBM_PEAK_GBS, 2),
@@ -270,7 +328,7 @@ def main():
         "roofline": {"kernel": "k_compress_gq16<bf16> + k_compress_pt8 (one lsp_compress_planned_grouped call, 7 matrices)",
                      "bound": "hbm", "achieved": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(cbytes / (ms_gcomp1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": traffic_gc,
+                     "traffic": traffic_gc, "traffic_source": "profiles/traffic_compress_cfg4.json (rocprofv3 --pmc runs, not live)",
                      # the same launches against the vector-ALU roofline (useful flop only: one FMA per stored
                      # projector entry and element, 2 m n d + 2 m d r per matrix; widening bf16 is not counted)
                      "alu": {"TFLOP/s": round(cflop / (ms_gcomp1 * 1e-3) / 1e12, 2), "peak_fp32_vector_TFLOP/s": 157.3,
@@ -282,7 +340,7 @@ def main():
         "roofline_decompress": {"kernel": "k_decompress<bf16,d=8,r<=512> (one lsp_decompress_apply_grouped call, 7 matrices)",
                                 "bound": "hbm", "achieved": round(dbytes / (ms_gdeco1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                                 "unit": "GB/s", "frac": round(dbytes / (ms_gdeco1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                                "traffic": traffic_gd,
+                                "traffic": traffic_gd, "traffic_source": "profiles/traffic_decompress_cfg4.json (rocprofv3 --pmc runs, not live)",
                                 "launches": len(layers), "avg_launch_us": round(ms_gdeco1 * 1e3 / len(layers), 2),
                                 "algorithmic_bytes_per_launch_avg": int(dbytes / len(layers)),
                                 "per_matrix_calls": {"achieved": round(deco_gbs, 1), "frac": round(deco_gbs / HBM_PEAK_GBS, 4),
@@ -307,20 +365,24 @@ def main():
 def other_configs(torch, syn, L, dev, stream):
     """One lsp_compress_planned and one lsp_decompress_apply call per matrix, on one stream, for the shapes of the
     benchmark configurations other than the timed one and for the subspace sizes the paper trained with; uniform
-    projector columns, buffers rotating so that G / W come from HBM.  Times in us per call; percentages are the
+    projector columns except for the wide sweep (bounded Zipf(1.1) columns in both projectors, as that configuration
+    is specified), buffers rotating so that G / W come from HBM.  Times in us per call; percentages are the
     call's algorithmic bytes per second over the 8 TB/s HBM peak."""
-    cases = [("cfg2", "f16", 2048, 2048, 256, 4), ("cfg3", "f16", 2048, 8192, 512, 4), ("cfg3", "f16", 8192, 2048, 512, 4)]
-    cases += [("cfg5", "bf16", 4096, 16384, r, d) for r, d in ((256, 2), (256, 16), (512, 4), (512, 8), (1024, 2), (1024, 16))]
-    cases += [("fp32", "f32", 4096, 4096, 512, 8), ("paper-sized subspace", "bf16", 4096, 4096, 2048, 8),
-              ("paper-sized subspace", "f16", 2048, 2048, 1280, 4)]
+    cases = [("cfg2", "f16", 2048, 2048, 256, 4, "uniform"), ("cfg3", "f16", 2048, 8192, 512, 4, "uniform"),
+             ("cfg3", "f16", 8192, 2048, 512, 4, "uniform")]
+    # the wide sweep as specified: both projectors' columns drawn from the bounded Zipf(1.1) distribution
+    cases += [("cfg5 zipf", "bf16", 4096, 16384, r, d, "zipf") for r in (256, 512, 1024) for d in (2, 4, 8, 16)]
+    cases += [("cfg5 shape, uniform columns", "bf16", 4096, 16384, 512, 8, "uniform")]
+    cases += [("fp32", "f32", 4096, 4096, 512, 8, "uniform"), ("paper-sized subspace", "bf16", 4096, 4096, 2048, 8, "uniform"),
+              ("paper-sized subspace", "f16", 2048, 2048, 1280, 4, "uniform")]
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
     rows = []
-    for name, dt, m, n, r, d in cases:
+    for name, dt, m, n, r, d, dist in cases:
         code, esz = syn.DTYPE_CODE[dt], (4 if dt == "f32" else 2)
         nbuf = max(3, min(12, int(1.5e9 // (m * n * esz))))
-        rng = np.random.default_rng(1)
-        P_idx, P_val = syn.ell_projector(m, r, d, rng)
-        Q_idx, Q_val = syn.ell_projector(n, r, d, rng)
+        rng = np.random.default_rng(5000 + r + d if dist == "zipf" else 1)
+        P_idx, P_val = syn.ell_projector(m, r, d, rng, dist)
+        Q_idx, Q_val = syn.ell_projector(n, r, d, rng, dist)
         qi, qv = np.empty_like(Q_idx), np.empty_like(Q_val)
         L.lsp_projector_reorder_host(Q_idx, Q_val, n, d, r, qi, qv)          # the expand side gets the reordered copy of Q
         Qx_idx, Qx_val = torch.from_numpy(qi).to(dev), torch.from_numpy(qv).to(dev)
@@ -330,8 +392,8 @@ def other_configs(torch, syn, L, dev, stream):
         Su = torch.randn(r, r, device=dev) * 1e-3
         pbytes = L.lsp_plan_bytes(m, n, r, d)
         plan = torch.empty(pbytes, dtype=torch.uint8, device=dev)
-        L.lsp_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan, pbytes, stream)
-        wb = L.lsp_compress_planned_workspace_bytes(m, n, r, d)
+        planned = L.lsp_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan, pbytes, stream, check=False) == 0
+        wb = max(L.lsp_compress_planned_workspace_bytes(m, n, r, d), L.lsp_compress_workspace_bytes(m, n, r, d))
         ws = torch.empty(wb, dtype=torch.uint8, device=dev)
         cb, db = algorithmic_bytes(m, n, r, d, esz)
 
@@ -347,9 +409,13 @@ def other_configs(torch, syn, L, dev, stream):
             b.record(stream)
             torch.cuda.synchronize()
             return a.elapsed_time(b) * 1e3 / (reps * nbuf)
-        tc = run(lambda G: L.lsp_compress_planned(G, plan, m, n, r, d, S, code, ws, wb, stream))
+        if planned:
+            tc = run(lambda G: L.lsp_compress_planned(G, plan, m, n, r, d, S, code, ws, wb, stream))
+        else:   # columns too uneven for a plan (LSP_ERR_SKEW): the raw entry is the documented way
+            tc = run(lambda G: L.lsp_compress(G, P_idx, P_val, Q_idx, Q_val, m, n, r, d, S, code, ws, wb, stream))
         td = run(lambda G: L.lsp_decompress_apply(G, Su, P_idx, P_val, Qx_idx, Qx_val, m, n, r, d, code, stream))
-        rows.append({"config": name, "dtype": dt, "m": m, "n": n, "r": r, "d": d,
+        rows.append({"config": name, "dtype": dt, "m": m, "n": n, "r": r, "d": d, "columns": dist,
+                     "compress_entry": "lsp_compress_planned" if planned else "lsp_compress (raw; plan refused: skew)",
                      "compress_us": round(tc, 1), "compress_pct_of_hbm_peak": round(cb / tc / 1e3 / HBM_PEAK_GBS * 100, 1),
                      "decompress_us": round(td, 1), "decompress_pct_of_hbm_peak": round(db / td / 1e3 / HBM_PEAK_GBS * 100, 1)})
         del Gs, plan, ws

@@ -299,6 +299,16 @@ size_t lsp_reproject_state_workspace_bytes(int32_t r);
 int lsp_validate_projector(const int32_t* idx, int64_t rows, int32_t d, int32_t r,
                            int32_t* flag, void* stream);
 
+/* Measurement aids (not part of the method): one plain streaming pass over `bytes` bytes of device
+ * memory (a multiple of 16; fp32 data for the second call), to find out what a kernel with nothing
+ * but the stream in it reaches on this GPU.  lsp_hbm_probe_read reads every byte once (compress reads G
+ * once) and leaves one float per workgroup in `workspace` (>= lsp_hbm_probe_workspace_bytes(bytes));
+ * lsp_hbm_probe_rmw does y[i] -= c on fp32 data (decompress-apply reads and writes W once).  Asynchronous
+ * on `stream`; errors as above. */
+size_t lsp_hbm_probe_workspace_bytes(size_t bytes);
+int    lsp_hbm_probe_read(const void* buf, size_t bytes, void* workspace, size_t workspace_bytes, void* stream);
+int    lsp_hbm_probe_rmw(void* buf, size_t bytes, float c, void* stream);
+
 const char* lsp_strerror(int code);      /* static string for an lsp_status */
 int         lsp_last_hip_error(void);    /* raw hipError_t of the last LSP_ERR_LAUNCH on this thread */
 int         lsp_version(void);           /* major*10000 + minor*100 + patch */

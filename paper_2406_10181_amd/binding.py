@@ -85,6 +85,12 @@ def lib() -> ctypes.CDLL:
         L.lsp_reproject_state_workspace_bytes.restype = ctypes.c_size_t
         L.lsp_estimation_bias_workspace_bytes.argtypes = [i64, i64, i32, i32]
         L.lsp_estimation_bias_workspace_bytes.restype = ctypes.c_size_t
+        L.lsp_hbm_probe_workspace_bytes.argtypes = [sz]
+        L.lsp_hbm_probe_workspace_bytes.restype = sz
+        L.lsp_hbm_probe_read.argtypes = [vp, sz, vp, sz, vp]
+        L.lsp_hbm_probe_read.restype = ctypes.c_int
+        L.lsp_hbm_probe_rmw.argtypes = [vp, sz, ctypes.c_float, vp]
+        L.lsp_hbm_probe_rmw.restype = ctypes.c_int
         L.lsp_validate_projector.argtypes = [vp, i64, i32, i32, vp, vp]
         L.lsp_validate_projector.restype = ctypes.c_int
         L.lsp_strerror.argtypes = [ctypes.c_int]
@@ -278,6 +284,24 @@ def lsp_decompress_apply_grouped(items, count, r, d, dtype: int, stream=None, ch
                                             _stream(stream))
     if check:
         _check(rc, "lsp_decompress_apply_grouped")
+    return rc
+
+
+def lsp_hbm_probe_workspace_bytes(nbytes: int) -> int:
+    return int(lib().lsp_hbm_probe_workspace_bytes(nbytes))
+
+
+def lsp_hbm_probe_read(buf, nbytes: int, workspace, workspace_bytes: int, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_hbm_probe_read(_ptr(buf), nbytes, _ptr(workspace), workspace_bytes, _stream(stream))
+    if check:
+        _check(rc, "lsp_hbm_probe_read")
+    return rc
+
+
+def lsp_hbm_probe_rmw(buf, nbytes: int, c: float, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_hbm_probe_rmw(_ptr(buf), nbytes, c, _stream(stream))
+    if check:
+        _check(rc, "lsp_hbm_probe_rmw")
     return rc
 
 

@@ -15,7 +15,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblsp_hip.so")
 OBJDIR = os.path.join(PKG, "_build")
 SOURCES = ["api.cpp", "plan.cpp", "plan_device.hip", "compress.hip", "decompress.hip", "reproject.hip", "fitgrad.hip",
-           "noalloc.hip"]
+           "noalloc.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

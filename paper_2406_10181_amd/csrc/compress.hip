@@ -14,6 +14,8 @@
 // per pair and 16 rows for bf16), not by HBM.  No matrix cores are involved because the
 // projectors are sparse (d entries per row, Def. 1) and the work is gather + fp32 FMA.
 
+#include <utility>
+
 #include "lsp_internal.h"
 
 namespace lsp {
@@ -973,9 +975,22 @@ static hipError_t launch_gq(const CompressGroup& g, int32_t r, int32_t d, int bl
     return hipGetLastError();
 }
 
+// The hardware hands the workgroups of a launch to the CUs in index order as CUs fall free, so the
+// order of the problems inside a group is the order of a greedy list schedule: the problems whose
+// workgroups run longest (widest matrices: work per row block grows with n) go first, and the
+// short ones fill in behind them.
+static void longest_first(CompressGroup& g) {
+    for (int a = 1; a < g.count; ++a)
+        for (int b = a; b > 0 && g.n[b] > g.n[b - 1]; --b) {
+            std::swap(g.G[b], g.G[b - 1]); std::swap(g.plan[b], g.plan[b - 1]); std::swap(g.T[b], g.T[b - 1]);
+            std::swap(g.S[b], g.S[b - 1]); std::swap(g.m[b], g.m[b - 1]); std::swap(g.n[b], g.n[b - 1]);
+        }
+}
+
 hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
     const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
     const bool striped = (r % 4) == 0;
+    longest_first(g);
     const int bpw = gq_blocks_per_wg(g, dtype);
     g.first_gq[0] = g.first_pt[0] = 0;
     for (int p = 0; p < g.count; ++p) {

@@ -11,6 +11,8 @@
 // makes in Alg. 1): with S = P^T G Q they rebuild P S Q^T tile by tile in registers, read G where
 // the apply step reads W, and instead of storing anything add up (P S Q^T - G)^2 and G^2; every
 // workgroup leaves its two sums in a list that k_bias_finish adds in a fixed order.
+#include <utility>
+
 #include "lsp_internal.h"
 
 namespace lsp {
@@ -353,6 +355,14 @@ bool apply_group_uniform(const ApplyGroup& g, int32_t r, int32_t d) {
 template <typename D, int RG, int PS, int NT, int CPT, int DEPTH, bool NORMS = false>
 static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st, float2* partial = nullptr) {
     using E = typename D::elem;
+    // widest matrices first: workgroups are started in index order as CUs fall free, and a workgroup's
+    // run time grows with n, so the long ones should not be the last to start
+    for (int a = 1; a < g.count; ++a)
+        for (int b = a; b > 0 && g.n[b] > g.n[b - 1]; --b) {
+            std::swap(g.W[b], g.W[b - 1]); std::swap(g.S[b], g.S[b - 1]); std::swap(g.P_idx[b], g.P_idx[b - 1]);
+            std::swap(g.P_val[b], g.P_val[b - 1]); std::swap(g.Q_idx[b], g.Q_idx[b - 1]); std::swap(g.Q_val[b], g.Q_val[b - 1]);
+            std::swap(g.m[b], g.m[b - 1]); std::swap(g.n[b], g.n[b - 1]);
+        }
     g.first[0] = 0;
     for (int p = 0; p < g.count; ++p) g.first[p + 1] = g.first[p] + (g.m[p] + RG * 4 - 1) / (RG * 4);
     const unsigned grid = (unsigned)g.first[g.count];
