@@ -1,4 +1,5 @@
-"""CPU oracle for the LSP compress / decompress-apply path and the estimation bias.  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for the LSP compress / decompress-apply path, the estimation bias, the state re-projection and
+the fitting gradient.  TEST INFRASTRUCTURE ONLY.
 
 Thin ctypes wrapper around ``lsp_oracle.c`` (plain fp64 loops written from the paper's
 two formulas: the compress step S = P^T G Q and the decompress-and-apply step
@@ -54,6 +55,8 @@ def _load():
         lib.lsp_oracle_compress_entries.argtypes = [vp, i32] + proj + [i64, i64, i32, i32, vp, vp, i64, vp]
         lib.lsp_oracle_bias.argtypes = [vp, i32] + proj + [i64, i64, i32, i32, vp]
         lib.lsp_oracle_bias_dense.argtypes = lib.lsp_oracle_bias.argtypes
+        lib.lsp_oracle_bias_grad.argtypes = [vp, i32] + proj + [i64, i64, i32, i32, vp, vp]
+        lib.lsp_oracle_bias_grad_dense.argtypes = lib.lsp_oracle_bias_grad.argtypes
         lib.lsp_oracle_reproject.argtypes = proj + proj + [i64, i64, i32, i32, vp, vp, vp, vp]
         lib.lsp_oracle_round_to_storage.argtypes = [ctypes.c_double, i32]
         lib.lsp_oracle_round_to_storage.restype = ctypes.c_double
@@ -151,6 +154,26 @@ def estimation_bias(G, dtype, P_idx, P_val, Q_idx, Q_val, r: int, *, dense: bool
     if rc != 0:
         raise RuntimeError(f"oracle estimation_bias failed rc={rc}")
     return float(out[0]), float(out[1])
+
+
+def bias_gradient(G, dtype, P_idx, P_val, Q_idx, Q_val, r: int, *, dense: bool = False):
+    """Gradient of F = 1/2 ||P P^T G Q Q^T - G||_F^2 (half the squared numerator of Def. 2's bias: the data
+    term of the fitting objective of Eq. 2 / MaybeUpdate, Alg. 1) with respect to the stored projector
+    values: returns (dF/dP_val [m][d], dF/dQ_val [n][d]) in float64.  dense=True evaluates the chain rule on
+    dense m x m and n x n matrices (tiny inputs)."""
+    lib = _load()
+    m, n = G.shape
+    d = P_idx.shape[1]
+    G = _storage(G, dtype, (m, n))
+    P_idx, P_val = _proj(P_idx, P_val, m, r, d)
+    Q_idx, Q_val = _proj(Q_idx, Q_val, n, r, d)
+    gP = np.zeros((m, d), dtype=np.float64)
+    gQ = np.zeros((n, d), dtype=np.float64)
+    fn = lib.lsp_oracle_bias_grad_dense if dense else lib.lsp_oracle_bias_grad
+    rc = fn(_p(G), DTYPE_CODE[dtype], _p(P_idx), _p(P_val), _p(Q_idx), _p(Q_val), m, n, r, d, _p(gP), _p(gQ))
+    if rc != 0:
+        raise RuntimeError(f"oracle bias_gradient failed rc={rc}")
+    return gP, gQ
 
 
 def reproject_state(P_idx, P_val, Pp_idx, Pp_val, Q_idx, Q_val, Qp_idx, Qp_val, r: int, M, V):

@@ -28,6 +28,12 @@
  *                                                and V stays non-negative); a matrix square
  *                                                would do neither.
  *
+ *   fitting gradient     dF/dP_val, dF/dQ_val for F = 1/2 ||P P^T G Q Q^T - G||_F^2
+ *                                             -- the data term of the minimisation in MaybeUpdate
+ *                                                (Alg. 1) / Eq. 2, squared and halved; the norm's own
+ *                                                gradient is this one over ||b||_F, the regulariser is
+ *                                                element-wise in the values and stays with the caller
+ *
  * P (m x r) and Q (n x r) are (d,r)-sparse projectors in the sense of Def. 1: exactly d
  * stored entries per row, kept in ELL layout as idx[row][k] (int32 column in [0,r)) and
  * val[row][k] (fp32).  The dense view is  Phat[i][a] = sum over k with idx[i][k]==a of
@@ -282,6 +288,88 @@ int lsp_oracle_reproject(const int32_t *P_idx, const float *P_val,
     return rc;
 }
 
+/* Gradient of the projector-fitting objective's data term with respect to the stored projector values
+ * (the minimisation in MaybeUpdate, Alg. 1; Eq. 2):
+ *     F(P, Q) = 1/2 || Phat Phat^T G Qhat Qhat^T - G ||_F^2        (half the squared norm of Def. 2's bias),
+ *     gP[i][k] = dF / d P_val[i][k],   gQ[j][k] = dF / d Q_val[j][k].
+ * A stored value val[i][k] enters Phat only through Phat[i][idx[i][k]] (linearly, duplicates add), so
+ * gP[i][k] = dF / d Phat[i][idx[i][k]].  Written out on dense matrices, with A = Phat Phat^T (m x m),
+ * B = Qhat Qhat^T (n x n) and R = A G B - G:
+ *     dF = <R, dA G B> + <R, A G dB>,   dA = dPhat Phat^T + Phat dPhat^T,   dB likewise,
+ * hence   dF/dPhat = (X + X^T) Phat  with X = R B G^T  (m x m),
+ *         dF/dQhat = (Y + Y^T) Qhat  with Y = G^T A R  (n x n).
+ * The paper's objective is ||b||_F + beta * regulariser; its data term is sqrt(2 F), whose gradient is
+ * this one divided by ||b||_F, and the regulariser (whose exponents differ between Alg. 1 and Eq. 2) is an
+ * element-wise function of the values: neither is part of this routine.  Tiny inputs only: O(m n (m + n)). */
+int lsp_oracle_bias_grad_dense(const void *G, int dtype,
+                               const int32_t *P_idx, const float *P_val,
+                               const int32_t *Q_idx, const float *Q_val,
+                               int64_t m, int64_t n, int r, int d, double *gP, double *gQ) {
+    double *Ph = densify(P_idx, P_val, m, r, d);
+    double *Qh = densify(Q_idx, Q_val, n, r, d);
+    double *A  = (double *)calloc((size_t)(m * m), sizeof(double));
+    double *B  = (double *)calloc((size_t)(n * n), sizeof(double));
+    double *Gd = (double *)calloc((size_t)(m * n), sizeof(double));
+    double *AG = (double *)calloc((size_t)(m * n), sizeof(double));      /* A G   */
+    double *GB = (double *)calloc((size_t)(m * n), sizeof(double));      /* G B   */
+    double *R  = (double *)calloc((size_t)(m * n), sizeof(double));      /* A G B - G */
+    double *X  = (double *)calloc((size_t)(m * m), sizeof(double));      /* R (G B)^T */
+    double *Y  = (double *)calloc((size_t)(n * n), sizeof(double));      /* (A G)^T R */
+    int rc = -1;
+    if (Ph && Qh && A && B && Gd && AG && GB && R && X && Y) {
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) Gd[i * n + j] = load_elem(G, i * n + j, dtype);
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t i2 = 0; i2 < m; ++i2)
+                for (int a = 0; a < r; ++a) A[i * m + i2] += Ph[i * r + a] * Ph[i2 * r + a];
+        for (int64_t j = 0; j < n; ++j)
+            for (int64_t j2 = 0; j2 < n; ++j2)
+                for (int b = 0; b < r; ++b) B[j * n + j2] += Qh[j * r + b] * Qh[j2 * r + b];
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) {
+                double ag = 0.0, gb = 0.0;
+                for (int64_t i2 = 0; i2 < m; ++i2) ag += A[i * m + i2] * Gd[i2 * n + j];
+                for (int64_t j2 = 0; j2 < n; ++j2) gb += Gd[i * n + j2] * B[j2 * n + j];
+                AG[i * n + j] = ag; GB[i * n + j] = gb;
+            }
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) {
+                double x = 0.0;
+                for (int64_t j2 = 0; j2 < n; ++j2) x += AG[i * n + j2] * B[j2 * n + j];
+                R[i * n + j] = x - Gd[i * n + j];
+            }
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t i2 = 0; i2 < m; ++i2) {
+                double x = 0.0;
+                for (int64_t j = 0; j < n; ++j) x += R[i * n + j] * GB[i2 * n + j];
+                X[i * m + i2] = x;
+            }
+        for (int64_t j = 0; j < n; ++j)
+            for (int64_t j2 = 0; j2 < n; ++j2) {
+                double y = 0.0;
+                for (int64_t i = 0; i < m; ++i) y += AG[i * n + j] * R[i * n + j2];
+                Y[j * n + j2] = y;
+            }
+        for (int64_t i = 0; i < m; ++i)
+            for (int k = 0; k < d; ++k) {
+                const int a = P_idx[i * d + k];
+                double g = 0.0;
+                for (int64_t i2 = 0; i2 < m; ++i2) g += (X[i * m + i2] + X[i2 * m + i]) * Ph[i2 * r + a];
+                gP[i * d + k] = g;
+            }
+        for (int64_t j = 0; j < n; ++j)
+            for (int k = 0; k < d; ++k) {
+                const int b = Q_idx[j * d + k];
+                double g = 0.0;
+                for (int64_t j2 = 0; j2 < n; ++j2) g += (Y[j * n + j2] + Y[j2 * n + j]) * Qh[j2 * r + b];
+                gQ[j * d + k] = g;
+            }
+        rc = 0;
+    }
+    free(Ph); free(Qh); free(A); free(B); free(Gd); free(AG); free(GB); free(R); free(X); free(Y);
+    return rc;
+}
+
 /* ---------------------------------------------------------------- working form */
 
 /* rows [i0, i1) of the compress sum, accumulated into S (which the caller zeroed).
@@ -387,6 +475,78 @@ int lsp_oracle_bias(const void *G, int dtype,
     out[0] = num; out[1] = den;
     free(S); free(row);
     return 0;
+}
+
+/* The same gradient by associativity, with sparse loops only (no m x m or n x n matrix):
+ *     S = P^T G Q,   R = P S Q^T - G  (row by row),
+ *     T_G = G Q,  T_R = R Q  (m x r);   Y_G = G^T P,  Y_R = R^T P  (n x r);   Z = P^T R Q = P^T T_R,
+ *     dF/dPhat = T_R S^T + T_G Z^T,      dF/dQhat = Y_R S + Y_G Z,
+ * read off at the stored positions.  (From the dense statement: X Phat = R B G^T Phat = (R Q)(Q^T G^T P) = T_R S^T and
+ * X^T Phat = G B R^T Phat = (G Q)(Q^T R^T P) = T_G Z^T; the Q side is the mirror image.)
+ * O(m n d + (m + n) d r) operations, fp64 throughout. */
+int lsp_oracle_bias_grad(const void *G, int dtype,
+                         const int32_t *P_idx, const float *P_val,
+                         const int32_t *Q_idx, const float *Q_val,
+                         int64_t m, int64_t n, int r, int d, double *gP, double *gQ) {
+    const size_t rr = (size_t)r * (size_t)r;
+    double *S  = (double *)calloc(rr, sizeof(double));
+    double *Z  = (double *)calloc(rr, sizeof(double));
+    double *TG = (double *)calloc((size_t)m * (size_t)r, sizeof(double));
+    double *TR = (double *)calloc((size_t)m * (size_t)r, sizeof(double));
+    double *YG = (double *)calloc((size_t)n * (size_t)r, sizeof(double));
+    double *YR = (double *)calloc((size_t)n * (size_t)r, sizeof(double));
+    double *row = (double *)malloc((size_t)r * sizeof(double));
+    int rc = -1;
+    if (S && Z && TG && TR && YG && YR && row) {
+        compress_rows(G, dtype, P_idx, P_val, Q_idx, Q_val, 0, m, n, r, d, row, S);
+        for (int64_t i = 0; i < m; ++i) {
+            for (int b = 0; b < r; ++b) row[b] = 0.0;                     /* row i of U = P S */
+            for (int k = 0; k < d; ++k) {
+                const double pv = (double)P_val[i * d + k];
+                const double *Srow = S + (int64_t)P_idx[i * d + k] * r;
+                for (int b = 0; b < r; ++b) row[b] += pv * Srow[b];
+            }
+            for (int64_t j = 0; j < n; ++j) {
+                double rij = 0.0;
+                for (int k = 0; k < d; ++k) rij += row[Q_idx[j * d + k]] * (double)Q_val[j * d + k];
+                const double g = load_elem(G, i * n + j, dtype);
+                rij -= g;                                                 /* R[i][j] */
+                for (int k = 0; k < d; ++k) {
+                    const double qv = (double)Q_val[j * d + k];
+                    TG[i * r + Q_idx[j * d + k]] += g * qv;
+                    TR[i * r + Q_idx[j * d + k]] += rij * qv;
+                }
+                for (int k = 0; k < d; ++k) {
+                    const double pv = (double)P_val[i * d + k];
+                    YG[j * r + P_idx[i * d + k]] += g * pv;
+                    YR[j * r + P_idx[i * d + k]] += rij * pv;
+                }
+            }
+        }
+        for (int64_t i = 0; i < m; ++i)                                   /* Z = P^T T_R */
+            for (int k = 0; k < d; ++k) {
+                const double pv = (double)P_val[i * d + k];
+                double *Zrow = Z + (int64_t)P_idx[i * d + k] * r;
+                for (int b = 0; b < r; ++b) Zrow[b] += pv * TR[i * r + b];
+            }
+        for (int64_t i = 0; i < m; ++i)
+            for (int k = 0; k < d; ++k) {
+                const int a = P_idx[i * d + k];
+                double g = 0.0;
+                for (int b = 0; b < r; ++b) g += TR[i * r + b] * S[(int64_t)a * r + b] + TG[i * r + b] * Z[(int64_t)a * r + b];
+                gP[i * d + k] = g;
+            }
+        for (int64_t j = 0; j < n; ++j)
+            for (int k = 0; k < d; ++k) {
+                const int b = Q_idx[j * d + k];
+                double g = 0.0;
+                for (int a = 0; a < r; ++a) g += YR[j * r + a] * S[(int64_t)a * r + b] + YG[j * r + a] * Z[(int64_t)a * r + b];
+                gQ[j * d + k] = g;
+            }
+        rc = 0;
+    }
+    free(S); free(Z); free(TG); free(TR); free(YG); free(YR); free(row);
+    return rc;
 }
 
 /* Selected rows only (for sampled checks at sizes where all m rows would take too long):

@@ -494,3 +494,123 @@ def test_reproject_closed_forms():
     # the roles of the old and the new projector are not interchangeable
     M3, _ = oracle.reproject_state(Pp_idx, Pp_val, P_idx, P_val, Q_idx, Q_val, Qp_idx, Qp_val, 4, M4, V4)
     assert np.abs(M3 - M1).max() > 1e-6 * np.abs(M1).max()
+
+
+# ---------------------------------------------------------------- fitting gradient (Eq. 2 / MaybeUpdate)
+def _grad(G, dtype, P_idx, P_val, Q_idx, Q_val, r, **kw):
+    return oracle.bias_gradient(G, dtype, P_idx, P_val, Q_idx, Q_val, r, **kw)
+
+
+def _half_bias_sq(G, dtype, P_idx, P_val, Q_idx, Q_val, r):
+    """F = 1/2 ||P P^T G Q Q^T - G||_F^2 from the (separately pinned) bias oracle."""
+    return 0.5 * oracle.estimation_bias(G, dtype, P_idx, P_val, Q_idx, Q_val, r, dense=True)[0]
+
+
+@pytest.mark.parametrize("m,n,r,d,dist", [
+    (5, 7, 3, 2, "uniform"),
+    (6, 4, 4, 3, "zipf"),                  # duplicate columns inside rows
+    (4, 9, 2, 1, "uniform"),
+])
+def test_gradient_against_finite_differences_of_the_bias(m, n, r, d, dist):
+    """F is a polynomial of degree four in every single projector value (the value enters P P^T twice and F is
+    quadratic in P P^T), so the five-point central difference
+        (-F(x+2h) + 8 F(x+h) - 8 F(x-h) + F(x-2h)) / (12 h)
+    is its derivative exactly, up to fp64 rounding.  Values are multiples of 2^-6 and h = 2^-3, so every
+    perturbed value is an exact float32.  F comes from the bias oracle's literal form (Def. 2), which knows
+    nothing about gradients."""
+    rng = _rng(900 + m * n + r)
+    G = syn.integer_matrix(m, n, -8, 8, "f32", rng)
+    P_idx, _ = syn.ell_projector(m, r, d, rng, dist)
+    Q_idx, _ = syn.ell_projector(n, r, d, rng, dist)
+    P_val = (rng.integers(-48, 49, size=(m, d)) / 64.0).astype(np.float32)
+    Q_val = (rng.integers(-48, 49, size=(n, d)) / 64.0).astype(np.float32)
+    h = 0.125
+    for dense in (True, False):
+        gP, gQ = _grad(G, "f32", P_idx, P_val, Q_idx, Q_val, r, dense=dense)
+        scale = max(np.abs(gP).max(), np.abs(gQ).max())
+        for (val, grad, which) in ((P_val, gP, "P"), (Q_val, gQ, "Q")):
+            for (i, k) in [(0, 0), (val.shape[0] - 1, d - 1), (val.shape[0] // 2, d // 2)]:
+                F = {}
+                for s in (-2, -1, 1, 2):
+                    v2 = val.copy()
+                    v2[i, k] = np.float32(val[i, k] + s * h)
+                    args = (P_idx, v2, Q_idx, Q_val) if which == "P" else (P_idx, P_val, Q_idx, v2)
+                    F[s] = _half_bias_sq(G, "f32", *args, r)
+                fd = (-F[2] + 8 * F[1] - 8 * F[-1] + F[-2]) / (12 * h)
+                assert abs(fd - grad[i, k]) <= 1e-9 * scale, (which, i, k, dense, fd, grad[i, k])
+
+
+@pytest.mark.parametrize("m,n,r,d,dist,dtype", [
+    (12, 9, 6, 3, "uniform", "f32"),
+    (9, 14, 5, 2, "zipf", "bf16"),
+    (40, 33, 8, 4, "uniform", "f16"),
+])
+def test_gradient_working_form_equals_dense_form_and_numpy(m, n, r, d, dist, dtype):
+    """Sparse working form (T_R S^T + T_G Z^T, Y_R S + Y_G Z) against the chain rule on dense m x m / n x n
+    matrices, and both against numpy's matrix products on densified projectors."""
+    pb = syn.make_problem("g", m, n, r, d, dtype, seed=700 + m * n, g_std=1.0, index_dist=dist)
+    gPw, gQw = _grad(pb.G, dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r)
+    gPd, gQd = _grad(pb.G, dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, r, dense=True)
+    Ph, Qh = _dense(pb.P_idx, pb.P_val, r), _dense(pb.Q_idx, pb.Q_val, r)
+    G64 = syn.storage_to_f64(pb.G, dtype)
+    A, B = Ph @ Ph.T, Qh @ Qh.T
+    R = A @ G64 @ B - G64
+    X = R @ B @ G64.T
+    Y = G64.T @ A @ R
+    refP = ((X + X.T) @ Ph)[np.arange(m)[:, None], pb.P_idx]
+    refQ = ((Y + Y.T) @ Qh)[np.arange(n)[:, None], pb.Q_idx]
+    scale = max(np.abs(refP).max(), np.abs(refQ).max())
+    for gP, gQ in ((gPw, gQw), (gPd, gQd)):
+        assert np.abs(gP - refP).max() <= 1e-11 * scale and np.abs(gQ - refQ).max() <= 1e-11 * scale
+
+
+def test_gradient_closed_forms():
+    rng = _rng(31)
+    # (1) projectors that reproduce G exactly (identity on both sides): R = 0, so the gradient vanishes
+    G = syn.integer_matrix(6, 6, -8, 8, "f32", rng)
+    eye_i = np.arange(6, dtype=np.int32).reshape(6, 1); eye_v = np.ones((6, 1), dtype=np.float32)
+    gP, gQ = _grad(G, "f32", eye_i, eye_v, eye_i, eye_v, 6)
+    assert not gP.any() and not gQ.any()
+    # (2) G inside the span of orthonormal selection projectors: R = 0 again, although r < m, n
+    m, n, r = 11, 13, 4
+    rows = rng.permutation(m)[:r]; cols = rng.permutation(n)[:r]
+    P_idx = np.zeros((m, 1), dtype=np.int32); P_val = np.zeros((m, 1), dtype=np.float32)
+    Q_idx = np.zeros((n, 1), dtype=np.int32); Q_val = np.zeros((n, 1), dtype=np.float32)
+    P_idx[rows, 0] = np.arange(r); P_val[rows, 0] = 1.0
+    Q_idx[cols, 0] = np.arange(r); Q_val[cols, 0] = 1.0
+    G = np.zeros((m, n), dtype=np.float32)
+    G[np.ix_(rows, cols)] = rng.integers(-8, 9, size=(r, r))
+    gP, gQ = _grad(G, "f32", P_idx, P_val, Q_idx, Q_val, r)
+    assert not gP.any() and not gQ.any()
+    # (3) Euler's relation along the ray t -> F(t P, Q):  <dF/dP_val, P_val> = d/dt F(tP, Q) at t = 1
+    #     = <R, 2 (R + G)> = 2 (||R||^2 + ||S||^2 - ||G||^2)   with S = P^T G Q  (since <P S Q^T, G> = ||S||^2),
+    #     all three norms from the compress and bias oracles; the same for Q.
+    pb = syn.make_problem("e", 17, 23, 6, 3, "f32", seed=32, g_std=1.0)
+    gP, gQ = _grad(pb.G, "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    num, den = oracle.estimation_bias(pb.G, "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    S = oracle.compress(pb.G, "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    want = 2.0 * (num + float((S ** 2).sum()) - den)
+    assert abs(float((gP * pb.P_val).sum()) - want) <= 1e-10 * abs(want)
+    assert abs(float((gQ * pb.Q_val).sum()) - want) <= 1e-10 * abs(want)
+    # (4) duplicated columns inside a row are one dense entry: their stored values get the same derivative
+    P_idx = pb.P_idx.copy(); P_idx[:, 1] = P_idx[:, 0]
+    gP, _ = _grad(pb.G, "f32", P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    assert np.array_equal(gP[:, 0], gP[:, 1])
+    # (5) a zero G gives a zero gradient; doubling G quadruples F and hence the gradient (exactly: power of two)
+    gP1, gQ1 = _grad(pb.G, "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    gP2, gQ2 = _grad((pb.G * np.float32(2.0)).astype(np.float32), "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    assert np.array_equal(gP2, 4.0 * gP1) and np.array_equal(gQ2, 4.0 * gQ1)
+    gP0, gQ0 = _grad(np.zeros_like(pb.G), "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    assert not gP0.any() and not gQ0.any()
+
+
+def test_gradient_of_the_transposed_problem_swaps_the_roles():
+    """F(P, Q; G) = F(Q, P; G^T): the gradient with respect to Q's values is the gradient with respect to the
+    left projector of the transposed problem.  A routine that mixed up the two sides would fail here (m != n)."""
+    pb = syn.make_problem("t", 10, 15, 5, 2, "f32", seed=33, g_std=1.0)
+    gP, gQ = _grad(pb.G, "f32", pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    Gt = np.ascontiguousarray(pb.G.T)
+    gQ_t, gP_t = _grad(Gt, "f32", pb.Q_idx, pb.Q_val, pb.P_idx, pb.P_val, pb.r)
+    scale = max(np.abs(gP).max(), np.abs(gQ).max())
+    assert np.abs(gP - gP_t).max() <= 1e-12 * scale and np.abs(gQ - gQ_t).max() <= 1e-12 * scale
+    assert np.abs(gP).max() > 0 and np.abs(gQ).max() > 0
