@@ -234,6 +234,22 @@ def main():
     ms_bias = timed(bias_all, sub)
     bbytes = sum(e["cb"] for e in mats)             # one read of G, the projector arrays and S: as for compress
 
+    # one iteration of projector fitting on the GPU (MaybeUpdate, Alg. 1 / Eq. 2): new values into the plan, then the
+    # gradient of 1/2 ||P P^T G Q Q^T - G||_F^2 with respect to the stored values, one 4096 x 4096 matrix
+    fe = [e for e in mats if e["m"] == 4096 and e["n"] == 4096][0]
+    fg_bytes = L.lsp_bias_gradient_workspace_bytes(4096, 4096, r, d)
+    fg_ws = torch.empty(fg_bytes, dtype=torch.uint8, device=dev)
+    fg_P = torch.empty(4096, d, dtype=torch.float32, device=dev)
+    fg_Q = torch.empty(4096, d, dtype=torch.float32, device=dev)
+
+    def fit_iteration():
+        L.lsp_plan_refresh_values(fe["plan"], fe["P_val"], fe["Q_val"], 4096, 4096, r, d, stream)
+        L.lsp_bias_gradient(fe["G"], fe["plan"], fe["P_idx"], fe["P_val"], fe["Q_idx"], fe["Q_val"], 4096, 4096, r, d,
+                            fg_P, fg_Q, fg_ws, fg_bytes, code, stream)
+    fit_iteration()
+    ms_fit = timed(fit_iteration, 10)
+    ms_refresh = timed(lambda: L.lsp_plan_refresh_values(fe["plan"], fe["P_val"], fe["Q_val"], 4096, 4096, r, d, stream), 10)
+
     # state re-projection after a change of projectors (MaybeUpdate, Alg. 1): one 4096 x 4096 matrix, the
     # projectors of two consecutive entries of the stack standing in for (new, previous)
     sq = [e for e in mats if e["m"] == 4096 and e["n"] == 4096][:2]
@@ -354,6 +370,12 @@ def main():
         "reproject_state": {"kernel": "k_gram x2 + k_gemm_rr x4 (one lsp_reproject_state call, 4096 x 4096, r=512, d=8)",
                             "us_per_call": round(ms_rep * 1e3, 1), "bound": "mfma", "dense_flop": 8 * r ** 3,
                             "TFLOP/s": round(8 * r ** 3 / (ms_rep * 1e-3) / 1e12, 2), "peak_fp32_TFLOP/s": 157.3},
+        # one fitting iteration on a 4096 x 4096 matrix: values-only plan refresh + gradient of the bias loss (G is
+        # streamed twice: 2 x 33.6 MB algorithmic)
+        "fitting_gradient": {"kernel": "k_plan_refresh + compress kernels + k_gram x2 + k_gemm_rr x5 + k_gather_rows + k_grad_left/right "
+                                       "(lsp_plan_refresh_values + lsp_bias_gradient, 4096 x 4096, r=512, d=8)",
+                             "us_per_iteration": round(ms_fit * 1e3, 1), "plan_refresh_us": round(ms_refresh * 1e3, 1),
+                             "GB/s_on_two_reads_of_G": round(2 * 4096 * 4096 * sz / (ms_fit * 1e-3) / 1e9, 1)},
         "setup_s": round(setup_s, 1),
     }
 
@@ -508,7 +530,10 @@ def cpu_baseline(syn, r, d):
     t = time.time()
     oracle.estimation_bias(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
     bias_s = time.time() - t
-    next_rows = {"estimation_bias_s_per_call": round(bias_s, 2),
+    t = time.time()
+    oracle.bias_gradient(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    grad_s = time.time() - t
+    next_rows = {"estimation_bias_s_per_call": round(bias_s, 2), "fitting_gradient_s_per_call": round(grad_s, 2),
                  "sample": "one 4096x4096 bf16 matrix, r=512, d=8, one host thread"}
     return {"value": round(total_bytes / total_s / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle", "next_rows": next_rows,
             "sample": "compress + decompress-apply of the 14 matrices of two layers (each: " + ", ".join(names) +

@@ -290,6 +290,48 @@ int lsp_reproject_state(const int32_t* P_idx, const float* P_val,
 size_t lsp_reproject_state_workspace_bytes(int32_t r);
 
 /* ------------------------------------------------------------------------------------------
+ * Projector fitting (the minimisation in MaybeUpdate, Alg. 1; Eq. 2): gradient of the data term
+ *     F(P, Q) = 1/2 || P P^T G Q Q^T - G ||_F^2      (half the squared numerator of Def. 2's bias)
+ * with respect to the stored projector values,
+ *     gP[i][k] = dF / dP_val[i][k],      gQ[j][k] = dF / dQ_val[j][k]
+ * (a stored value enters the dense projector linearly at its position, duplicates add; so two stored
+ * entries of a row with the same column get the same derivative).  The paper's objective is
+ * ||b||_F + beta * regulariser: its data term is sqrt(2 F), whose gradient is this one divided by ||b||_F
+ * (lsp_estimation_bias gives the norm), and the regulariser -- written with different exponents in
+ * Alg. 1 and in Eq. 2 -- is an element-wise function of the values; both are left to the caller's
+ * optimiser.  fp32 arithmetic; G is streamed twice; no m x n temporary.
+ *
+ *   G            device, m*n elements of `dtype`, read only
+ *   plan         device, the plan of these projectors WITH THEIR CURRENT VALUES (lsp_plan_build, or
+ *                lsp_plan_refresh_values after the values changed); a plan of another problem makes
+ *                every output NaN (see lsp_compress_planned)
+ *   P_*, Q_*     device, the same projectors as ELL arrays
+ *   gP, gQ       device, [m][d] and [n][d] fp32, overwritten
+ *   workspace    device scratch of at least lsp_bias_gradient_workspace_bytes(m,n,r,d) bytes, 16-byte
+ *                aligned; afterwards its first m*r floats hold T = G Q and the next r*r floats S = P^T G Q
+ * The r x r products of sparse matrices inside use fp32 atomics (results can differ in the last bits from
+ * run to run).  Errors as for lsp_estimation_bias.  Asynchronous on `stream`.
+ */
+int lsp_bias_gradient(const void* G, const void* plan,
+                      const int32_t* P_idx, const float* P_val,
+                      const int32_t* Q_idx, const float* Q_val,
+                      int64_t m, int64_t n, int32_t r, int32_t d,
+                      float* gP, float* gQ,
+                      void* workspace, size_t workspace_bytes,
+                      lsp_dtype dtype, void* stream);
+size_t lsp_bias_gradient_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+
+/* New values into an existing plan: for projectors whose positions (idx arrays) are unchanged since
+ * the plan was built and whose values changed -- every iteration of projector fitting.  One small
+ * kernel on `stream`; nothing is sorted again, the host is not involved, no synchronisation.
+ *   plan         device, a plan built for (m, n, r, d) with the same P_idx / Q_idx; updated in place
+ *                (a plan of another problem is left untouched)
+ *   P_val/Q_val  device, [m][d] / [n][d], the new values
+ */
+int lsp_plan_refresh_values(void* plan, const float* P_val, const float* Q_val,
+                            int64_t m, int64_t n, int32_t r, int32_t d, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Utilities.
  */
 

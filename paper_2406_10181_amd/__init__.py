@@ -15,5 +15,5 @@ from .binding import (  # noqa: F401
     lsp_estimation_bias, lsp_estimation_bias_workspace_bytes,
     lsp_reproject_state, lsp_reproject_state_workspace_bytes, lsp_projector_reorder_host, lsp_projector_reorder,
     lsp_compress_item, lsp_apply_item, compress_items, apply_items, lsp_validate_projector, lsp_strerror, lsp_version,
-    torch_dtype_code, lsp_hbm_probe_read, lsp_hbm_probe_rmw, lsp_hbm_probe_workspace_bytes,
+    torch_dtype_code, lsp_plan_refresh_values, lsp_bias_gradient, lsp_bias_gradient_workspace_bytes, lsp_hbm_probe_read, lsp_hbm_probe_rmw, lsp_hbm_probe_workspace_bytes,
 )

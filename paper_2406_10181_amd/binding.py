@@ -85,6 +85,12 @@ def lib() -> ctypes.CDLL:
         L.lsp_reproject_state_workspace_bytes.restype = ctypes.c_size_t
         L.lsp_estimation_bias_workspace_bytes.argtypes = [i64, i64, i32, i32]
         L.lsp_estimation_bias_workspace_bytes.restype = ctypes.c_size_t
+        L.lsp_plan_refresh_values.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp]
+        L.lsp_plan_refresh_values.restype = ctypes.c_int
+        L.lsp_bias_gradient.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp, sz, i32, vp]
+        L.lsp_bias_gradient.restype = ctypes.c_int
+        L.lsp_bias_gradient_workspace_bytes.argtypes = [i64, i64, i32, i32]
+        L.lsp_bias_gradient_workspace_bytes.restype = sz
         L.lsp_hbm_probe_workspace_bytes.argtypes = [sz]
         L.lsp_hbm_probe_workspace_bytes.restype = sz
         L.lsp_hbm_probe_read.argtypes = [vp, sz, vp, sz, vp]
@@ -284,6 +290,26 @@ def lsp_decompress_apply_grouped(items, count, r, d, dtype: int, stream=None, ch
                                             _stream(stream))
     if check:
         _check(rc, "lsp_decompress_apply_grouped")
+    return rc
+
+
+def lsp_plan_refresh_values(plan, P_val, Q_val, m, n, r, d, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_plan_refresh_values(_ptr(plan), _ptr(P_val), _ptr(Q_val), m, n, r, d, _stream(stream))
+    if check:
+        _check(rc, "lsp_plan_refresh_values")
+    return rc
+
+
+def lsp_bias_gradient_workspace_bytes(m, n, r, d) -> int:
+    return int(lib().lsp_bias_gradient_workspace_bytes(m, n, r, d))
+
+
+def lsp_bias_gradient(G, plan, P_idx, P_val, Q_idx, Q_val, m, n, r, d, gP, gQ, workspace, workspace_bytes,
+                      dtype: int, stream=None, check: bool = True) -> int:
+    rc = lib().lsp_bias_gradient(_ptr(G), _ptr(plan), _ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val), m, n, r, d,
+                                 _ptr(gP), _ptr(gQ), _ptr(workspace), workspace_bytes, dtype, _stream(stream))
+    if check:
+        _check(rc, "lsp_bias_gradient")
     return rc
 
 

@@ -55,6 +55,7 @@ size_t lsp_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype
     size_t need = t_bytes(m, r);                                                    // both compress entries
     need = std::max(need, lsp_estimation_bias_workspace_bytes(m, n, r, d));
     need = std::max(need, lsp_reproject_state_workspace_bytes(r));
+    need = std::max(need, lsp_bias_gradient_workspace_bytes(m, n, r, d));
     return need;
 }
 
@@ -287,6 +288,40 @@ int lsp_reproject_state(const int32_t* P_idx, const float* P_val, const int32_t*
     if (M == V) return LSP_ERR_SHAPE;
     hipError_t e = lsp::launch_reproject(P_idx, P_val, Pprev_idx, Pprev_val, Q_idx, Q_val, Qprev_idx, Qprev_val,
                                          m, n, r, d, M, V, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
+int lsp_plan_refresh_values(void* plan, const float* P_val, const float* Q_val,
+                            int64_t m, int64_t n, int32_t r, int32_t d, void* stream) {
+    if (!plan || !P_val || !Q_val) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    if (!aligned16(plan)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(P_val) || !aligned16(Q_val)) return LSP_ERR_ALIGN;
+    hipError_t e = lsp::launch_plan_refresh(static_cast<uint8_t*>(plan), P_val, Q_val, m, n, r, d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
+size_t lsp_bias_gradient_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
+    if (check_shape(m, n, r, d) != LSP_OK) return 0;
+    return lsp::align_up(lsp::fitgrad_workspace_floats(m, n, r) * sizeof(float), 256);
+}
+
+int lsp_bias_gradient(const void* G, const void* plan,
+                      const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                      int64_t m, int64_t n, int32_t r, int32_t d, float* gP, float* gQ,
+                      void* workspace, size_t workspace_bytes, lsp_dtype dtype, void* stream) {
+    if (!G || !plan || !P_idx || !P_val || !Q_idx || !Q_val || !gP || !gQ) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    rc = check_dtype(dtype);
+    if (rc != LSP_OK) return rc;
+    if (!workspace || workspace_bytes < lsp_bias_gradient_workspace_bytes(m, n, r, d) || !aligned16(workspace) || !aligned16(plan))
+        return LSP_ERR_WORKSPACE;
+    if (!aligned16(G) || !aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val) || !aligned16(gP) || !aligned16(gQ))
+        return LSP_ERR_ALIGN;
+    hipError_t e = lsp::launch_fitgrad(G, static_cast<const uint8_t*>(plan), P_idx, P_val, Q_idx, Q_val, m, n, r, d, gP, gQ,
+                                       static_cast<float*>(workspace), dtype, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LSP_OK : fail_launch(e);
 }
 

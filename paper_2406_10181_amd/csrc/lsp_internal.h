@@ -83,10 +83,15 @@ struct PlanHeader {            // first 256 bytes of the plan buffer
     uint64_t total_bytes;
     uint64_t off_q_vcnt;       // uint16[nslots * 512]               owners of the column if this is its first owner, else 0
     uint64_t off_q_perm;       // uint16[nchunks][512]               virtual column walked by thread t in chunk c
-    uint64_t pad2[4];
+    // where every stored value came from, so that new values can be dropped into an existing plan when only
+    // the values of the projectors change (lsp_plan_refresh_values): flat ELL positions row * d + k
+    uint64_t off_q_src;        // uint32[q_total_rows][64], laid out like q_rows; kNoSource for padding pairs
+    uint64_t off_p_src;        // uint32[m*d], parallel to p_ent
+    uint64_t pad2[2];
 };
 static_assert(sizeof(PlanHeader) == 192, "PlanHeader layout");
-constexpr uint32_t kPlanMagic = 0x4C535037u;   // "LSP7"
+constexpr uint32_t kPlanMagic = 0x4C535038u;   // "LSP8"
+constexpr uint32_t kNoSource = 0xFFFFFFFFu;    // q_src of a padding pair
 constexpr size_t   kPlanHeaderBytes = 256;
 
 struct RowItem   { int32_t a; int32_t start; int32_t len; int32_t atomic; };
@@ -187,6 +192,21 @@ hipError_t launch_reproject(const int32_t* P_idx, const float* P_val, const int3
                             int64_t m, int64_t n, int32_t r, int32_t d, float* M, float* V, float* workspace,
                             hipStream_t st);
 hipError_t launch_validate(const int32_t* idx, int64_t count, int32_t r, int32_t* flag, hipStream_t st);
+// Values-only refresh of a plan (same indices, new values).
+hipError_t launch_plan_refresh(uint8_t* plan, const float* P_val, const float* Q_val,
+                               int64_t m, int64_t n, int32_t r, int32_t d, hipStream_t st);
+// C = op(A) op(B) + beta E on r x r fp32 matrices (matrix cores); ta / tb transpose an operand; E may be null.
+hipError_t launch_gemm_rr(const float* A, const float* B, float* C, int32_t r, bool ta, bool tb,
+                          float beta, const float* E, hipStream_t st);
+// C += L^T R for two ELL matrices with the same number of rows (C must hold zeros or a running sum).
+hipError_t launch_gram(const int32_t* L_idx, const float* L_val, const int32_t* R_idx, const float* R_val,
+                       int64_t rows, int32_t d, int32_t r, float* C, hipStream_t st);
+hipError_t launch_zero(float* p, int64_t count, hipStream_t st);
+// Gradient of 1/2 ||P P^T G Q Q^T - G||_F^2 with respect to the stored projector values (fitgrad.hip).
+size_t     fitgrad_workspace_floats(int64_t m, int64_t n, int32_t r);
+hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_idx, const float* P_val,
+                          const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
+                          float* gP, float* gQ, float* workspace, lsp_dtype dtype, hipStream_t st);
 
 // ------------------------------------------------------------------------------------------
 // Storage types on the device.

@@ -32,7 +32,7 @@ size_t plan_max_items(int64_t m, int32_t r, int32_t d) {
 }
 
 namespace {
-struct Layout { size_t off_q_seg, off_q_vcol, off_q_vcnt, off_q_perm, off_q_rows, off_p_item, off_p_ent, total; };
+struct Layout { size_t off_q_seg, off_q_vcol, off_q_vcnt, off_q_perm, off_q_rows, off_p_item, off_p_ent, off_q_src, off_p_src, total; };
 Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
     Layout L;
     const size_t nchunks = (size_t)((n + kChunk - 1) / kChunk);
@@ -44,6 +44,8 @@ Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
     L.off_q_rows = o; o = align_up(o + plan_max_rows(n, r, d) * kWave * sizeof(uint2), 256);
     L.off_p_item = o; o = align_up(o + plan_max_items(m, r, d) * sizeof(RowItem), 256);
     L.off_p_ent  = o; o = align_up(o + (size_t)(m * d) * sizeof(uint2), 256);
+    L.off_q_src  = o; o = align_up(o + plan_max_rows(n, r, d) * kWave * sizeof(uint32_t), 256);
+    L.off_p_src  = o; o = align_up(o + (size_t)(m * d) * sizeof(uint32_t), 256);
     L.total = o;
     return L;
 }
@@ -62,6 +64,7 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
     // start[c][b] .. start[c][b+1] index into sorted[c], ordered by (b, j, k)
     std::vector<std::vector<int32_t>> start((size_t)nchunks, std::vector<int32_t>((size_t)r + 1, 0));
     std::vector<std::vector<uint2>> sorted((size_t)nchunks);
+    std::vector<std::vector<uint32_t>> sorted_src((size_t)nchunks);      // flat ELL position j * d + k of each sorted pair
     std::vector<int32_t> cur((size_t)r);
     for (int c = 0; c < nchunks; ++c) {
         const int64_t j0 = (int64_t)c * kChunk, j1 = std::min<int64_t>(n, j0 + kChunk);
@@ -70,10 +73,12 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
             for (int k = 0; k < d; ++k) st[(size_t)Q_idx[j * d + k] + 1]++;
         for (int b = 0; b < r; ++b) st[(size_t)b + 1] += st[(size_t)b];
         sorted[(size_t)c].assign((size_t)st[(size_t)r], uint2{0, 0});
+        sorted_src[(size_t)c].assign((size_t)st[(size_t)r], 0u);
         for (int b = 0; b < r; ++b) cur[(size_t)b] = st[(size_t)b];
         for (int64_t j = j0; j < j1; ++j)
             for (int k = 0; k < d; ++k) {
                 const int32_t b = Q_idx[j * d + k];
+                sorted_src[(size_t)c][(size_t)cur[(size_t)b]] = (uint32_t)(j * d + k);
                 sorted[(size_t)c][(size_t)cur[(size_t)b]++] =
                     uint2{chunk_col_offset((uint32_t)(j - j0)), float_bits(Q_val[j * d + k])};
             }
@@ -121,10 +126,12 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
     H->nslots = nslots; H->nvcols = V; H->list_cap = cap;
     H->off_q_seg = L.off_q_seg; H->off_q_vcol = L.off_q_vcol; H->off_q_vcnt = L.off_q_vcnt; H->off_q_perm = L.off_q_perm; H->off_q_rows = L.off_q_rows;
     H->off_p_item = L.off_p_item; H->off_p_ent = L.off_p_ent; H->total_bytes = L.total;
+    H->off_q_src = L.off_q_src; H->off_p_src = L.off_p_src;
 
     uint32_t* seg  = reinterpret_cast<uint32_t*>(out + L.off_q_seg);
     uint16_t* vcol = reinterpret_cast<uint16_t*>(out + L.off_q_vcol);
     uint2*    rows = reinterpret_cast<uint2*>(out + L.off_q_rows);
+    uint32_t* qsrc = reinterpret_cast<uint32_t*>(out + L.off_q_src);
     std::vector<int32_t> v_col((size_t)nslots * kThreadsGQ, -1), v_own((size_t)nslots * kThreadsGQ, 0);
     for (int b = 0; b < r; ++b)
         for (int o = 0; o < owners[(size_t)b]; ++o) {
@@ -196,20 +203,26 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
                     const size_t v = walked(lane);
                     int32_t lo = 0, hi = 0;
                     if (v_col[v] >= 0) share(c, v_col[v], v_own[v], lo, hi);
-                    for (int32_t e = 0; e < len; ++e)
-                        rows[row_slot(row + (size_t)e, lane)] =
-                            e < hi - lo ? sorted[(size_t)c][(size_t)(lo + e)] : pad_pair;
+                    for (int32_t e = 0; e < len; ++e) {
+                        const size_t slot = row_slot(row + (size_t)e, lane);
+                        rows[slot] = e < hi - lo ? sorted[(size_t)c][(size_t)(lo + e)] : pad_pair;
+                        qsrc[slot] = e < hi - lo ? sorted_src[(size_t)c][(size_t)(lo + e)] : kNoSource;
+                    }
                 }
                 row += (size_t)len;
             }
         for (int e = 0; e < kStreamSlack; ++e, ++row)
-            for (int lane = 0; lane < kWave; ++lane) rows[row_slot(row, lane)] = pad_pair;
+            for (int lane = 0; lane < kWave; ++lane) {
+                rows[row_slot(row, lane)] = pad_pair;
+                qsrc[row_slot(row, lane)] = kNoSource;
+            }
     }
     H->q_total_rows = (int32_t)row;
 
     // ---- P^T: for each subspace row a, the (row of G, value) pairs, cut into pieces -------------
     RowItem* items = reinterpret_cast<RowItem*>(out + L.off_p_item);
     uint2*   pent  = reinterpret_cast<uint2*>(out + L.off_p_ent);
+    uint32_t* psrc = reinterpret_cast<uint32_t*>(out + L.off_p_src);
     std::vector<int32_t> cnt((size_t)r + 1, 0);
     for (int64_t i = 0; i < m; ++i)
         for (int k = 0; k < d; ++k) cnt[(size_t)P_idx[i * d + k] + 1]++;
@@ -218,6 +231,7 @@ int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_i
     for (int64_t i = 0; i < m; ++i)
         for (int k = 0; k < d; ++k) {
             const int32_t a = P_idx[i * d + k];
+            psrc[(size_t)cur[(size_t)a]] = (uint32_t)(i * d + k);
             pent[(size_t)cur[(size_t)a]++] = uint2{(uint32_t)i, float_bits(P_val[i * d + k])};
         }
     int nitems = 0, any_split = 0;

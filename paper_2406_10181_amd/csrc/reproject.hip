@@ -32,7 +32,8 @@ __global__ __launch_bounds__(256) void k_gram(const int32_t* __restrict__ L_idx,
     }
 }
 
-// C = op(A) op(B), all r x r row-major fp32; op squares every element when the flag is set.
+// C = op(A) op(B) + beta E, all r x r row-major fp32; op squares every element (SQ*) or transposes the
+// operand (T*) while its tiles are staged.
 // A workgroup of four waves makes a 32 x 32 tile of C (many small tiles: r is a few hundred, and
 // every CU should get one).  The K range goes by in 64-wide tiles staged through LDS; inside a
 // tile the four waves take 16 consecutive k each with v_mfma_f32_32x32x2_f32 -- lane l supplies
@@ -41,9 +42,9 @@ __global__ __launch_bounds__(256) void k_gram(const int32_t* __restrict__ L_idx,
 // tiles are added through LDS at the end, in wave order.
 constexpr int kTileMN = 32, kTileK = 64;
 constexpr int kTileElems = kTileMN * kTileK / 256;                  // elements of each tile a thread stages
-template <bool SQA, bool SQB>
+template <bool SQA, bool SQB, bool TA, bool TB>
 __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, const float* __restrict__ B,
-                                                 float* __restrict__ C, int r) {
+                                                 float* __restrict__ C, int r, float beta, const float* __restrict__ E) {
     __shared__ float As[kTileMN][kTileK + 1];
     __shared__ float Bs[kTileK][kTileMN + 1];
     __shared__ float Cs[4][16][64];
@@ -52,17 +53,20 @@ __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, co
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    // the next pair of tiles is fetched into registers while the matrix cores work on the current one
+    // the next pair of tiles is fetched into registers while the matrix cores work on the current one;
+    // consecutive threads read consecutive addresses whichever way the operand lies in memory
     float an[kTileElems], bn[kTileElems];
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int e = 0; e < kTileElems; ++e) {
             const int q = tid + e * 256;
-            const int ar = q / kTileK, ak = q % kTileK;
-            const float a = (row0 + ar < r && k0 + ak < r) ? A[(int64_t)(row0 + ar) * r + k0 + ak] : 0.0f;
+            const int ar = TA ? q % kTileMN : q / kTileK, ak = TA ? q / kTileMN : q % kTileK;
+            const bool aok = row0 + ar < r && k0 + ak < r;
+            const float a = !aok ? 0.0f : TA ? A[(int64_t)(k0 + ak) * r + row0 + ar] : A[(int64_t)(row0 + ar) * r + k0 + ak];
             an[e] = SQA ? a * a : a;
-            const int bk = q / kTileMN, bc = q % kTileMN;
-            const float b = (k0 + bk < r && col0 + bc < r) ? B[(int64_t)(k0 + bk) * r + col0 + bc] : 0.0f;
+            const int bk = TB ? q % kTileK : q / kTileMN, bc = TB ? q / kTileK : q % kTileMN;
+            const bool bok = k0 + bk < r && col0 + bc < r;
+            const float b = !bok ? 0.0f : TB ? B[(int64_t)(col0 + bc) * r + k0 + bk] : B[(int64_t)(k0 + bk) * r + col0 + bc];
             bn[e] = SQB ? b * b : b;
         }
     };
@@ -71,8 +75,8 @@ __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, co
 #pragma unroll
         for (int e = 0; e < kTileElems; ++e) {
             const int q = tid + e * 256;
-            As[q / kTileK][q % kTileK] = an[e];
-            Bs[q / kTileMN][q % kTileMN] = bn[e];
+            As[TA ? q % kTileMN : q / kTileK][TA ? q / kTileMN : q % kTileK] = an[e];
+            Bs[TB ? q % kTileK : q / kTileMN][TB ? q / kTileK : q % kTileMN] = bn[e];
         }
         __syncthreads();
         if (k0 + kTileK < r) fetch(k0 + kTileK);
@@ -90,10 +94,36 @@ __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, co
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int i = row0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            const float sum = ((Cs[0][v][lane] + Cs[1][v][lane]) + Cs[2][v][lane]) + Cs[3][v][lane];
-            if (i < r && j < r) C[(int64_t)i * r + j] = sum;
+            float sum = ((Cs[0][v][lane] + Cs[1][v][lane]) + Cs[2][v][lane]) + Cs[3][v][lane];
+            if (i < r && j < r) {
+                if (E) sum = fmaf(beta, E[(int64_t)i * r + j], sum);
+                C[(int64_t)i * r + j] = sum;
+            }
         }
     }
+}
+
+static dim3 blocks_for(int64_t count) { return dim3((unsigned)((count + 255) / 256 > 2048 ? 2048 : (count + 255) / 256)); }
+
+hipError_t launch_zero(float* p, int64_t count, hipStream_t st) {
+    hipLaunchKernelGGL(k_zero, blocks_for(count), dim3(256), 0, st, p, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram(const int32_t* L_idx, const float* L_val, const int32_t* R_idx, const float* R_val,
+                       int64_t rows, int32_t d, int32_t r, float* C, hipStream_t st) {
+    hipLaunchKernelGGL(k_gram, blocks_for(rows * d * d), dim3(256), 0, st, L_idx, L_val, R_idx, R_val, rows, (int)d, (int)r, C);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_rr(const float* A, const float* B, float* C, int32_t r, bool ta, bool tb,
+                          float beta, const float* E, hipStream_t st) {
+    const dim3 grid((unsigned)((r + kTileMN - 1) / kTileMN), (unsigned)((r + kTileMN - 1) / kTileMN));
+    if (ta && tb) return hipErrorInvalidValue;                       // not needed anywhere
+    if (ta)      hipLaunchKernelGGL((k_gemm_rr<false, false, true, false>), grid, dim3(256), 0, st, A, B, C, (int)r, beta, E);
+    else if (tb) hipLaunchKernelGGL((k_gemm_rr<false, false, false, true>), grid, dim3(256), 0, st, A, B, C, (int)r, beta, E);
+    else         hipLaunchKernelGGL((k_gemm_rr<false, false, false, false>), grid, dim3(256), 0, st, A, B, C, (int)r, beta, E);
+    return hipGetLastError();
 }
 
 hipError_t launch_reproject(const int32_t* P_idx, const float* P_val, const int32_t* Pp_idx, const float* Pp_val,
@@ -104,16 +134,16 @@ hipError_t launch_reproject(const int32_t* P_idx, const float* P_val, const int3
     float* A = workspace;
     float* B = workspace + rr;
     float* X = workspace + 2 * rr;
-    auto blocks_for = [](int64_t count) { return dim3((unsigned)((count + 255) / 256 > 2048 ? 2048 : (count + 255) / 256)); };
     hipLaunchKernelGGL(k_zero, blocks_for(2 * rr), dim3(256), 0, st, A, 2 * rr);
     hipLaunchKernelGGL(k_gram, blocks_for(m * d * d), dim3(256), 0, st, P_idx, P_val, Pp_idx, Pp_val, m, (int)d, (int)r, A);
     hipLaunchKernelGGL(k_gram, blocks_for(n * d * d), dim3(256), 0, st, Qp_idx, Qp_val, Q_idx, Q_val, n, (int)d, (int)r, B);
     const dim3 grid((unsigned)((r + kTileMN - 1) / kTileMN), (unsigned)((r + kTileMN - 1) / kTileMN));
-    hipLaunchKernelGGL((k_gemm_rr<false, false>), grid, dim3(256), 0, st, A, M, X, (int)r);
-    hipLaunchKernelGGL((k_gemm_rr<false, false>), grid, dim3(256), 0, st, X, B, M, (int)r);
+    const float* none = nullptr;
+    hipLaunchKernelGGL((k_gemm_rr<false, false, false, false>), grid, dim3(256), 0, st, A, M, X, (int)r, 0.0f, none);
+    hipLaunchKernelGGL((k_gemm_rr<false, false, false, false>), grid, dim3(256), 0, st, X, B, M, (int)r, 0.0f, none);
     if (V) {
-        hipLaunchKernelGGL((k_gemm_rr<true, false>), grid, dim3(256), 0, st, A, V, X, (int)r);
-        hipLaunchKernelGGL((k_gemm_rr<false, true>), grid, dim3(256), 0, st, X, B, V, (int)r);
+        hipLaunchKernelGGL((k_gemm_rr<true, false, false, false>), grid, dim3(256), 0, st, A, V, X, (int)r, 0.0f, none);
+        hipLaunchKernelGGL((k_gemm_rr<false, true, false, false>), grid, dim3(256), 0, st, X, B, V, (int)r, 0.0f, none);
     }
     return hipGetLastError();
 }

@@ -1,0 +1,131 @@
+"""GPU parity of the projector-fitting side (MaybeUpdate of Alg. 1 / Eq. 2): the gradient of
+F = 1/2 ||P P^T G Q Q^T - G||_F^2 with respect to the stored projector values, and the values-only refresh of a
+plan, through the C ABI against the CPU oracle."""
+import numpy as np
+import pytest
+
+import lsp_synth as syn
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+# fp32 evaluation of sums of up to ~1e5 products, with cancellation between the two terms of the gradient:
+# the error is stated against the largest gradient entry of the same projector
+GRAD_TOL = 2e-4
+
+
+def _gradient(dp):
+    import torch
+    import paper_2406_10181_amd as L
+    pb = dp.pb
+    if dp.plan is None:
+        dp.build_plan()
+    nb = L.lsp_bias_gradient_workspace_bytes(pb.m, pb.n, pb.r, pb.d)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    gP = torch.full((pb.m, pb.d), float("nan"), dtype=torch.float32, device="cuda")
+    gQ = torch.full((pb.n, pb.d), float("nan"), dtype=torch.float32, device="cuda")
+    L.lsp_bias_gradient(dp.G, dp.plan, dp.P_idx, dp.P_val, dp.Q_idx, dp.Q_val, pb.m, pb.n, pb.r, pb.d, gP, gQ, ws, nb,
+                        dp.code, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    return gP.cpu().numpy(), gQ.cpu().numpy(), ws
+
+
+def _check_gradient(pb, tol=GRAD_TOL):
+    from gpu_util import DeviceProblem
+    print(f"[case] gradient {pb.name} m={pb.m} n={pb.n} r={pb.r} d={pb.d} {pb.dtype}", flush=True)
+    gP_o, gQ_o = oracle.bias_gradient(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    gP, gQ, _ = _gradient(DeviceProblem(pb))
+    assert np.isfinite(gP).all() and np.isfinite(gQ).all()
+    eP = np.abs(gP - gP_o).max() / np.abs(gP_o).max()
+    eQ = np.abs(gQ - gQ_o).max() / np.abs(gQ_o).max()
+    print(f"[ok]   gradient {pb.name}: rel err dP {eP:.2e}, dQ {eQ:.2e}", flush=True)
+    assert eP <= tol and eQ <= tol, (eP, eQ)
+
+
+@pytest.mark.parametrize("m,n,r,d,dtype,dist", [
+    (256, 256, 16, 2, "f32", "distinct"),        # config 1
+    (203, 3000, 512, 8, "bf16", "uniform"),      # ragged row block, several chunks
+    (130, 1030, 64, 3, "f16", "uniform"),        # n % 8 != 0: element-wise loads everywhere
+    (64, 2048, 96, 4, "bf16", "zipf"),           # duplicates inside rows, shared columns
+    (2000, 64, 4, 2, "f32", "uniform"),          # rows of P^T cut into pieces: the atomic path of the row gather
+    (96, 1024, 1100, 2, "bf16", "uniform"),      # more subspace columns than lanes
+])
+def test_bias_gradient_against_oracle(m, n, r, d, dtype, dist):
+    _check_gradient(syn.make_problem("grad", m, n, r, d, dtype, seed=5100 + m + n, g_std=1.0, index_dist=dist))
+
+
+def test_bias_gradient_config4_shape():
+    # one 4096 x 4096 bf16 matrix of the 6.7B-style stack, r = 512, d = 8, with gradients of training scale
+    _check_gradient(syn.config4_matrix(31, 3))
+
+
+def test_bias_gradient_is_zero_where_the_projectors_reproduce_g():
+    """G inside the span of orthonormal selection projectors: P P^T G Q Q^T = G, so the data term is at its
+    minimum and the gradient is exactly zero (integers: every product and sum is exact in fp32)."""
+    from gpu_util import DeviceProblem
+    rng = np.random.default_rng(52)
+    m, n, r = 300, 1024, 32
+    rows = rng.permutation(m)[:r]; cols = rng.permutation(n)[:r]
+    P_idx = np.zeros((m, 1), dtype=np.int32); P_val = np.zeros((m, 1), dtype=np.float32)
+    Q_idx = np.zeros((n, 1), dtype=np.int32); Q_val = np.zeros((n, 1), dtype=np.float32)
+    P_idx[rows, 0] = np.arange(r); P_val[rows, 0] = 1.0
+    Q_idx[cols, 0] = rng.permutation(r); Q_val[cols, 0] = 1.0
+    G = np.zeros((m, n), dtype=np.float32)
+    G[np.ix_(rows, cols)] = rng.integers(-8, 9, size=(r, r))
+    pb = syn.Problem("fix", m, n, r, 1, "bf16", syn.to_storage(G, "bf16"), syn.to_storage(G, "bf16"), P_idx, P_val, Q_idx, Q_val,
+                     np.zeros((r, r), np.float32))
+    gP, gQ, _ = _gradient(DeviceProblem(pb))
+    assert not gP.any() and not gQ.any()
+
+
+def test_plan_refresh_values_equals_a_rebuilt_plan_and_feeds_the_gradient():
+    """New values, same positions: the refreshed plan is byte for byte the plan built from scratch, and the
+    gradient computed through it is the gradient at the new values."""
+    import torch
+    import paper_2406_10181_amd as L
+    from gpu_util import DeviceProblem, to_device
+    pb = syn.make_problem("refresh", 260, 4104, 256, 4, "bf16", seed=5300, g_std=1.0, index_dist="zipf")
+    dp = DeviceProblem(pb)
+    dp.build_plan()
+    rng = np.random.default_rng(5301)
+    P_val2 = (pb.P_val + 0.1 * rng.standard_normal(pb.P_val.shape)).astype(np.float32)
+    Q_val2 = (pb.Q_val + 0.1 * rng.standard_normal(pb.Q_val.shape)).astype(np.float32)
+    nb = dp.plan_bytes
+    want = np.zeros(nb, dtype=np.uint8)
+    L.lsp_plan_build_host(pb.P_idx, P_val2, pb.Q_idx, Q_val2, pb.m, pb.n, pb.r, pb.d, want, nb)
+    dp.P_val, dp.Q_val = to_device(P_val2), to_device(Q_val2)
+    L.lsp_plan_refresh_values(dp.plan, dp.P_val, dp.Q_val, pb.m, pb.n, pb.r, pb.d, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.plan.cpu().numpy(), want)
+    # a plan of another problem is left alone
+    other = torch.from_numpy(want.copy()).cuda()
+    L.lsp_plan_refresh_values(other, dp.P_val, dp.Q_val, pb.m, pb.n, pb.r, pb.d + 1, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(other.cpu().numpy(), want)
+    gP_o, gQ_o = oracle.bias_gradient(pb.G, pb.dtype, pb.P_idx, P_val2, pb.Q_idx, Q_val2, pb.r)
+    gP, gQ, _ = _gradient(dp)
+    assert np.abs(gP - gP_o).max() <= GRAD_TOL * np.abs(gP_o).max() and np.abs(gQ - gQ_o).max() <= GRAD_TOL * np.abs(gQ_o).max()
+
+
+def test_bias_gradient_with_a_foreign_plan_gives_nan_and_leaves_by_products_in_the_workspace():
+    import torch
+    import paper_2406_10181_amd as L
+    import gpu_util as gu
+    from gpu_util import DeviceProblem
+    pb = syn.make_problem("gws", 200, 2304, 128, 4, "bf16", seed=5400, g_std=1.0)
+    dp = DeviceProblem(pb)
+    gP, gQ, ws = _gradient(dp)
+    # by-products promised by the header: T = G Q and S = P^T G Q at the head of the workspace
+    S_o = oracle.compress(pb.G, pb.dtype, pb.P_idx, pb.P_val, pb.Q_idx, pb.Q_val, pb.r)
+    wsf = ws.view(torch.float32)
+    t_floats = -(-pb.m * pb.r // 64) * 64
+    gu.check_compress(wsf[t_floats:t_floats + pb.r * pb.r].reshape(pb.r, pb.r).cpu().numpy(), S_o, "S in the workspace")
+    # a plan built for another d: every output is NaN, no kernel follows the plan
+    rng = np.random.default_rng(1)
+    pi, pv = syn.ell_projector(pb.m, pb.r, 8, rng); qi, qv = syn.ell_projector(pb.n, pb.r, 8, rng)
+    nb8 = L.lsp_plan_bytes(pb.m, pb.n, pb.r, 8)
+    host = np.zeros(nb8, dtype=np.uint8)
+    L.lsp_plan_build_host(pi, pv, qi, qv, pb.m, pb.n, pb.r, 8, host, nb8)
+    dp.plan = torch.from_numpy(host).cuda()
+    gP, gQ, _ = _gradient(dp)
+    assert np.isnan(gP).all() and np.isnan(gQ).all()

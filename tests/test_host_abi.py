@@ -69,6 +69,20 @@ def test_argument_errors_without_gpu():
     assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed - 1, 0) == -4
     assert bias(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, None, bneed, 0) == -4
     assert bias(fake, fake + 4, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, bneed, 0) == -7
+    # the fitting gradient and the values-only refresh of a plan
+    grad = lambda *a, **k: L.lsp_bias_gradient(*a, check=False, **k)
+    gneed = L.lsp_bias_gradient_workspace_bytes(**ok)
+    assert gneed >= (64 * 16 + 8 * 16 * 16 + 16 * 64) * 4 and L.lsp_bias_gradient_workspace_bytes(64, 64, 4, 8) == 0
+    assert L.lsp_workspace_bytes(64, 64, 16, 2, 2) >= gneed and L.lsp_workspace_bytes(64, 64, 16, 2, 9) == 0
+    assert grad(None, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, fake, gneed, 0) == -1
+    assert grad(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, None, fake, gneed, 0) == -1
+    assert grad(fake, fake, fake, fake, fake, fake, 64, 64, 16, 0, fake, fake, fake, gneed, 0) == -2
+    assert grad(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, fake, gneed, 3) == -3
+    assert grad(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake, fake, gneed - 1, 0) == -4
+    assert grad(fake, fake, fake, fake, fake, fake, 64, 64, 16, 2, fake, fake + 4, fake, gneed, 0) == -7
+    assert L.lsp_plan_refresh_values(None, fake, fake, 64, 64, 16, 2, None, check=False) == -1
+    assert L.lsp_plan_refresh_values(fake, fake, fake, 64, 0, 16, 2, None, check=False) == -2
+    assert L.lsp_plan_refresh_values(fake, fake + 4, fake, 64, 64, 16, 2, None, check=False) == -7
     # and so does the state re-projection
     rep = lambda *a, **k: L.lsp_reproject_state(*a, check=False, **k)
     rneed = L.lsp_reproject_state_workspace_bytes(16)
@@ -131,7 +145,7 @@ def _replay_plan(buf, pb):
     slot, each segment's length from the table; lane l of wave w in slot s walks the list of virtual
     column s*512 + w*64 + l, or, with one slot, of the virtual column the per-chunk table names."""
     hdr32 = buf[:48].view(np.int32)
-    assert hdr32[0] == 0x4C535037
+    assert hdr32[0] == 0x4C535038
     m, n, r, d, nchunks, nslots, nvcols, total_rows, nitems, any_split, cap = [int(x) for x in hdr32[1:12]]
     assert (m, n, r, d) == (pb.m, pb.n, pb.r, pb.d) and nchunks == -(-n // CHUNK)
     assert 1 <= nslots <= 4 and nvcols <= nslots * 512
@@ -149,6 +163,13 @@ def _replay_plan(buf, pb):
     permuted = int(buf[84:88].view(np.int32)[0])
     o_perm = int(buf[152:160].view(np.uint64)[0])
     perm = buf[o_perm:o_perm + nchunks * THREADS * 2].view(np.uint16).reshape(nchunks, 8, 64)
+    # where every stored value came from (flat ELL position), laid out like the rows / the P entries
+    o_qsrc, o_psrc = int(buf[160:168].view(np.uint64)[0]), int(buf[168:176].view(np.uint64)[0])
+    assert o_qsrc % 16 == 0 and o_psrc % 16 == 0 and o_pent + m * d * 8 <= o_qsrc and o_qsrc + total_rows * 64 * 4 <= o_psrc
+    qsrc = buf[o_qsrc:o_qsrc + total_rows * 64 * 4].view(np.uint32).reshape(total_rows // 2, 64, 2)
+    qsrc = np.ascontiguousarray(qsrc.transpose(0, 2, 1)).reshape(total_rows, 64)
+    psrc = buf[o_psrc:o_psrc + m * d * 4].view(np.uint32)
+    q_seen = np.zeros(n * d, dtype=bool)
     assert permuted == int(nslots == 1) and o_perm % 16 == 0
     if permuted:
         for c in range(nchunks):
@@ -196,14 +217,18 @@ def _replay_plan(buf, pb):
                         off = int(ent[e, lane, 0])
                         v = float(ent[e, lane, 1:2].view(np.float32)[0])
                         assert off % 16 == 0 and off <= PAD_OFFSET, "LDS offset inside one plane"
+                        src = int(qsrc[p + e, lane])
                         if off == PAD_OFFSET:
-                            assert v == 0.0
+                            assert v == 0.0 and src == 0xFFFFFFFF
                             continue
                         if nslots == 1:
                             longest[c, w] = max(longest[c, w], e + 1)
                         assert col != 0xFFFF
                         j = c * CHUNK + _decode_col(off)
                         assert j < n
+                        assert src // d == j and not q_seen[src], "the pair's source is an entry of row j of Q, used once"
+                        q_seen[src] = True
+                        assert int(pb.Q_idx.reshape(-1)[src]) == (col & 0x7FFF) and np.float32(v) == pb.Q_val.reshape(-1)[src]
                         T[:, col & 0x7FFF] += v * G[:, j]
                         nent += 1
                 p += ln
@@ -211,6 +236,7 @@ def _replay_plan(buf, pb):
         assert p + SLACK <= total_rows and (w == 7 or p + SLACK <= stream_row[w + 1])
         tail = rows[p:p + SLACK]
         assert np.all(tail[:, :, 0] == PAD_OFFSET) and np.all(tail[:, :, 1] == 0)
+        assert np.all(qsrc[p:p + SLACK] == 0xFFFFFFFF)
     assert nent == n * d
     if permuted:
         # the lists of a chunk are dealt by length: waves 0,1,2,3,7,6,5,4 get ever shorter ones, and
@@ -232,10 +258,12 @@ def _replay_plan(buf, pb):
             i = int(pent[e, 0])
             v = float(pent[e, 1:2].view(np.float32)[0])
             assert i < m
+            assert int(psrc[e]) // d == i and int(pb.P_idx.reshape(-1)[psrc[e]]) == a and np.float32(v) == pb.P_val.reshape(-1)[psrc[e]]
             S[a, :] += v * T[i, :]
         if atomic:
             assert any_split == 1
     assert seen.all() and rows_seen == set(range(r))
+    assert q_seen.all() and sorted(psrc.tolist()) == list(range(m * d)), "every stored value has exactly one place in the plan"
     return T, S
 
 
