@@ -82,12 +82,13 @@ typedef enum {
  *              16-byte aligned; contents are clobbered; may be reused by later calls on
  *              the same stream
  *
- * This entry takes raw ELL projectors and needs no preparation: it evaluates the same sums
- * in scatter form (LDS and global fp32 atomics), which is several times slower than the
- * planned entry and not bit-reproducible from run to run (atomic order).  When the
- * projectors stay fixed over many steps -- the paper refreshes them only every CheckFreq
+ * This entry takes raw ELL projectors and needs no preparation: it builds the plan on the
+ * device into the workspace and runs the planned kernels on it, all asynchronously; only
+ * projectors too skewed for a plan are served by a scatter form (LDS and global fp32 atomics, far
+ * slower, not bit-reproducible), chosen on the device.  An index outside [0, r) makes S NaN.
+ * When the projectors stay fixed over many steps -- the paper refreshes them only every CheckFreq
  * steps in MaybeUpdate, Alg. 1 -- build a plan once with lsp_plan_build and call
- * lsp_compress_planned, which is the entry meant for the per-step loop.
+ * lsp_compress_planned, which saves the build in every step.
  */
 int lsp_compress(const void* G,
                  const int32_t* P_idx, const float* P_val,
@@ -109,11 +110,19 @@ size_t lsp_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d, lsp_dtype
  * problem, valid until the projector arrays change (every CheckFreq steps at most, Alg. 1).
  * It lives entirely in a caller-owned device buffer of lsp_plan_bytes() bytes; there is no
  * host handle.  Building a plan only sorts and packs the projector entries (no arithmetic on
- * G, W or S).  lsp_plan_build is a set-up call, NOT part of the per-step path: it waits for
- * `stream`, copies the four ELL arrays to the host, sorts there, uploads the plan and waits
- * again (it allocates host memory; it returns LSP_ERR_INDEX if an index is outside [0, r)).
- * lsp_plan_build_host does the same packing with every pointer in HOST memory and makes no HIP
- * call; the resulting bytes can be copied to the device by the caller.
+ * G, W or S) and happens on the device, where the projectors live: a radix sort of one key per
+ * stored entry and a handful of small kernels (tens of microseconds; nothing is copied to the host).
+ *
+ * lsp_plan_build_async only enqueues that work on `stream`; it needs device scratch of
+ * lsp_plan_build_workspace_bytes() and reports what only the data can show -- an index outside
+ * [0, r) (LSP_ERR_INDEX) or columns too skewed for a plan (LSP_ERR_SKEW) -- in `status` (device,
+ * one int32, may be NULL), written when the build has run; a failed build also leaves the buffer
+ * marked as "no plan", so that compress calls with it fill S with NaN.
+ * lsp_plan_build is the synchronous form: it allocates and frees the scratch itself (a set-up call,
+ * NOT part of the per-step path), waits for `stream` and returns the build's status.
+ * lsp_plan_build_host makes the same bytes with every pointer in HOST memory and no HIP call; the
+ * result can be copied to the device by the caller.  lsp_plan_refresh_values (below) drops new
+ * values into a plan whose positions are unchanged.
  */
 size_t lsp_plan_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
 
@@ -121,6 +130,14 @@ int lsp_plan_build(const int32_t* P_idx, const float* P_val,
                    const int32_t* Q_idx, const float* Q_val,
                    int64_t m, int64_t n, int32_t r, int32_t d,
                    void* plan, size_t plan_bytes, void* stream);
+
+size_t lsp_plan_build_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+int lsp_plan_build_async(const int32_t* P_idx, const float* P_val,
+                         const int32_t* Q_idx, const float* Q_val,
+                         int64_t m, int64_t n, int32_t r, int32_t d,
+                         void* plan, size_t plan_bytes,
+                         void* workspace, size_t workspace_bytes,
+                         int32_t* status, void* stream);
 
 int lsp_plan_build_host(const int32_t* P_idx, const float* P_val,
                         const int32_t* Q_idx, const float* Q_val,

@@ -9,7 +9,7 @@ no CPU fallback, and importing the binding fails loudly if the library has not b
 from .binding import (  # noqa: F401
     LspError, DTYPE_CODE, lib, lib_path,
     lsp_compress, lsp_compress_workspace_bytes, lsp_workspace_bytes,
-    lsp_plan_bytes, lsp_plan_build, lsp_plan_build_host,
+    lsp_plan_bytes, lsp_plan_build, lsp_plan_build_host, lsp_plan_build_async, lsp_plan_build_workspace_bytes,
     lsp_compress_planned, lsp_compress_planned_workspace_bytes, lsp_compress_planned_static, lsp_static_scratch_bytes,
     lsp_decompress_apply, lsp_compress_planned_grouped, lsp_decompress_apply_grouped,
     lsp_estimation_bias, lsp_estimation_bias_workspace_bytes,

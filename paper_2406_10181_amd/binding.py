@@ -57,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.lsp_plan_bytes.restype = sz
         L.lsp_plan_build.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.lsp_plan_build.restype = ctypes.c_int
+        L.lsp_plan_build_async.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp, sz, vp, vp]
+        L.lsp_plan_build_async.restype = ctypes.c_int
+        L.lsp_plan_build_workspace_bytes.argtypes = [i64, i64, i32, i32]
+        L.lsp_plan_build_workspace_bytes.restype = sz
         L.lsp_plan_build_host.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, sz]
         L.lsp_plan_build_host.restype = ctypes.c_int
         L.lsp_compress_planned.argtypes = [vp, vp, i64, i64, i32, i32, vp, i32, vp, sz, vp]
@@ -176,6 +180,19 @@ def lsp_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan, plan_bytes, str
                               plan_bytes, _stream(stream))
     if check:
         _check(rc, "lsp_plan_build")
+    return rc
+
+
+def lsp_plan_build_workspace_bytes(m, n, r, d) -> int:
+    return int(lib().lsp_plan_build_workspace_bytes(m, n, r, d))
+
+
+def lsp_plan_build_async(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan, plan_bytes, workspace, workspace_bytes, status=None,
+                         stream=None, check: bool = True) -> int:
+    rc = lib().lsp_plan_build_async(_ptr(P_idx), _ptr(P_val), _ptr(Q_idx), _ptr(Q_val), m, n, r, d, _ptr(plan), plan_bytes,
+                                    _ptr(workspace), workspace_bytes, _ptr(status), _stream(stream))
+    if check:
+        _check(rc, "lsp_plan_build_async")
     return rc
 
 

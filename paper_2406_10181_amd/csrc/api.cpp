@@ -40,9 +40,15 @@ size_t t_bytes(int64_t m, int32_t r) { return lsp::align_up((size_t)m * (size_t)
 
 extern "C" {
 
+size_t lsp_plan_build_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
+    if (check_shape(m, n, r, d) != LSP_OK) return 0;
+    return lsp::plan_build_workspace_bytes(m, n, r, d);
+}
+
+// raw entry: T | plan | scratch of the plan build | status word
 size_t lsp_compress_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
     if (check_shape(m, n, r, d) != LSP_OK) return 0;
-    return t_bytes(m, r);
+    return t_bytes(m, r) + lsp::align_up(lsp::plan_bytes(m, n, r, d), 256) + lsp::plan_build_workspace_bytes(m, n, r, d) + 256;
 }
 
 size_t lsp_compress_planned_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
@@ -76,8 +82,35 @@ int lsp_compress(const void* G, const int32_t* P_idx, const float* P_val, const 
     if (!aligned16(workspace)) return LSP_ERR_WORKSPACE;
     if (!aligned16(G) || !aligned16(S) || !aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val))
         return LSP_ERR_ALIGN;
-    hipError_t e = lsp::launch_compress_raw(G, P_idx, P_val, Q_idx, Q_val, m, n, r, d, S, dtype,
-                                            static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+    // A plan is built on the device into the workspace, the planned kernels run on it, and the scatter-form
+    // kernels follow, which do their work only if the build found the columns too skewed for a plan.
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    float* T = reinterpret_cast<float*>(ws);
+    uint8_t* plan = ws + t_bytes(m, r);
+    uint8_t* scratch = plan + lsp::align_up(lsp::plan_bytes(m, n, r, d), 256);
+    int32_t* status = reinterpret_cast<int32_t*>(scratch + lsp::plan_build_workspace_bytes(m, n, r, d));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = lsp::launch_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, plan, scratch, status, st);
+    if (e != hipSuccess) return fail_launch(e);
+    lsp::CompressGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.count = 1; g.G[0] = G; g.plan[0] = plan; g.T[0] = T; g.S[0] = S; g.m[0] = (int32_t)m; g.n[0] = (int32_t)n;
+    if ((e = lsp::launch_compress_planned(g, r, d, dtype, st)) != hipSuccess) return fail_launch(e);
+    e = lsp::launch_compress_raw(G, P_idx, P_val, Q_idx, Q_val, m, n, r, d, S, dtype, T, status, st);
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
+int lsp_plan_build_async(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                         int64_t m, int64_t n, int32_t r, int32_t d, void* plan, size_t plan_bytes,
+                         void* workspace, size_t workspace_bytes, int32_t* status, void* stream) {
+    if (!P_idx || !P_val || !Q_idx || !Q_val) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, d);
+    if (rc != LSP_OK) return rc;
+    if (!plan || plan_bytes < lsp::plan_bytes(m, n, r, d) || !aligned16(plan)) return LSP_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < lsp::plan_build_workspace_bytes(m, n, r, d) || !aligned16(workspace)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val)) return LSP_ERR_ALIGN;
+    hipError_t e = lsp::launch_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, static_cast<uint8_t*>(plan),
+                                          static_cast<uint8_t*>(workspace), status, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LSP_OK : fail_launch(e);
 }
 
@@ -88,24 +121,22 @@ int lsp_plan_build(const int32_t* P_idx, const float* P_val, const int32_t* Q_id
     if (rc != LSP_OK) return rc;
     const size_t need = lsp::plan_bytes(m, n, r, d);
     if (!plan || plan_bytes < need || !aligned16(plan)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(P_idx) || !aligned16(P_val) || !aligned16(Q_idx) || !aligned16(Q_val)) return LSP_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // Order after whatever produced the projector arrays on this stream, then bring them to the host.
-    hipError_t e = hipStreamSynchronize(st);
+    // a set-up call: scratch for the device-side build is allocated here and released before returning
+    const size_t ws_bytes = lsp::plan_build_workspace_bytes(m, n, r, d) + 256;
+    uint8_t* ws = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ws), ws_bytes);
     if (e != hipSuccess) return fail_launch(e);
-    std::vector<int32_t> pi((size_t)m * d), qi((size_t)n * d);
-    std::vector<float> pv((size_t)m * d), qv((size_t)n * d);
-    if ((e = hipMemcpy(pi.data(), P_idx, pi.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
-    if ((e = hipMemcpy(pv.data(), P_val, pv.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
-    if ((e = hipMemcpy(qi.data(), Q_idx, qi.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
-    if ((e = hipMemcpy(qv.data(), Q_val, qv.size() * 4, hipMemcpyDeviceToHost)) != hipSuccess) return fail_launch(e);
-    for (int32_t v : pi) if (v < 0 || v >= r) return LSP_ERR_INDEX;
-    for (int32_t v : qi) if (v < 0 || v >= r) return LSP_ERR_INDEX;
-    std::vector<uint8_t> host(need);
-    rc = lsp::build_plan_host(pi.data(), pv.data(), qi.data(), qv.data(), m, n, r, d, host.data());
-    if (rc != LSP_OK) return rc;
-    if ((e = hipMemcpyAsync(plan, host.data(), need, hipMemcpyHostToDevice, st)) != hipSuccess) return fail_launch(e);
-    if ((e = hipStreamSynchronize(st)) != hipSuccess) return fail_launch(e);
-    return LSP_OK;
+    int32_t* status = reinterpret_cast<int32_t*>(ws + ws_bytes - 256);
+    int32_t host_status = LSP_ERR_LAUNCH;
+    e = lsp::launch_plan_build(P_idx, P_val, Q_idx, Q_val, m, n, r, d, static_cast<uint8_t*>(plan), ws, status, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(&host_status, status, sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    const hipError_t e2 = hipStreamSynchronize(st);                 // also before the scratch is released
+    (void)hipFree(ws);
+    if (e != hipSuccess) return fail_launch(e);
+    if (e2 != hipSuccess) return fail_launch(e2);
+    return host_status;
 }
 
 int lsp_plan_build_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,

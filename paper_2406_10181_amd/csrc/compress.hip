@@ -899,8 +899,9 @@ constexpr int kRawRows = 16;
 template <typename D>
 __global__ __launch_bounds__(256) void k_raw_gq(const typename D::elem* __restrict__ G,
                                                const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
-                                               float* __restrict__ T, int m, int n, int r, int d) {
+                                               float* __restrict__ T, int m, int n, int r, int d, const int32_t* __restrict__ gate) {
     extern __shared__ __align__(16) uint8_t smem[];
+    if (gate && *gate != LSP_ERR_SKEW) return;                        // the planned kernels have done the work
     float* Tl = reinterpret_cast<float*>(smem);
     const int64_t i0 = (int64_t)blockIdx.x * kRawRows;
     for (int k = threadIdx.x; k < kRawRows * r; k += 256) Tl[k] = 0.0f;
@@ -923,12 +924,15 @@ __global__ __launch_bounds__(256) void k_raw_gq(const typename D::elem* __restri
     }
 }
 
-__global__ __launch_bounds__(256) void k_fill_zero(float* __restrict__ p, int64_t count) {
+__global__ __launch_bounds__(256) void k_fill_zero(float* __restrict__ p, int64_t count, const int32_t* __restrict__ gate) {
+    if (gate && *gate != LSP_ERR_SKEW) return;
     for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < count; k += (int64_t)gridDim.x * 256) p[k] = 0.0f;
 }
 
 __global__ __launch_bounds__(256) void k_raw_pt(const float* __restrict__ T, const int32_t* __restrict__ P_idx,
-                                               const float* __restrict__ P_val, float* __restrict__ S, int r, int d) {
+                                               const float* __restrict__ P_val, float* __restrict__ S, int r, int d,
+                                               const int32_t* __restrict__ gate) {
+    if (gate && *gate != LSP_ERR_SKEW) return;
     const int64_t i = blockIdx.x;
     for (int k = 0; k < d; ++k) {
         const int a = P_idx[i * d + k];
@@ -1019,31 +1023,31 @@ hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_d
 
 template <typename D>
 static hipError_t launch_raw_gq(const void* G, const int32_t* Q_idx, const float* Q_val, float* T,
-                                int64_t m, int64_t n, int32_t r, int32_t d, hipStream_t st) {
+                                int64_t m, int64_t n, int32_t r, int32_t d, const int32_t* gate, hipStream_t st) {
     const size_t lds = (size_t)kRawRows * r * sizeof(float);
     hipError_t e = allow_dynamic_lds<k_raw_gq<D>>((size_t)kRawRows * LSP_MAX_R * sizeof(float));
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_raw_gq<D>, dim3((unsigned)((m + kRawRows - 1) / kRawRows)), dim3(256), lds, st,
-                       reinterpret_cast<const typename D::elem*>(G), Q_idx, Q_val, T, (int)m, (int)n, (int)r, (int)d);
+                       reinterpret_cast<const typename D::elem*>(G), Q_idx, Q_val, T, (int)m, (int)n, (int)r, (int)d, gate);
     return hipGetLastError();
 }
 
 hipError_t launch_compress_raw(const void* G, const int32_t* P_idx, const float* P_val,
                                const int32_t* Q_idx, const float* Q_val,
                                int64_t m, int64_t n, int32_t r, int32_t d,
-                               float* S, lsp_dtype dtype, float* T, hipStream_t st) {
+                               float* S, lsp_dtype dtype, float* T, const int32_t* gate, hipStream_t st) {
     hipError_t e;
     switch (dtype) {
-        case LSP_F32:  e = launch_raw_gq<F32>(G, Q_idx, Q_val, T, m, n, r, d, st); break;
-        case LSP_F16:  e = launch_raw_gq<F16>(G, Q_idx, Q_val, T, m, n, r, d, st); break;
-        default:       e = launch_raw_gq<BF16>(G, Q_idx, Q_val, T, m, n, r, d, st); break;
+        case LSP_F32:  e = launch_raw_gq<F32>(G, Q_idx, Q_val, T, m, n, r, d, gate, st); break;
+        case LSP_F16:  e = launch_raw_gq<F16>(G, Q_idx, Q_val, T, m, n, r, d, gate, st); break;
+        default:       e = launch_raw_gq<BF16>(G, Q_idx, Q_val, T, m, n, r, d, gate, st); break;
     }
     if (e != hipSuccess) return e;
     const int64_t rr = (int64_t)r * r;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((rr + 255) / 256 > 1024 ? 1024 : (rr + 255) / 256)), dim3(256), 0, st, S, rr);
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((rr + 255) / 256 > 1024 ? 1024 : (rr + 255) / 256)), dim3(256), 0, st, S, rr, gate);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_raw_pt, dim3((unsigned)m), dim3(256), 0, st, T, P_idx, P_val, S, (int)r, (int)d);
+    hipLaunchKernelGGL(k_raw_pt, dim3((unsigned)m), dim3(256), 0, st, T, P_idx, P_val, S, (int)r, (int)d, gate);
     return hipGetLastError();
 }
 

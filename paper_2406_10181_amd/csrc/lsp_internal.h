@@ -101,6 +101,10 @@ struct RowItem   { int32_t a; int32_t start; int32_t len; int32_t atomic; };
 int reorder_rows_host(const int32_t* idx, const float* val, int64_t rows, int32_t d, int32_t r,
                       int32_t* idx_out, float* val_out);
 
+// Byte offsets of the plan's sections (they depend on the shape only).
+struct PlanLayout { size_t off_q_seg, off_q_vcol, off_q_vcnt, off_q_perm, off_q_rows, off_p_item, off_p_ent, off_q_src, off_p_src, total; };
+PlanLayout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d);
+
 // Upper bounds (depend on shapes only) used to size the plan buffer.
 int    plan_list_cap(int32_t r, int32_t d);
 size_t plan_max_rows(int64_t n, int32_t r, int32_t d);
@@ -178,10 +182,11 @@ __device__ __forceinline__ int group_find(const int32_t* first, int count, int b
 bool       compress_group_uniform(const CompressGroup& g);
 bool       apply_group_uniform(const ApplyGroup& g, int32_t r, int32_t d);
 hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
+// Scatter form on raw ELL arrays.  gate (device, may be null): the kernels run only if *gate == LSP_ERR_SKEW.
 hipError_t launch_compress_raw(const void* G, const int32_t* P_idx, const float* P_val,
                                const int32_t* Q_idx, const float* Q_val,
                                int64_t m, int64_t n, int32_t r, int32_t d,
-                               float* S, lsp_dtype dtype, float* T, hipStream_t st);
+                               float* S, lsp_dtype dtype, float* T, const int32_t* gate, hipStream_t st);
 hipError_t launch_decompress(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
 // Estimation bias (Def. 2): `partial` holds bias_blocks(m, r) pairs of floats, `out` three floats.
 int64_t    bias_blocks(int64_t m, int32_t r);
@@ -195,6 +200,12 @@ hipError_t launch_validate(const int32_t* idx, int64_t count, int32_t r, int32_t
 // Values-only refresh of a plan (same indices, new values).
 hipError_t launch_plan_refresh(uint8_t* plan, const float* P_val, const float* Q_val,
                                int64_t m, int64_t n, int32_t r, int32_t d, hipStream_t st);
+// Device-side plan build (plan_device.hip): the bytes of build_plan_host, from kernels on `st`; workspace of
+// plan_build_workspace_bytes(); status_out (device, may be null) receives LSP_OK / LSP_ERR_INDEX / LSP_ERR_SKEW.
+size_t     plan_build_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d);
+hipError_t launch_plan_build(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
+                             int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* plan, uint8_t* workspace,
+                             int32_t* status_out, hipStream_t st);
 // C = op(A) op(B) + beta E on r x r fp32 matrices (matrix cores); ta / tb transpose an operand; E may be null.
 hipError_t launch_gemm_rr(const float* A, const float* B, float* C, int32_t r, bool ta, bool tb,
                           float beta, const float* E, hipStream_t st);

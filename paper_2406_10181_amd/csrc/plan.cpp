@@ -31,10 +31,8 @@ size_t plan_max_items(int64_t m, int32_t r, int32_t d) {
     return (size_t)((int64_t)r + (m * d + kRowPiece - 1) / kRowPiece + 1);
 }
 
-namespace {
-struct Layout { size_t off_q_seg, off_q_vcol, off_q_vcnt, off_q_perm, off_q_rows, off_p_item, off_p_ent, off_q_src, off_p_src, total; };
-Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
-    Layout L;
+PlanLayout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
+    PlanLayout L;
     const size_t nchunks = (size_t)((n + kChunk - 1) / kChunk);
     size_t o = kPlanHeaderBytes;
     L.off_q_seg  = o; o = align_up(o + nchunks * kMaxSlots * kWavesGQ * sizeof(uint32_t), 256);
@@ -49,6 +47,7 @@ Layout plan_layout(int64_t m, int64_t n, int32_t r, int32_t d) {
     L.total = o;
     return L;
 }
+namespace {
 uint32_t float_bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
 }  // namespace
 
@@ -56,7 +55,7 @@ size_t plan_bytes(int64_t m, int64_t n, int32_t r, int32_t d) { return plan_layo
 
 int build_plan_host(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
                     int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* out) {
-    const Layout L = plan_layout(m, n, r, d);
+    const PlanLayout L = plan_layout(m, n, r, d);
     const int nchunks = (int)((n + kChunk - 1) / kChunk);
     const int cap = plan_list_cap(r, d);
 
