@@ -14,8 +14,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblsp_hip.so")
 OBJDIR = os.path.join(PKG, "_build")
-SOURCES = ["api.cpp", "plan.cpp", "plan_device.hip", "compress.hip", "decompress.hip", "reproject.hip", "fitgrad.hip",
-           "noalloc.hip", "probe.hip"]
+SOURCES = ["compress_gq16_bf16.hip", "compress_gq16_f16.hip", "compress_gq32.hip", "plan_device.hip", "decompress.hip",
+           "compress.hip", "api.cpp", "plan.cpp", "reproject.hip", "fitgrad.hip", "noalloc.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
@@ -26,7 +26,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, defines=(), sources=None, jobs: int = 8) -> str:
+def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, defines=(), sources=None, jobs: int = 8,
+          incremental: bool = False) -> str:
+    """incremental: reuse an object that is newer than its source and every header (development only; the default
+    compiles everything)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     sources = [s for s in (sources or SOURCES) if os.path.exists(os.path.join(CSRC, s))]
     tag = os.path.splitext(os.path.basename(out))[0]
@@ -34,8 +37,25 @@ def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, define
     os.makedirs(objdir, exist_ok=True)
     base = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC] + [f"-D{x}" for x in defines]
 
+    def newest_dependency(path: str, seen=None) -> float:
+        """Latest modification time of a source and of the project headers it includes, directly or not."""
+        seen = set() if seen is None else seen
+        if path in seen or not os.path.exists(path):
+            return 0.0
+        seen.add(path)
+        t = os.path.getmtime(path)
+        for line in open(path):
+            line = line.strip()
+            if line.startswith('#include "'):
+                name = line.split('"')[1]
+                for folder in (CSRC, os.path.join(ROOT, "include")):
+                    t = max(t, newest_dependency(os.path.join(folder, name), seen))
+        return t
+
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > newest_dependency(os.path.join(CSRC, src)):
+            return obj
         cmd = base + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         if save_temps:
             cmd += ["-save-temps=obj"]
@@ -54,4 +74,4 @@ def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, define
 
 
 if __name__ == "__main__":
-    build(save_temps="--save-temps" in sys.argv)
+    build(save_temps="--save-temps" in sys.argv, incremental="--incremental" in sys.argv)

@@ -1,0 +1,96 @@
+// Pieces shared by the translation units of the compress path (kernel A in its 16-bit and its
+// fp32-staged variants, kernel B and the launchers).
+#pragma once
+
+#include <utility>
+
+#include "lsp_internal.h"
+
+namespace lsp {
+
+constexpr int kPlaneStride = kChunk * 16 + 16;   // bytes; last 16 bytes of a plane stay zero
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// A plan is only followed when its header names this very problem: the offsets and counts in it
+// index S and T with the call's r and m, so a plan built for other sizes (or a buffer that holds no
+// plan at all) must not be walked.  Kernel A then fills S with NaN, which is how the caller sees
+// the mistake, and kernel B does nothing; all kernels exit normally.
+__device__ __forceinline__ bool plan_matches(PlanHeaderPtr H, int m, int n, int r, int d) {
+    return H->magic == kPlanMagic && H->m == m && H->n == n && H->r == r && H->d == d;
+}
+__device__ __forceinline__ void poison_s(float* __restrict__ S, int r, int block, int nblocks, int tid, int nthreads) {
+    const int64_t total = (int64_t)r * r;
+    for (int64_t k = (int64_t)block * nthreads + tid; k < total; k += (int64_t)nblocks * nthreads) S[k] = __builtin_nanf("");
+}
+
+
+// Kernel A: one workgroup = 16 rows of G, 512 threads, one lane per (virtual) column of T.
+constexpr int kPlanes = 4;                                    // 4-row planes of an fp32-staged chunk
+constexpr int kRowsGQ = 4 * kPlanes;
+constexpr int kBatchLoads = kSegBatch / 2;                    // 128-bit loads per batch of plan rows
+
+// Partial sums of several owners of one column meet in LDS: every lane parks its 16 sums at its
+// virtual column, [16][nslots * 512] floats; the first owner of a column then adds the owners'
+// sums in owner order (they sit side by side) and stores the column of T.  No atomics, so the
+// result does not depend on timing.  Called by all threads of the workgroup.
+template <int NS>
+__device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* plan, PlanHeaderPtr H, float* __restrict__ T,
+                                                  const float (&acc)[NS][kRowsGQ], int nslots, int64_t i0, int m, int r, int tid) {
+    __syncthreads();                                                  // the staged chunk is no longer read
+    float* Tl = reinterpret_cast<float*>(smem);
+    const int V = nslots * kThreadsGQ;
+    const auto* vcol = as_const<uint16_t>(plan + H->off_q_vcol);
+    const auto* vcnt = as_const<uint16_t>(plan + H->off_q_vcnt);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        if (s < nslots) {
+#pragma unroll
+            for (int t = 0; t < kRowsGQ; ++t) Tl[t * V + s * kThreadsGQ + tid] = acc[s][t];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        if (s < nslots) {
+            const int v = s * kThreadsGQ + tid;
+            const int owners = vcnt[v];
+            if (owners > 0) {
+                const uint32_t bb = vcol[v] & 0x7FFFu;
+                for (int t = 0; t < kRowsGQ; ++t) {
+                    float sum = Tl[t * V + v];
+                    for (int o = 1; o < owners; ++o) sum += Tl[t * V + v + o];
+                    if (i0 + t < m) T[(i0 + t) * (int64_t)r + bb] = sum;
+                }
+            }
+        }
+    }
+}
+
+// Hands the 16 partial sums of every virtual column from the lane that walked its list in one
+// chunk to the lane that walks it in the next (`from`, `to`: virtual columns of this thread; the
+// plan deals the lists of each chunk to the waves by length).  They pass through the first 32 KB
+// of `area`, the LDS of the chunk consumed last: the first barrier makes sure nobody reads that
+// chunk any more (and publishes whatever was written to other LDS before the call), the last one
+// that the area may be staged into again.  Called by all threads.
+__device__ __forceinline__ void swap_owner(uint8_t* area, float (&acc)[16], uint32_t from, uint32_t to) {
+    f32x4* X = reinterpret_cast<f32x4*>(area);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        X[q * kThreadsGQ + from] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};   // lanes spread over all banks
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f32x4 a = X[q * kThreadsGQ + to];
+        acc[4 * q] = a[0]; acc[4 * q + 1] = a[1]; acc[4 * q + 2] = a[2]; acc[4 * q + 3] = a[3];
+    }
+    __syncthreads();
+}
+
+
+// Launchers of kernel A (first_gq filled in): fp16 / bf16 with rows of whole 8-element groups, and the rest.
+hipError_t launch_gq16_bf16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
+hipError_t launch_gq16_f16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
+hipError_t launch_gq_staged32(const CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
+
+}  // namespace lsp

@@ -1,0 +1,388 @@
+// Compress, kernel A, 16-bit variant (fp16 / bf16 storage, rows of whole 8-element groups): the template
+// code; compress_gq16_bf16.hip and compress_gq16_f16.hip instantiate it.  See compress.hip for the path as a whole.
+#pragma once
+
+#include "compress_common.h"
+
+namespace lsp {
+
+// ----------------------------------------------------------------------------------------------
+// 16-bit storage types (fp16, bf16), n % 8 == 0, one column per lane: G is staged as it is stored,
+// 8 rows to a 16-byte LDS unit ([plane of 8 rows][column][8 rows]), so one 128-bit gather serves
+// eight rows (half the LDS bytes per pair) and a chunk takes half the space: the LDS holds two
+// chunks, the one being consumed and the one being staged, with one barrier per chunk.  The
+// elements are widened in registers when they are used (exact: a shift or mask for bf16, a
+// conversion for fp16).
+constexpr int kPlanes16 = 2;                                          // planes of 8 rows
+constexpr int kBufStride16 = kPlanes16 * kPlaneStride;                // bytes between the two chunk buffers
+static_assert(2 * kBufStride16 == kPlanes * kPlaneStride, "both layouts use the same LDS allocation");
+
+template <typename D> __device__ __forceinline__ void widen2(uint32_t w, float& lo, float& hi);
+template <> __device__ __forceinline__ void widen2<BF16>(uint32_t w, float& lo, float& hi) {
+    lo = __uint_as_float(w << 16); hi = __uint_as_float(w & 0xFFFF0000u);
+}
+template <> __device__ __forceinline__ void widen2<F16>(uint32_t w, float& lo, float& hi) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 h; __builtin_memcpy(&h, &w, 4);
+    lo = (float)h.x; hi = (float)h.y;
+}
+
+struct ChunkStager16 {
+    u32x4 pre[8];                                                     // 8 rows x 8 columns, as stored
+    uint32_t live = 0;                                                // bit t: pre[t] holds data of the matrix
+
+    template <typename E>
+    __device__ __forceinline__ void fetch(const E* __restrict__ G, int64_t i0, int m, int n, int c, int tid) {
+        const int plane = tid / (kChunk / 8), oct = tid % (kChunk / 8);
+        const int64_t col0 = (int64_t)c * kChunk + (int64_t)oct * 8;
+        const int64_t colc = col0 < n ? col0 : 0;                    // clamped: always a valid address
+        live = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int64_t row = i0 + plane * 8 + t;
+            const int64_t rowc = row < m ? row : (int64_t)m - 1;
+            pre[t] = stream_load(reinterpret_cast<const u32x4*>(G + rowc * (int64_t)n + colc));
+            live |= (row < m && col0 < n) ? (1u << t) : 0u;
+        }
+    }
+    // transposes the 8x8 block and writes its 8 units (column q: rows 0..7) into buffer `buf`
+    __device__ __forceinline__ void stage(uint8_t* smem, int buf, int tid) {
+        const int plane = tid / (kChunk / 8), oct = tid % (kChunk / 8);
+        if (live != 0xFFu) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (!((live >> t) & 1u)) pre[t] = u32x4{0u, 0u, 0u, 0u};
+        }
+        uint8_t* base = smem + buf * kBufStride16 + plane * kPlaneStride + oct * 16;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            u32x4 unit;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t a = pre[2 * k][q >> 1], b = pre[2 * k + 1][q >> 1];   // rows 2k, 2k+1; columns q&~1, q|1
+                unit[k] = (q & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+            }
+            *reinterpret_cast<u32x4*>(base + q * (kChunk / 8) * 16) = unit;
+        }
+    }
+};
+
+__device__ __forceinline__ void gather_pair16(const uint8_t* buf, const u32x4 e, u32x4 (&x)[2][kPlanes16]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int g = 0; g < kPlanes16; ++g)
+            x[h][g] = *reinterpret_cast<const u32x4*>(buf + (h ? e.z : e.x) + g * kPlaneStride);
+}
+template <typename D>
+__device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][kPlanes16], float (&acc)[kRowsGQ]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float v = __uint_as_float(h ? e.w : e.y);
+#pragma unroll
+        for (int g = 0; g < kPlanes16; ++g)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float lo, hi;
+                widen2<D>(x[h][g][k], lo, hi);
+                acc[g * 8 + 2 * k]     = fmaf(v, lo, acc[g * 8 + 2 * k]);
+                acc[g * 8 + 2 * k + 1] = fmaf(v, hi, acc[g * 8 + 2 * k + 1]);
+            }
+    }
+}
+
+// One workgroup walks `nblk` consecutive blocks of 16 rows (several when the grid is big: the first
+// chunk of the next block is fetched and staged while the last chunk of the current one is
+// consumed, and the stores of T go out under the next block's work, so that the set-up and the
+// tail of a block cost nothing but for the first and the last one).
+template <typename D>
+__device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+                                              const uint8_t* __restrict__ plan, PlanHeaderPtr H,
+                                              float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
+                                              int tid, int lane, int wave) {
+    const int nchunks = H->nchunks;
+    const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
+    const u32x4* rp0 = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+    const u32x4* rp = rp0;
+    const uint32_t mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
+    const bool shared = H->q_any_shared != 0;
+    const uint16_t* __restrict__ perm = reinterpret_cast<const uint16_t*>(plan + H->off_q_perm) + tid;
+    const uint32_t first = perm[0];
+    uint32_t walked = first;                                          // virtual column whose list this thread walks
+
+    // ring of kPrefetch batches of plan rows in fixed register slots (see gq_one_slot)
+    u32x4 ring[kPrefetch][kBatchLoads];
+    auto ring_restart = [&]() {
+        rp = rp0;
+#pragma unroll
+        for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+            for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
+        rp += (size_t)kPrefetch * kBatchLoads * kWave;
+    };
+    ring_restart();
+
+    float acc[1][kRowsGQ];
+#pragma unroll
+    for (int t = 0; t < kRowsGQ; ++t) acc[0][t] = 0.0f;
+
+    const uint8_t* buf = smem;
+    auto step = [&](u32x4 (&slot)[kBatchLoads]) {
+        u32x4 x[2][2][kPlanes16];
+        gather_pair16(buf, slot[0], x[0]);
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) {
+            if (q + 1 < kBatchLoads) gather_pair16(buf, slot[q + 1], x[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            fma_pair16<D>(slot[q], x[q & 1], acc[0]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) slot[q] = rp[(size_t)q * kWave];
+        rp += (size_t)kBatchLoads * kWave;
+    };
+
+    stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
+    __syncthreads();
+    int rot = 0, c = 0, blk = 0;
+    const int units = nblk * nchunks;                                 // (row block, chunk) pairs, in order
+    for (int u = 0; u < units; ++u) {
+        if (rot != 0) {                                               // undo the slot rotation left by the previous chunk
+            u32x4 t[kPrefetch][kBatchLoads];
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) {
+                    t[k][q] = ring[(k + 1) % kPrefetch][q];
+                    if (rot == 2) t[k][q] = ring[(k + 2) % kPrefetch][q];
+                    if (rot == 3) t[k][q] = ring[(k + 3) % kPrefetch][q];
+                }
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = t[k][q];
+        }
+        static_assert(kPrefetch == 4, "the rotation above is written for four slots");
+        const bool last_chunk = c + 1 == nchunks;
+        const uint32_t next = last_chunk ? (uint32_t)tid : (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ];
+        if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * kRowsGQ, m, n, last_chunk ? 0 : c + 1, tid);
+        buf = smem + (u & 1) * kBufStride16;
+        const bool more = u + 1 < units;
+        // The next chunk is staged (into the buffer nobody reads now) in the middle of this one's
+        // work rather than at its end, where every wave would wait for it; only a block's last
+        // chunk with shared columns stages later, behind the merge that uses the same LDS.
+        const bool stage_early = more && !(last_chunk && shared);
+        const int nb = (int)(seg[c * kWavesGQ] / kSegBatch);
+        const int groups = nb / kPrefetch, before = groups < 2 ? groups : 2;
+        for (int g = before; g > 0; --g) {
+            step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
+        }
+        if (stage_early) stg.stage(smem, (u + 1) & 1, tid);
+        for (int g = groups - before; g > 0; --g) {
+            step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
+        }
+        rot = nb % kPrefetch;
+        if (rot > 0) step(ring[0]);
+        if (rot > 1) step(ring[1]);
+        if (rot > 2) step(ring[2]);
+        // The sums move to the lanes that walk the columns in the next chunk; after the last chunk
+        // of a block they go home (thread t: virtual column t) and out to T.
+        if (last_chunk && more) { ring_restart(); rot = 0; }          // the stream starts over; in flight during the stores
+        swap_owner(smem + (u & 1) * kBufStride16, acc[0], walked, next);
+        if (last_chunk) {
+            const int64_t ib = i0 + (int64_t)blk * kRowsGQ;
+            if (shared) {
+                write_tile_shared<1>(smem, plan, H, T, acc, 1, ib, m, r, tid);   // uses the LDS of the first chunk buffer
+                if (more) {
+                    __syncthreads();                                  // before that LDS is staged into again
+                    stg.stage(smem, (u + 1) & 1, tid);
+                    __syncthreads();
+                }
+            } else if (mycol != kNoColumn) {
+#pragma unroll
+                for (int t = 0; t < kRowsGQ; ++t)
+                    if (ib + t < m) T[(ib + t) * (int64_t)r + mycol] = acc[0][t];
+            }
+        }
+        if (last_chunk) {                                             // the block's sums are out
+#pragma unroll
+            for (int t = 0; t < kRowsGQ; ++t) acc[0][t] = 0.0f;
+            c = 0; ++blk;
+            walked = first;
+        } else {
+            ++c;
+            walked = next;
+        }
+    }
+}
+
+// Several columns per lane (r > 512, or columns used so unevenly that they were split), 16-bit
+// storage: the same staging, plan ring and block walk as gq16_one_slot, the lane's columns taken
+// slot by slot inside each chunk.  A lane keeps its columns for all chunks (no dealing by length:
+// the sums of NS columns per lane would not fit through LDS cheaply).
+template <typename D, int NS>
+__device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+                                                const uint8_t* __restrict__ plan, PlanHeaderPtr H,
+                                                float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
+                                                int tid, int lane, int wave) {
+    const int nchunks = H->nchunks, nslots = H->nslots;
+    const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
+    const u32x4* rp0 = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
+    const u32x4* rp = rp0;
+    const auto* vcol = as_const<uint16_t>(plan + H->off_q_vcol);
+    const bool shared = H->q_any_shared != 0;
+
+    u32x4 ring[kPrefetch][kBatchLoads];                               // fixed register slots (see gq_one_slot)
+    auto ring_restart = [&]() {
+        rp = rp0;
+#pragma unroll
+        for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+            for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
+        rp += (size_t)kPrefetch * kBatchLoads * kWave;
+    };
+    ring_restart();
+
+    float acc[NS][kRowsGQ];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int t = 0; t < kRowsGQ; ++t) acc[s][t] = 0.0f;
+
+    const uint8_t* buf = smem;
+    auto step = [&](u32x4 (&slot)[kBatchLoads], float (&a)[kRowsGQ]) {
+        u32x4 x[2][2][kPlanes16];
+        gather_pair16(buf, slot[0], x[0]);
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) {
+            if (q + 1 < kBatchLoads) gather_pair16(buf, slot[q + 1], x[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            fma_pair16<D>(slot[q], x[q & 1], a);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int q = 0; q < kBatchLoads; ++q) slot[q] = rp[(size_t)q * kWave];
+        rp += (size_t)kBatchLoads * kWave;
+    };
+    static_assert(kPrefetch == 4, "the rotation below is written for four slots");
+    auto unrotate = [&](int rot) {                                    // slot 0 holds the oldest batch again
+        if (rot != 0) {
+            u32x4 t[kPrefetch][kBatchLoads];
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) {
+                    t[k][q] = ring[(k + 1) % kPrefetch][q];
+                    if (rot == 2) t[k][q] = ring[(k + 2) % kPrefetch][q];
+                    if (rot == 3) t[k][q] = ring[(k + 3) % kPrefetch][q];
+                }
+#pragma unroll
+            for (int k = 0; k < kPrefetch; ++k)
+#pragma unroll
+                for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = t[k][q];
+        }
+    };
+
+    stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
+    __syncthreads();
+    int rot = 0, c = 0, blk = 0;
+    const int units = nblk * nchunks;
+    for (int u = 0; u < units; ++u) {
+        const bool last_chunk = c + 1 == nchunks;
+        const bool more = u + 1 < units;
+        if (more)
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * kRowsGQ, m, n, last_chunk ? 0 : c + 1, tid);
+        buf = smem + (u & 1) * kBufStride16;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s < nslots) {
+                unrotate(rot);
+                const int nb = (int)(seg[(c * nslots + s) * kWavesGQ] / kSegBatch);
+                for (int g = nb / kPrefetch; g > 0; --g) {
+                    step(ring[0], acc[s]); step(ring[1], acc[s]); step(ring[2], acc[s]); step(ring[3], acc[s]);
+                }
+                rot = nb % kPrefetch;
+                if (rot > 0) step(ring[0], acc[s]);
+                if (rot > 1) step(ring[1], acc[s]);
+                if (rot > 2) step(ring[2], acc[s]);
+            }
+        }
+        if (last_chunk) {                                             // the block's 16 sums per column are complete
+            const int64_t ib = i0 + (int64_t)blk * kRowsGQ;
+            if (more) { ring_restart(); rot = 0; }                    // the stream starts over; in flight during the stores
+            if (shared) {
+                write_tile_shared<NS>(smem, plan, H, T, acc, nslots, ib, m, r, tid);   // uses the LDS of both chunk buffers
+                if (more) {
+                    __syncthreads();                                  // before that LDS is staged into again
+                    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const uint32_t col = s < nslots ? (uint32_t)vcol[s * kThreadsGQ + tid] : kNoColumn;
+                    if (col != kNoColumn) {
+#pragma unroll
+                        for (int t = 0; t < kRowsGQ; ++t)
+                            if (ib + t < m) T[(ib + t) * (int64_t)r + col] = acc[s][t];
+                    }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+#pragma unroll
+                for (int t = 0; t < kRowsGQ; ++t) acc[s][t] = 0.0f;
+            c = 0; ++blk;
+        } else {
+            ++c;
+        }
+        if (more) stg.stage(smem, (u + 1) & 1, tid);                  // the other buffer: nobody reads it now
+        __syncthreads();                                              // the next chunk is staged; this one is no longer read
+    }
+}
+
+// Kernel A for fp16 / bf16 with n % 8 == 0.
+template <typename D>
+__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r, int d, int blocks_per_wg) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
+    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
+    const uint8_t* __restrict__ plan = pr.plan;
+    float* __restrict__ T = pr.T;
+    float* __restrict__ S = pr.S;
+    const int m = pr.m, n = pr.n;
+    const int block = pr.block_gq, nblocks = pr.nblocks_gq;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t i0 = (int64_t)block * blocks_per_wg * kRowsGQ;
+    const int nblk = min(blocks_per_wg, (int)((m - i0 + kRowsGQ - 1) / kRowsGQ));   // row blocks of this workgroup
+
+    PlanHeaderPtr H = as_const<PlanHeader>(plan);
+    if (!plan_matches(H, m, n, r, d)) {                               // not a plan for this problem
+        poison_s(S, r, block, nblocks, tid, kThreadsGQ);
+        return;
+    }
+    if (H->p_any_split) {
+        const int64_t total = (int64_t)r * r;
+        for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
+    }
+    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    ChunkStager16 stg;
+    stg.fetch(G, i0, m, n, 0, tid);
+    if (H->nslots == 1)      gq16_one_slot<D>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else if (H->nslots == 2) gq16_multi_slot<D, 2>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else                     gq16_multi_slot<D, kMaxSlots>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+}
+
+
+template <typename D>
+static hipError_t launch_gq16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st) {
+    constexpr size_t lds = (size_t)kPlanes * kPlaneStride;   // two chunk buffers of two 8-row planes
+    hipError_t e;
+    if ((e = allow_dynamic_lds<k_compress_gq16<D>>(lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL(k_compress_gq16<D>, dim3((unsigned)g.first_gq[g.count]), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d, blocks_per_wg);
+    return hipGetLastError();
+}
+
+}  // namespace lsp
