@@ -178,9 +178,14 @@ bool compress_group_uniform(const CompressGroup& g) {
 // Row blocks per workgroup of kernel A: several on big grids (grouped calls) of the 16-bit kernel
 static int gq_blocks_per_wg(const CompressGroup& g, lsp_dtype dtype) {
     if (dtype == LSP_F32 || g.n[0] % 8 != 0) return 1;
-    int64_t blocks = 0;
-    for (int p = 0; p < g.count; ++p) blocks += (g.m[p] + kRowsGQ - 1) / kRowsGQ;
-    return blocks >= 1024 ? 2 : 1;
+    int64_t rows = 0;
+    for (int p = 0; p < g.count; ++p) rows += g.m[p];
+    return rows >= 16384 ? 2 : 1;
+}
+
+// Rows of a row block of kernel A: the 16-bit kernel and the 32-bit-staged kernel differ
+static int gq_block_rows(const CompressGroup& g, lsp_dtype dtype) {
+    return (dtype != LSP_F32 && g.n[0] % 8 == 0) ? kRowsGQ16 : kRowsGQ;
 }
 
 static hipError_t launch_gq(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, lsp_dtype dtype, hipStream_t st) {
@@ -205,10 +210,10 @@ hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_d
     const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
     const bool striped = (r % 4) == 0;
     longest_first(g);
-    const int bpw = gq_blocks_per_wg(g, dtype);
+    const int bpw = gq_blocks_per_wg(g, dtype), rows = gq_block_rows(g, dtype);
     g.first_gq[0] = g.first_pt[0] = 0;
     for (int p = 0; p < g.count; ++p) {
-        g.first_gq[p + 1] = g.first_gq[p] + (int32_t)(((g.m[p] + kRowsGQ - 1) / kRowsGQ + bpw - 1) / bpw);
+        g.first_gq[p + 1] = g.first_gq[p] + (int32_t)(((g.m[p] + rows - 1) / rows + bpw - 1) / bpw);
         const int32_t items = (int32_t)plan_max_items(g.m[p], r, d);
         g.first_pt[p + 1] = g.first_pt[p] + (striped ? ((items + 3) / 4) * 8 : items * nstripes);
     }

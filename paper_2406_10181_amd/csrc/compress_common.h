@@ -33,9 +33,9 @@ constexpr int kBatchLoads = kSegBatch / 2;                    // 128-bit loads p
 // virtual column, [16][nslots * 512] floats; the first owner of a column then adds the owners'
 // sums in owner order (they sit side by side) and stores the column of T.  No atomics, so the
 // result does not depend on timing.  Called by all threads of the workgroup.
-template <int NS>
+template <int NS, int R = kRowsGQ>
 __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* plan, PlanHeaderPtr H, float* __restrict__ T,
-                                                  const float (&acc)[NS][kRowsGQ], int nslots, int64_t i0, int m, int r, int tid) {
+                                                  const float (&acc)[NS][R], int nslots, int64_t i0, int m, int r, int tid) {
     __syncthreads();                                                  // the staged chunk is no longer read
     float* Tl = reinterpret_cast<float*>(smem);
     const int V = nslots * kThreadsGQ;
@@ -45,7 +45,7 @@ __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* 
     for (int s = 0; s < NS; ++s) {
         if (s < nslots) {
 #pragma unroll
-            for (int t = 0; t < kRowsGQ; ++t) Tl[t * V + s * kThreadsGQ + tid] = acc[s][t];
+            for (int t = 0; t < R; ++t) Tl[t * V + s * kThreadsGQ + tid] = acc[s][t];
         }
     }
     __syncthreads();
@@ -56,7 +56,7 @@ __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* 
             const int owners = vcnt[v];
             if (owners > 0) {
                 const uint32_t bb = vcol[v] & 0x7FFFu;
-                for (int t = 0; t < kRowsGQ; ++t) {
+                for (int t = 0; t < R; ++t) {
                     float sum = Tl[t * V + v];
                     for (int o = 1; o < owners; ++o) sum += Tl[t * V + v + o];
                     if (i0 + t < m) T[(i0 + t) * (int64_t)r + bb] = sum;
@@ -66,21 +66,22 @@ __device__ __forceinline__ void write_tile_shared(uint8_t* smem, const uint8_t* 
     }
 }
 
-// Hands the 16 partial sums of every virtual column from the lane that walked its list in one
+// Hands the R partial sums of every virtual column from the lane that walked its list in one
 // chunk to the lane that walks it in the next (`from`, `to`: virtual columns of this thread; the
-// plan deals the lists of each chunk to the waves by length).  They pass through the first 32 KB
+// plan deals the lists of each chunk to the waves by length).  They pass through the first 2 R KB
 // of `area`, the LDS of the chunk consumed last: the first barrier makes sure nobody reads that
 // chunk any more (and publishes whatever was written to other LDS before the call), the last one
 // that the area may be staged into again.  Called by all threads.
-__device__ __forceinline__ void swap_owner(uint8_t* area, float (&acc)[16], uint32_t from, uint32_t to) {
+template <int R>
+__device__ __forceinline__ void swap_owner(uint8_t* area, float (&acc)[R], uint32_t from, uint32_t to) {
     f32x4* X = reinterpret_cast<f32x4*>(area);
     __syncthreads();
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < R / 4; ++q)
         X[q * kThreadsGQ + from] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};   // lanes spread over all banks
     __syncthreads();
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < R / 4; ++q) {
         const f32x4 a = X[q * kThreadsGQ + to];
         acc[4 * q] = a[0]; acc[4 * q + 1] = a[1]; acc[4 * q + 2] = a[2]; acc[4 * q + 3] = a[3];
     }
@@ -89,6 +90,8 @@ __device__ __forceinline__ void swap_owner(uint8_t* area, float (&acc)[16], uint
 
 
 // Launchers of kernel A (first_gq filled in): fp16 / bf16 with rows of whole 8-element groups, and the rest.
+// rows of G per row block of the 16-bit kernel (a workgroup holds that many rows of two chunks in LDS)
+constexpr int kRowsGQ16 = 16;
 hipError_t launch_gq16_bf16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
 hipError_t launch_gq16_f16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
 hipError_t launch_gq_staged32(const CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);

@@ -7,16 +7,13 @@
 namespace lsp {
 
 // ----------------------------------------------------------------------------------------------
-// 16-bit storage types (fp16, bf16), n % 8 == 0, one column per lane: G is staged as it is stored,
-// 8 rows to a 16-byte LDS unit ([plane of 8 rows][column][8 rows]), so one 128-bit gather serves
-// eight rows (half the LDS bytes per pair) and a chunk takes half the space: the LDS holds two
-// chunks, the one being consumed and the one being staged, with one barrier per chunk.  The
-// elements are widened in registers when they are used (exact: a shift or mask for bf16, a
-// conversion for fp16).
-constexpr int kPlanes16 = 2;                                          // planes of 8 rows
-constexpr int kBufStride16 = kPlanes16 * kPlaneStride;                // bytes between the two chunk buffers
-static_assert(2 * kBufStride16 == kPlanes * kPlaneStride, "both layouts use the same LDS allocation");
-
+// 16-bit storage types (fp16, bf16), n % 8 == 0: G is staged as it is stored, 8 rows to a 16-byte LDS
+// unit ([plane of 8 rows][column][8 rows]), so one 128-bit gather serves eight rows, and the LDS holds two
+// chunks, the one being consumed and the one being staged, with one barrier per chunk.  The elements are
+// widened in registers when they are used (exact: a shift or mask for bf16, a conversion for fp16).
+// RP = planes of 8 rows per workgroup.  With RP = 1 (8 rows, 64 KB of LDS, at most 128 registers per lane) two
+// workgroups share a CU, four waves per SIMD: a single wave issues a vector instruction only every 5 to 6
+// cycles, so a SIMD needs more than two resident waves to stay busy while some of them wait at a barrier.
 template <typename D> __device__ __forceinline__ void widen2(uint32_t w, float& lo, float& hi);
 template <> __device__ __forceinline__ void widen2<BF16>(uint32_t w, float& lo, float& hi) {
     lo = __uint_as_float(w << 16); hi = __uint_as_float(w & 0xFFFF0000u);
@@ -27,60 +24,94 @@ template <> __device__ __forceinline__ void widen2<F16>(uint32_t w, float& lo, f
     lo = (float)h.x; hi = (float)h.y;
 }
 
-struct ChunkStager16 {
+// Rows 2k and 2k+1 of two adjacent columns sit in the dwords a (row 2k) and b (row 2k+1); the unit
+// of the even column takes their low halves, that of the odd column their high halves (one byte permute).
+__device__ __forceinline__ uint32_t pair_rows(uint32_t a, uint32_t b, bool odd_column) {
+    return __builtin_amdgcn_perm(b, a, odd_column ? 0x07060302u : 0x05040100u);
+}
+
+// Fetches and stages a chunk of 8 RP rows.  Rows past the matrix are read from its last row and columns
+// past it from its first ones (always a valid address): what they hold is never used, as the plan
+// has no entry for such a column and the sums of such a row are not stored.  The rows of a thread
+// are the same for the whole wave, so the row addresses are scalar.
+template <int RP> struct ChunkStager16;
+
+// RP = 2: a thread fetches 8 rows x 8 columns (one 16-byte load per row)
+template <> struct ChunkStager16<2> {
     u32x4 pre[8];                                                     // 8 rows x 8 columns, as stored
-    uint32_t live = 0;                                                // bit t: pre[t] holds data of the matrix
 
     template <typename E>
-    __device__ __forceinline__ void fetch(const E* __restrict__ G, int64_t i0, int m, int n, int c, int tid) {
-        const int plane = tid / (kChunk / 8), oct = tid % (kChunk / 8);
-        const int64_t col0 = (int64_t)c * kChunk + (int64_t)oct * 8;
-        const int64_t colc = col0 < n ? col0 : 0;                    // clamped: always a valid address
-        live = 0;
+    __device__ __forceinline__ void fetch(const E* __restrict__ G, int64_t i0, int m, int n, int c, int tid, int wave) {
+        const int plane = wave / (kWavesGQ / 2), oct = tid % (kChunk / 8);
+        const uint32_t col0 = (uint32_t)c * kChunk + (uint32_t)oct * 8;
+        const uint32_t byte0 = (col0 < (uint32_t)n ? col0 : 0u) * (uint32_t)sizeof(E);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const int64_t row = i0 + plane * 8 + t;
             const int64_t rowc = row < m ? row : (int64_t)m - 1;
-            pre[t] = stream_load(reinterpret_cast<const u32x4*>(G + rowc * (int64_t)n + colc));
-            live |= (row < m && col0 < n) ? (1u << t) : 0u;
+            const char* rowp = reinterpret_cast<const char*>(G + rowc * (int64_t)n);
+            pre[t] = stream_load(reinterpret_cast<const u32x4*>(rowp + byte0));
         }
     }
     // transposes the 8x8 block and writes its 8 units (column q: rows 0..7) into buffer `buf`
     __device__ __forceinline__ void stage(uint8_t* smem, int buf, int tid) {
         const int plane = tid / (kChunk / 8), oct = tid % (kChunk / 8);
-        if (live != 0xFFu) {
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-                if (!((live >> t) & 1u)) pre[t] = u32x4{0u, 0u, 0u, 0u};
-        }
-        uint8_t* base = smem + buf * kBufStride16 + plane * kPlaneStride + oct * 16;
+        uint8_t* base = smem + buf * (2 * kPlaneStride) + plane * kPlaneStride + oct * 16;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             u32x4 unit;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint32_t a = pre[2 * k][q >> 1], b = pre[2 * k + 1][q >> 1];   // rows 2k, 2k+1; columns q&~1, q|1
-                unit[k] = (q & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
-            }
+            for (int k = 0; k < 4; ++k) unit[k] = pair_rows(pre[2 * k][q >> 1], pre[2 * k + 1][q >> 1], q & 1);
             *reinterpret_cast<u32x4*>(base + q * (kChunk / 8) * 16) = unit;
         }
     }
 };
 
-__device__ __forceinline__ void gather_pair16(const uint8_t* buf, const u32x4 e, u32x4 (&x)[2][kPlanes16]) {
+// RP = 1: a thread fetches 8 rows x 4 columns (one 8-byte load per row): 512 threads cover the 2048 columns
+template <> struct ChunkStager16<1> {
+    u32x2 pre[8];
+
+    template <typename E>
+    __device__ __forceinline__ void fetch(const E* __restrict__ G, int64_t i0, int m, int n, int c, int tid, int) {
+        const uint32_t col0 = (uint32_t)c * kChunk + (uint32_t)tid * 4;
+        const uint32_t byte0 = (col0 < (uint32_t)n ? col0 : 0u) * (uint32_t)sizeof(E);   // n % 8 == 0
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int64_t row = i0 + t;
+            const int64_t rowc = row < m ? row : (int64_t)m - 1;
+            const char* rowp = reinterpret_cast<const char*>(G + rowc * (int64_t)n);
+            pre[t] = stream_load(reinterpret_cast<const u32x2*>(rowp + byte0));
+        }
+    }
+    // transposes the 8x4 block and writes its 4 units (column q: rows 0..7) into buffer `buf`
+    __device__ __forceinline__ void stage(uint8_t* smem, int buf, int tid) {
+        // local column j = 4 tid + q sits at unit (j & 7) * (kChunk / 8) + (j >> 3)
+        uint8_t* base = smem + buf * kPlaneStride + ((4 * (tid & 1)) * (kChunk / 8) + (tid >> 1)) * 16;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32x4 unit;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) unit[k] = pair_rows(pre[2 * k][q >> 1], pre[2 * k + 1][q >> 1], q & 1);
+            *reinterpret_cast<u32x4*>(base + q * (kChunk / 8) * 16) = unit;
+        }
+    }
+};
+
+template <int RP>
+__device__ __forceinline__ void gather_pair16(const uint8_t* buf, const u32x4 e, u32x4 (&x)[2][RP]) {
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int g = 0; g < kPlanes16; ++g)
+        for (int g = 0; g < RP; ++g)
             x[h][g] = *reinterpret_cast<const u32x4*>(buf + (h ? e.z : e.x) + g * kPlaneStride);
 }
-template <typename D>
-__device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][kPlanes16], float (&acc)[kRowsGQ]) {
+template <typename D, int RP>
+__device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][RP], float (&acc)[8 * RP]) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const float v = __uint_as_float(h ? e.w : e.y);
 #pragma unroll
-        for (int g = 0; g < kPlanes16; ++g)
+        for (int g = 0; g < RP; ++g)
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float lo, hi;
@@ -95,11 +126,12 @@ __device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][kP
 // chunk of the next block is fetched and staged while the last chunk of the current one is
 // consumed, and the stores of T go out under the next block's work, so that the set-up and the
 // tail of a block cost nothing but for the first and the last one).
-template <typename D>
-__device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+template <typename D, int RP>
+__device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
                                               const uint8_t* __restrict__ plan, PlanHeaderPtr H,
                                               float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
                                               int tid, int lane, int wave) {
+    constexpr int R = 8 * RP;                                         // rows of a row block
     const int nchunks = H->nchunks;
     const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
     const u32x4* rp0 = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
@@ -122,19 +154,19 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
     };
     ring_restart();
 
-    float acc[1][kRowsGQ];
+    float acc[1][R];
 #pragma unroll
-    for (int t = 0; t < kRowsGQ; ++t) acc[0][t] = 0.0f;
+    for (int t = 0; t < R; ++t) acc[0][t] = 0.0f;
 
     const uint8_t* buf = smem;
     auto step = [&](u32x4 (&slot)[kBatchLoads]) {
-        u32x4 x[2][2][kPlanes16];
-        gather_pair16(buf, slot[0], x[0]);
+        u32x4 x[2][2][RP];
+        gather_pair16<RP>(buf, slot[0], x[0]);
 #pragma unroll
         for (int q = 0; q < kBatchLoads; ++q) {
-            if (q + 1 < kBatchLoads) gather_pair16(buf, slot[q + 1], x[(q + 1) & 1]);
+            if (q + 1 < kBatchLoads) gather_pair16<RP>(buf, slot[q + 1], x[(q + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
-            fma_pair16<D>(slot[q], x[q & 1], acc[0]);
+            fma_pair16<D, RP>(slot[q], x[q & 1], acc[0]);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -166,8 +198,8 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
         const bool last_chunk = c + 1 == nchunks;
         const uint32_t next = last_chunk ? (uint32_t)tid : (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ];
         if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
-            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * kRowsGQ, m, n, last_chunk ? 0 : c + 1, tid);
-        buf = smem + (u & 1) * kBufStride16;
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * R, m, n, last_chunk ? 0 : c + 1, tid, wave);
+        buf = smem + (u & 1) * (RP * kPlaneStride);
         const bool more = u + 1 < units;
         // The next chunk is staged (into the buffer nobody reads now) in the middle of this one's
         // work rather than at its end, where every wave would wait for it; only a block's last
@@ -189,11 +221,11 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
         // The sums move to the lanes that walk the columns in the next chunk; after the last chunk
         // of a block they go home (thread t: virtual column t) and out to T.
         if (last_chunk && more) { ring_restart(); rot = 0; }          // the stream starts over; in flight during the stores
-        swap_owner(smem + (u & 1) * kBufStride16, acc[0], walked, next);
+        swap_owner<R>(smem + (u & 1) * (RP * kPlaneStride), acc[0], walked, next);
         if (last_chunk) {
-            const int64_t ib = i0 + (int64_t)blk * kRowsGQ;
+            const int64_t ib = i0 + (int64_t)blk * R;
             if (shared) {
-                write_tile_shared<1>(smem, plan, H, T, acc, 1, ib, m, r, tid);   // uses the LDS of the first chunk buffer
+                write_tile_shared<1, R>(smem, plan, H, T, acc, 1, ib, m, r, tid);   // uses the LDS of the first chunk buffer
                 if (more) {
                     __syncthreads();                                  // before that LDS is staged into again
                     stg.stage(smem, (u + 1) & 1, tid);
@@ -201,13 +233,13 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
                 }
             } else if (mycol != kNoColumn) {
 #pragma unroll
-                for (int t = 0; t < kRowsGQ; ++t)
+                for (int t = 0; t < R; ++t)
                     if (ib + t < m) T[(ib + t) * (int64_t)r + mycol] = acc[0][t];
             }
         }
         if (last_chunk) {                                             // the block's sums are out
 #pragma unroll
-            for (int t = 0; t < kRowsGQ; ++t) acc[0][t] = 0.0f;
+            for (int t = 0; t < R; ++t) acc[0][t] = 0.0f;
             c = 0; ++blk;
             walked = first;
         } else {
@@ -221,11 +253,12 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16& stg, uint8_t* smem,
 // storage: the same staging, plan ring and block walk as gq16_one_slot, the lane's columns taken
 // slot by slot inside each chunk.  A lane keeps its columns for all chunks (no dealing by length:
 // the sums of NS columns per lane would not fit through LDS cheaply).
-template <typename D, int NS>
-__device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+template <typename D, int NS, int RP>
+__device__ __forceinline__ void gq16_multi_slot(ChunkStager16<RP>& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
                                                 const uint8_t* __restrict__ plan, PlanHeaderPtr H,
                                                 float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
                                                 int tid, int lane, int wave) {
+    constexpr int R = 8 * RP;                                         // rows of a row block
     const int nchunks = H->nchunks, nslots = H->nslots;
     const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
     const u32x4* rp0 = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
@@ -244,21 +277,21 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
     };
     ring_restart();
 
-    float acc[NS][kRowsGQ];
+    float acc[NS][R];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int t = 0; t < kRowsGQ; ++t) acc[s][t] = 0.0f;
+        for (int t = 0; t < R; ++t) acc[s][t] = 0.0f;
 
     const uint8_t* buf = smem;
-    auto step = [&](u32x4 (&slot)[kBatchLoads], float (&a)[kRowsGQ]) {
-        u32x4 x[2][2][kPlanes16];
-        gather_pair16(buf, slot[0], x[0]);
+    auto step = [&](u32x4 (&slot)[kBatchLoads], float (&a)[R]) {
+        u32x4 x[2][2][RP];
+        gather_pair16<RP>(buf, slot[0], x[0]);
 #pragma unroll
         for (int q = 0; q < kBatchLoads; ++q) {
-            if (q + 1 < kBatchLoads) gather_pair16(buf, slot[q + 1], x[(q + 1) & 1]);
+            if (q + 1 < kBatchLoads) gather_pair16<RP>(buf, slot[q + 1], x[(q + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
-            fma_pair16<D>(slot[q], x[q & 1], a);
+            fma_pair16<D, RP>(slot[q], x[q & 1], a);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -292,8 +325,8 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
         const bool last_chunk = c + 1 == nchunks;
         const bool more = u + 1 < units;
         if (more)
-            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * kRowsGQ, m, n, last_chunk ? 0 : c + 1, tid);
-        buf = smem + (u & 1) * kBufStride16;
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * R, m, n, last_chunk ? 0 : c + 1, tid, wave);
+        buf = smem + (u & 1) * (RP * kPlaneStride);
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             if (s < nslots) {
@@ -309,13 +342,13 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
             }
         }
         if (last_chunk) {                                             // the block's 16 sums per column are complete
-            const int64_t ib = i0 + (int64_t)blk * kRowsGQ;
+            const int64_t ib = i0 + (int64_t)blk * R;
             if (more) { ring_restart(); rot = 0; }                    // the stream starts over; in flight during the stores
             if (shared) {
-                write_tile_shared<NS>(smem, plan, H, T, acc, nslots, ib, m, r, tid);   // uses the LDS of both chunk buffers
+                write_tile_shared<NS, R>(smem, plan, H, T, acc, nslots, ib, m, r, tid);   // uses the LDS of both chunk buffers
                 if (more) {
                     __syncthreads();                                  // before that LDS is staged into again
-                    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                    if (tid < 2 * RP) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
                 }
             } else {
 #pragma unroll
@@ -323,7 +356,7 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
                     const uint32_t col = s < nslots ? (uint32_t)vcol[s * kThreadsGQ + tid] : kNoColumn;
                     if (col != kNoColumn) {
 #pragma unroll
-                        for (int t = 0; t < kRowsGQ; ++t)
+                        for (int t = 0; t < R; ++t)
                             if (ib + t < m) T[(ib + t) * (int64_t)r + col] = acc[s][t];
                     }
                 }
@@ -331,7 +364,7 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
 #pragma unroll
             for (int s = 0; s < NS; ++s)
 #pragma unroll
-                for (int t = 0; t < kRowsGQ; ++t) acc[s][t] = 0.0f;
+                for (int t = 0; t < R; ++t) acc[s][t] = 0.0f;
             c = 0; ++blk;
         } else {
             ++c;
@@ -341,9 +374,10 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16& stg, uint8_t* sme
     }
 }
 
-// Kernel A for fp16 / bf16 with n % 8 == 0.
-template <typename D>
-__global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGroup grp, int r, int d, int blocks_per_wg) {
+// Kernel A for fp16 / bf16 with n % 8 == 0: R = 8 RP rows per row block.
+template <typename D, int RP>
+__global__ __launch_bounds__(kThreadsGQ, RP == 1 ? 4 : 1) void k_compress_gq16(const CompressGroup grp, int r, int d, int blocks_per_wg) {
+    constexpr int R = 8 * RP;
     extern __shared__ __align__(16) uint8_t smem[];
     const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
     const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
@@ -355,9 +389,11 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t i0 = (int64_t)block * blocks_per_wg * kRowsGQ;
-    const int nblk = min(blocks_per_wg, (int)((m - i0 + kRowsGQ - 1) / kRowsGQ));   // row blocks of this workgroup
+    const int64_t i0 = (int64_t)block * blocks_per_wg * R;
+    const int nblk = min(blocks_per_wg, (int)((m - i0 + R - 1) / R));   // row blocks of this workgroup
 
+    ChunkStager16<RP> stg;
+    stg.fetch(G, i0, m, n, 0, tid, wave);                             // in flight while the plan's header arrives
     PlanHeaderPtr H = as_const<PlanHeader>(plan);
     if (!plan_matches(H, m, n, r, d)) {                               // not a plan for this problem
         poison_s(S, r, block, nblocks, tid, kThreadsGQ);
@@ -367,21 +403,20 @@ __global__ __launch_bounds__(kThreadsGQ) void k_compress_gq16(const CompressGrou
         const int64_t total = (int64_t)r * r;
         for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
     }
-    if (tid < kPlanes) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    ChunkStager16 stg;
-    stg.fetch(G, i0, m, n, 0, tid);
-    if (H->nslots == 1)      gq16_one_slot<D>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
-    else if (H->nslots == 2) gq16_multi_slot<D, 2>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
-    else                     gq16_multi_slot<D, kMaxSlots>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    if (tid < 2 * RP) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (H->nslots == 1)      gq16_one_slot<D, RP>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else if (H->nslots == 2) gq16_multi_slot<D, 2, RP>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else                     gq16_multi_slot<D, kMaxSlots, RP>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
 }
 
 
 template <typename D>
 static hipError_t launch_gq16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st) {
-    constexpr size_t lds = (size_t)kPlanes * kPlaneStride;   // two chunk buffers of two 8-row planes
+    constexpr int RP = kRowsGQ16 / 8;
+    constexpr size_t lds = (size_t)2 * RP * kPlaneStride;    // two chunk buffers of RP 8-row planes
     hipError_t e;
-    if ((e = allow_dynamic_lds<k_compress_gq16<D>>(lds)) != hipSuccess) return e;
-    hipLaunchKernelGGL(k_compress_gq16<D>, dim3((unsigned)g.first_gq[g.count]), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d, blocks_per_wg);
+    if ((e = allow_dynamic_lds<k_compress_gq16<D, RP>>(lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL((k_compress_gq16<D, RP>), dim3((unsigned)g.first_gq[g.count]), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d, blocks_per_wg);
     return hipGetLastError();
 }
 
