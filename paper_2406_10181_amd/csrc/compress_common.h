@@ -91,7 +91,7 @@ __device__ __forceinline__ void swap_owner(uint8_t* area, float (&acc)[R], uint3
 
 // Launchers of kernel A (first_gq filled in): fp16 / bf16 with rows of whole 8-element groups, and the rest.
 // rows of G per row block of the 16-bit kernel (a workgroup holds that many rows of two chunks in LDS)
-constexpr int kRowsGQ16 = 16;
+constexpr int kRowsGQ16 = 8;
 hipError_t launch_gq16_bf16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
 hipError_t launch_gq16_f16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
 hipError_t launch_gq_staged32(const CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);

@@ -45,12 +45,15 @@ template <> struct ChunkStager16<2> {
         const int plane = wave / (kWavesGQ / 2), oct = tid % (kChunk / 8);
         const uint32_t col0 = (uint32_t)c * kChunk + (uint32_t)oct * 8;
         const uint32_t byte0 = (col0 < (uint32_t)n ? col0 : 0u) * (uint32_t)sizeof(E);
+        const int64_t first = i0 + plane * 8;                        // may lie past the matrix (second plane of a ragged block)
+        const int64_t top = first < m ? first : (int64_t)m - 1;
+        const int last = (int)(m - 1 - top < 7 ? m - 1 - top : 7);   // rows of this plane inside the matrix, less one
+        const char* base = reinterpret_cast<const char*>(G + top * (int64_t)n) + byte0;
+        const uint64_t stride = (uint64_t)n * sizeof(E);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            const int64_t row = i0 + plane * 8 + t;
-            const int64_t rowc = row < m ? row : (int64_t)m - 1;
-            const char* rowp = reinterpret_cast<const char*>(G + rowc * (int64_t)n);
-            pre[t] = stream_load(reinterpret_cast<const u32x4*>(rowp + byte0));
+            pre[t] = stream_load(reinterpret_cast<const u32x4*>(base));
+            base += t < last ? stride : 0;
         }
     }
     // transposes the 8x8 block and writes its 8 units (column q: rows 0..7) into buffer `buf`
@@ -75,12 +78,13 @@ template <> struct ChunkStager16<1> {
     __device__ __forceinline__ void fetch(const E* __restrict__ G, int64_t i0, int m, int n, int c, int tid, int) {
         const uint32_t col0 = (uint32_t)c * kChunk + (uint32_t)tid * 4;
         const uint32_t byte0 = (col0 < (uint32_t)n ? col0 : 0u) * (uint32_t)sizeof(E);   // n % 8 == 0
+        const int last = (int)(m - 1 - i0 < 7 ? m - 1 - i0 : 7);     // rows of the block inside the matrix, less one (i0 < m)
+        const char* base = reinterpret_cast<const char*>(G + i0 * (int64_t)n) + byte0;
+        const uint64_t stride = (uint64_t)n * sizeof(E);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            const int64_t row = i0 + t;
-            const int64_t rowc = row < m ? row : (int64_t)m - 1;
-            const char* rowp = reinterpret_cast<const char*>(G + rowc * (int64_t)n);
-            pre[t] = stream_load(reinterpret_cast<const u32x2*>(rowp + byte0));
+            pre[t] = stream_load(reinterpret_cast<const u32x2*>(base));
+            base += t < last ? stride : 0;
         }
     }
     // transposes the 8x4 block and writes its 4 units (column q: rows 0..7) into buffer `buf`
