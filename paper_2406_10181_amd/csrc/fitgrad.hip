@@ -97,35 +97,47 @@ __global__ __launch_bounds__(256) void k_grad_left(const float* __restrict__ T, 
     }
 }
 
-// gQ[j][k] = sum_k' Q_val[j][k'] M2[Q_idx[j][k']][b] + sum_a Y[a][j] D[a][b],  b = Q_idx[j][k]: one thread per
-// column j (the reads of Y are then contiguous), eight entries of the row at a time.
-__global__ __launch_bounds__(256) void k_grad_right(const float* __restrict__ Y, const float* __restrict__ Dm, const float* __restrict__ M2,
-                                                    const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
-                                                    int n, int r, int d, float* __restrict__ gQ) {
-    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (j >= n) return;
+// gQ[j][k] = sum_k' Q_val[j][k'] M2[Q_idx[j][k']][b] + sum_a Y[a][j] D[a][b],  b = Q_idx[j][k]: a workgroup takes
+// 16 columns j (the reads of Y are then contiguous) and cuts the sum over a into 16 interleaved slices, one per
+// group of 16 threads; the slices' sums meet in LDS and are added in slice order.  Eight entries of a row at a time.
+constexpr int kGradCols = 16, kGradSlices = 16;
+__global__ __launch_bounds__(kGradCols * kGradSlices) void k_grad_right(const float* __restrict__ Y, const float* __restrict__ Dm, const float* __restrict__ M2,
+                                                                      const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
+                                                                      int n, int r, int d, float* __restrict__ gQ) {
+    __shared__ float part[kGradSlices][kGradCols][8];
+    const int jl = threadIdx.x % kGradCols, sl = threadIdx.x / kGradCols;
+    const int64_t j = (int64_t)blockIdx.x * kGradCols + jl;
+    const bool live = j < n;
+    const int64_t jc = live ? j : (int64_t)n - 1;
     for (int k0 = 0; k0 < d; k0 += 8) {
         int b[8];
         float acc[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            b[q] = k0 + q < d ? Q_idx[j * d + k0 + q] : 0;
+            b[q] = k0 + q < d ? Q_idx[jc * d + k0 + q] : 0;
             acc[q] = 0.0f;
         }
-        for (int a = 0; a < r; ++a) {
-            const float y = Y[(int64_t)a * n + j];
+        for (int a = sl; a < r; a += kGradSlices) {
+            const float y = Y[(int64_t)a * n + jc];
             const float* Da = Dm + (int64_t)a * r;
 #pragma unroll
             for (int q = 0; q < 8; ++q) acc[q] = fmaf(y, Da[b[q]], acc[q]);
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            if (k0 + q < d) {
-                float g = acc[q];
-                for (int k2 = 0; k2 < d; ++k2) g = fmaf(Q_val[j * d + k2], M2[(int64_t)Q_idx[j * d + k2] * r + b[q]], g);
-                gQ[j * d + k0 + q] = g;
+        for (int q = 0; q < 8; ++q) part[sl][jl][q] = acc[q];
+        __syncthreads();
+        if (sl == 0 && live) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (k0 + q < d) {
+                    float g = 0.0f;
+                    for (int t = 0; t < kGradSlices; ++t) g += part[t][jl][q];
+                    for (int k2 = 0; k2 < d; ++k2) g = fmaf(Q_val[j * d + k2], M2[(int64_t)Q_idx[j * d + k2] * r + b[q]], g);
+                    gQ[j * d + k0 + q] = g;
+                }
             }
         }
+        __syncthreads();
     }
 }
 
@@ -186,7 +198,7 @@ hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_i
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_grad_left, dim3((unsigned)((m + 3) / 4)), dim3(256), 0, st, T, Dm, M1, P_idx, P_val, (int)m, (int)r, (int)d, gP);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(k_grad_right, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, Y, Dm, M2, Q_idx, Q_val, (int)n, (int)r, (int)d, gQ);
+    hipLaunchKernelGGL(k_grad_right, dim3((unsigned)((n + kGradCols - 1) / kGradCols)), dim3(kGradCols * kGradSlices), 0, st, Y, Dm, M2, Q_idx, Q_val, (int)n, (int)r, (int)d, gQ);
     return hipGetLastError();
 }
 
