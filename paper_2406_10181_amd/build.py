@@ -73,5 +73,10 @@ def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, define
     return out
 
 
+PHASE_LIB = os.path.join(PKG, "liblsp_hip_phase.so")   # development build with per-phase cycle counters in kernel A (phase_timing.py)
+
 if __name__ == "__main__":
-    build(save_temps="--save-temps" in sys.argv, incremental="--incremental" in sys.argv)
+    if "--phase-timing" in sys.argv:
+        build(out=PHASE_LIB, defines=("LSP_PHASE_TIMING",), incremental="--incremental" in sys.argv)
+    else:
+        build(save_temps="--save-temps" in sys.argv, incremental="--incremental" in sys.argv)

@@ -89,6 +89,39 @@ __device__ __forceinline__ void swap_owner(uint8_t* area, float (&acc)[R], uint3
 }
 
 
+// Development aid, compiled in only with -DLSP_PHASE_TIMING (build.py --phase-timing builds such a library beside the
+// normal one; phase_timing.py reads it out): the one-column walker of the 16-bit kernel A adds up, per wave, the core
+// clock cycles it spends in each phase of a chunk and leaves them in a device array.
+#ifdef LSP_PHASE_TIMING
+constexpr int kPhaseSlots = 16;                               // per wave: 12 phase sums, cycles, start, wall clock, spare
+constexpr int kPhaseMaxWG = 8192;
+static __device__ unsigned long long g_phase[kPhaseMaxWG * kWavesGQ * kPhaseSlots];   // one copy per translation unit
+struct PhaseClock {
+    unsigned long long sum[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long last, begin, wall;
+    __device__ __forceinline__ PhaseClock() { last = begin = clock64(); wall = wall_clock64(); }
+    __device__ __forceinline__ void tick(int phase) { const unsigned long long now = clock64(); sum[phase] += now - last; last = now; }
+    __device__ __forceinline__ void count(int slot, unsigned long long k) { sum[slot] += k; }
+    __device__ __forceinline__ void store(int wave, int lane) {
+        if (lane != 0 || blockIdx.x >= kPhaseMaxWG) return;
+        unsigned long long* o = g_phase + ((size_t)blockIdx.x * kWavesGQ + wave) * kPhaseSlots;
+        for (int k = 0; k < 12; ++k) o[k] = sum[k];
+        o[12] = clock64() - begin; o[13] = begin; o[14] = wall_clock64() - wall; o[15] = wall;
+    }
+};
+#else
+struct PhaseClock {
+    __device__ __forceinline__ void tick(int) {}
+    __device__ __forceinline__ void count(int, unsigned long long) {}
+    __device__ __forceinline__ void store(int, int) {}
+};
+#endif
+// phases of a chunk in gq16_one_slot: staging of the block's first chunk, top of the chunk loop, fetch of the next
+// chunk and segment length, the batches before the staging, staging, the remaining batches, exchange of the sums;
+// slots 5, 7, 8 count batches
+enum : int { kPhFirstStage = 0, kPhTop = 1, kPhFetch = 2, kPhFirst = 3, kPhStage = 4, kPhBatches = 5, kPhRest = 6, kPhNFirst = 7,
+             kPhNRest = 8, kPhSwap = 9 };
+
 // Launchers of kernel A (first_gq filled in): fp16 / bf16 with rows of whole 8-element groups, and the rest.
 // rows of G per row block of the 16-bit kernel (a workgroup holds that many rows of two chunks in LDS)
 constexpr int kRowsGQ16 = 8;

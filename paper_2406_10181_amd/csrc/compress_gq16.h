@@ -178,8 +178,10 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         rp += (size_t)kBatchLoads * kWave;
     };
 
+    PhaseClock clk;                                                   // empty unless built for phase timing
     stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
     __syncthreads();
+    clk.tick(kPhFirstStage);
     int rot = 0, c = 0, blk = 0;
     const int units = nblk * nchunks;                                 // (row block, chunk) pairs, in order
     for (int u = 0; u < units; ++u) {
@@ -201,6 +203,7 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         static_assert(kPrefetch == 4, "the rotation above is written for four slots");
         const bool last_chunk = c + 1 == nchunks;
         const uint32_t next = last_chunk ? (uint32_t)tid : (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ];
+        clk.tick(kPhTop);
         if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
             stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * R, m, n, last_chunk ? 0 : c + 1, tid, wave);
         buf = smem + (u & 1) * (RP * kPlaneStride);
@@ -211,10 +214,13 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         const bool stage_early = more && !(last_chunk && shared);
         const int nb = (int)(seg[c * kWavesGQ] / kSegBatch);
         const int groups = nb / kPrefetch, before = groups < 2 ? groups : 2;
+        clk.tick(kPhFetch);
         for (int g = before; g > 0; --g) {
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
         }
+        clk.tick(kPhFirst);
         if (stage_early) stg.stage(smem, (u + 1) & 1, tid);
+        clk.tick(kPhStage);
         for (int g = groups - before; g > 0; --g) {
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
         }
@@ -222,10 +228,13 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         if (rot > 0) step(ring[0]);
         if (rot > 1) step(ring[1]);
         if (rot > 2) step(ring[2]);
+        clk.tick(kPhRest);
+        clk.count(kPhNFirst, (unsigned)(4 * before)); clk.count(kPhNRest, (unsigned)(nb - 4 * before)); clk.count(kPhBatches, (unsigned)nb);
         // The sums move to the lanes that walk the columns in the next chunk; after the last chunk
         // of a block they go home (thread t: virtual column t) and out to T.
         if (last_chunk && more) { ring_restart(); rot = 0; }          // the stream starts over; in flight during the stores
         swap_owner<R>(smem + (u & 1) * (RP * kPlaneStride), acc[0], walked, next);
+        clk.tick(kPhSwap);
         if (last_chunk) {
             const int64_t ib = i0 + (int64_t)blk * R;
             if (shared) {
@@ -251,6 +260,7 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
             walked = next;
         }
     }
+    clk.store(wave, lane);
 }
 
 // Several columns per lane (r > 512, or columns used so unevenly that they were split), 16-bit
