@@ -182,27 +182,17 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
     stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
     __syncthreads();
     clk.tick(kPhFirstStage);
+    // Batch k of a chunk sits in ring slot (rot + k) % kPrefetch, where rot is what the chunks before left over:
+    // the walk enters the unrolled slot sequence at slot rot instead of moving the ring's registers.
+    static_assert(kPrefetch == 4, "the slot walk below is written for four slots");
     int rot = 0, c = 0, blk = 0;
     const int units = nblk * nchunks;                                 // (row block, chunk) pairs, in order
+    int nb_next = (int)(seg[0] / kSegBatch);                          // batches of this wave in the coming chunk
     for (int u = 0; u < units; ++u) {
-        if (rot != 0) {                                               // undo the slot rotation left by the previous chunk
-            u32x4 t[kPrefetch][kBatchLoads];
-#pragma unroll
-            for (int k = 0; k < kPrefetch; ++k)
-#pragma unroll
-                for (int q = 0; q < kBatchLoads; ++q) {
-                    t[k][q] = ring[(k + 1) % kPrefetch][q];
-                    if (rot == 2) t[k][q] = ring[(k + 2) % kPrefetch][q];
-                    if (rot == 3) t[k][q] = ring[(k + 3) % kPrefetch][q];
-                }
-#pragma unroll
-            for (int k = 0; k < kPrefetch; ++k)
-#pragma unroll
-                for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = t[k][q];
-        }
-        static_assert(kPrefetch == 4, "the rotation above is written for four slots");
         const bool last_chunk = c + 1 == nchunks;
         const uint32_t next = last_chunk ? (uint32_t)tid : (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ];
+        const int nb = nb_next;
+        nb_next = (int)(seg[(last_chunk ? 0 : c + 1) * kWavesGQ] / kSegBatch);   // arrives while this chunk is walked
         clk.tick(kPhTop);
         if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
             stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * R, m, n, last_chunk ? 0 : c + 1, tid, wave);
@@ -212,9 +202,15 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         // work rather than at its end, where every wave would wait for it; only a block's last
         // chunk with shared columns stages later, behind the merge that uses the same LDS.
         const bool stage_early = more && !(last_chunk && shared);
-        const int nb = (int)(seg[c * kWavesGQ] / kSegBatch);
-        const int groups = nb / kPrefetch, before = groups < 2 ? groups : 2;
+        int left = nb;
         clk.tick(kPhFetch);
+        switch (rot) {                                                // up to the ring's slot 0
+            case 1: if (left > 0) { step(ring[1]); --left; } [[fallthrough]];
+            case 2: if (left > 0) { step(ring[2]); --left; } [[fallthrough]];
+            case 3: if (left > 0) { step(ring[3]); --left; } [[fallthrough]];
+            default: break;
+        }
+        const int groups = left / kPrefetch, before = groups < 2 ? groups : 2;
         for (int g = before; g > 0; --g) {
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
         }
@@ -224,10 +220,11 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         for (int g = groups - before; g > 0; --g) {
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
         }
-        rot = nb % kPrefetch;
-        if (rot > 0) step(ring[0]);
-        if (rot > 1) step(ring[1]);
-        if (rot > 2) step(ring[2]);
+        left -= groups * kPrefetch;
+        if (left > 0) step(ring[0]);
+        if (left > 1) step(ring[1]);
+        if (left > 2) step(ring[2]);
+        rot = (rot + nb) % kPrefetch;
         clk.tick(kPhRest);
         clk.count(kPhNFirst, (unsigned)(4 * before)); clk.count(kPhNRest, (unsigned)(nb - 4 * before)); clk.count(kPhBatches, (unsigned)nb);
         // The sums move to the lanes that walk the columns in the next chunk; after the last chunk
