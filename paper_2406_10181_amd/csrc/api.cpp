@@ -34,7 +34,7 @@ int check_shape(int64_t m, int64_t n, int32_t r, int32_t d) {
 
 int check_dtype(lsp_dtype t) { return (t == LSP_F32 || t == LSP_F16 || t == LSP_BF16) ? LSP_OK : LSP_ERR_DTYPE; }
 
-size_t t_bytes(int64_t m, int32_t r) { return lsp::t_region_bytes(m, r); }
+size_t t_bytes(int64_t m, int32_t r) { return lsp::align_up((size_t)m * (size_t)r * sizeof(float), 256); }
 
 }  // namespace
 

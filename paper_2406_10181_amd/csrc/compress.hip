@@ -175,23 +175,29 @@ bool compress_group_uniform(const CompressGroup& g) {
     return true;
 }
 
+// Row blocks per workgroup of kernel A: several on big grids (grouped calls) of the 16-bit kernel
+static int gq_blocks_per_wg(const CompressGroup& g, lsp_dtype dtype) {
+    if (dtype == LSP_F32 || g.n[0] % 8 != 0) return 1;
+    int64_t rows = 0;
+    for (int p = 0; p < g.count; ++p) rows += g.m[p];
+    return rows >= 16384 ? 2 : 1;
+}
+
 // Rows of a row block of kernel A: the 16-bit kernel and the 32-bit-staged kernel differ
 static int gq_block_rows(const CompressGroup& g, lsp_dtype dtype) {
     return (dtype != LSP_F32 && g.n[0] % 8 == 0) ? kRowsGQ16 : kRowsGQ;
 }
 
-static hipError_t launch_gq(const CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st) {
-    if (dtype != LSP_F32 && g.n[0] % 8 == 0) {
-        uint32_t* counter = t_region_counter(g.T[0], g.m[0], r);      // every T of the group has one; the first serves the launch
-        return dtype == LSP_F16 ? launch_gq16_f16(g, r, d, counter, st) : launch_gq16_bf16(g, r, d, counter, st);
-    }
+static hipError_t launch_gq(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, lsp_dtype dtype, hipStream_t st) {
+    if (dtype != LSP_F32 && g.n[0] % 8 == 0)
+        return dtype == LSP_F16 ? launch_gq16_f16(g, r, d, blocks_per_wg, st) : launch_gq16_bf16(g, r, d, blocks_per_wg, st);
     return launch_gq_staged32(g, r, d, dtype, st);
 }
 
-// Row blocks are taken up in group order (by the hardware as CUs fall free, or by the workgroups of
-// the 16-bit kernel A from their counter), so the order of the problems inside a group is the order of a
-// greedy list schedule: the problems whose row blocks take longest (widest matrices: work per row block
-// grows with n) go first, and the short ones fill in behind them.
+// The hardware hands the workgroups of a launch to the CUs in index order as CUs fall free, so the
+// order of the problems inside a group is the order of a greedy list schedule: the problems whose
+// workgroups run longest (widest matrices: work per row block grows with n) go first, and the
+// short ones fill in behind them.
 static void longest_first(CompressGroup& g) {
     for (int a = 1; a < g.count; ++a)
         for (int b = a; b > 0 && g.n[b] > g.n[b - 1]; --b) {
@@ -204,14 +210,14 @@ hipError_t launch_compress_planned(CompressGroup& g, int32_t r, int32_t d, lsp_d
     const int nstripes = (r + kStripeQuads * 4 - 1) / (kStripeQuads * 4);
     const bool striped = (r % 4) == 0;
     longest_first(g);
-    const int rows = gq_block_rows(g, dtype);
+    const int bpw = gq_blocks_per_wg(g, dtype), rows = gq_block_rows(g, dtype);
     g.first_gq[0] = g.first_pt[0] = 0;
     for (int p = 0; p < g.count; ++p) {
-        g.first_gq[p + 1] = g.first_gq[p] + (int32_t)((g.m[p] + rows - 1) / rows);
+        g.first_gq[p + 1] = g.first_gq[p] + (int32_t)(((g.m[p] + rows - 1) / rows + bpw - 1) / bpw);
         const int32_t items = (int32_t)plan_max_items(g.m[p], r, d);
         g.first_pt[p + 1] = g.first_pt[p] + (striped ? ((items + 3) / 4) * 8 : items * nstripes);
     }
-    hipError_t e = launch_gq(g, r, d, dtype, st);
+    hipError_t e = launch_gq(g, r, d, bpw, dtype, st);
     if (e != hipSuccess) return e;
     const unsigned blocks = (unsigned)g.first_pt[g.count];
     if (striped) {

@@ -101,7 +101,6 @@ struct PhaseClock {
     unsigned long long last, begin, wall;
     __device__ __forceinline__ PhaseClock() { last = begin = clock64(); wall = wall_clock64(); }
     __device__ __forceinline__ void tick(int phase) { const unsigned long long now = clock64(); sum[phase] += now - last; last = now; }
-    __device__ __forceinline__ void resume() { last = clock64(); }     // what passed since the last tick belongs to no phase
     __device__ __forceinline__ void count(int slot, unsigned long long k) { sum[slot] += k; }
     __device__ __forceinline__ void store(int wave, int lane) {
         if (lane != 0 || blockIdx.x >= kPhaseMaxWG) return;
@@ -113,7 +112,6 @@ struct PhaseClock {
 #else
 struct PhaseClock {
     __device__ __forceinline__ void tick(int) {}
-    __device__ __forceinline__ void resume() {}
     __device__ __forceinline__ void count(int, unsigned long long) {}
     __device__ __forceinline__ void store(int, int) {}
 };
@@ -127,8 +125,8 @@ enum : int { kPhFirstStage = 0, kPhTop = 1, kPhFetch = 2, kPhFirst = 3, kPhStage
 // Launchers of kernel A (first_gq filled in): fp16 / bf16 with rows of whole 8-element groups, and the rest.
 // rows of G per row block of the 16-bit kernel (a workgroup holds that many rows of two chunks in LDS)
 constexpr int kRowsGQ16 = 8;
-hipError_t launch_gq16_bf16(const CompressGroup& g, int32_t r, int32_t d, uint32_t* counter, hipStream_t st);
-hipError_t launch_gq16_f16(const CompressGroup& g, int32_t r, int32_t d, uint32_t* counter, hipStream_t st);
+hipError_t launch_gq16_bf16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
+hipError_t launch_gq16_f16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st);
 hipError_t launch_gq_staged32(const CompressGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
 
 }  // namespace lsp

@@ -2,8 +2,6 @@
 // code; compress_gq16_bf16.hip and compress_gq16_f16.hip instantiate it.  See compress.hip for the path as a whole.
 #pragma once
 
-#include <cstdlib>
-
 #include "compress_common.h"
 
 namespace lsp {
@@ -128,130 +126,37 @@ __device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][RP
     }
 }
 
-// The launch has a fixed number of workgroups (two per CU) that stay until the group's work is done and take
-// the row blocks of the group, one at a time and in group order, from a counter in device memory: a workgroup
-// started anew pays for the launch, the plan header, its first chunk of G and the first plan rows with nothing
-// to overlap them, a workgroup that goes on to its next row block overlaps all of that with the block before.
-// (A fixed share of the blocks per workgroup instead of the counter leaves the CUs idle at the end: the two
-// workgroups of a CU do not advance at the same speed.)  A group with no more row blocks than that is launched
-// with one workgroup per row block and no counter.
-//
-// Per problem of the group, in LDS: what the kernel needs of it.  Thread 0 fills the table from the by-value
-// group with compile-time indices; a problem is then picked with a run-time index from LDS (indexing the
-// by-value group that way would make the compiler copy it to scratch memory, see group_pick).
-struct ProblemTable {
-    const void* G[kMaxGroup]; const uint8_t* plan[kMaxGroup]; float* T[kMaxGroup]; float* S[kMaxGroup];
-    int32_t m[kMaxGroup], n[kMaxGroup], first[kMaxGroup + 1];         // first: row blocks of the group before this problem
-    int32_t ticket[2];                                                // row blocks drawn ahead (see Tickets)
-};
-__device__ __forceinline__ void fill_table(const CompressGroup& g, ProblemTable* out) {
-#pragma unroll
-    for (int p = 0; p < kMaxGroup; ++p) {
-        if (p < g.count) {
-            out->G[p] = g.G[p]; out->plan[p] = g.plan[p]; out->T[p] = g.T[p]; out->S[p] = g.S[p];
-            out->m[p] = g.m[p]; out->n[p] = g.n[p];
-        }
-        out->first[p] = g.first_gq[p < g.count ? p : g.count];
-    }
-    out->first[kMaxGroup] = g.first_gq[g.count];
-}
-template <typename X> __device__ __forceinline__ X* uniform_ptr(X* const* slot) {   // a pointer every lane reads from the same LDS slot
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(slot);
-    const uint64_t v = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)w[0]) | ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)w[1]) << 32);
-    // the table holds device-memory addresses: saying so keeps the loads and stores through them on the vector-memory
-    // path of global memory (a pointer of unknown origin would be accessed with flat instructions, which tie the
-    // LDS and the vector-memory counters together)
-    typedef X __attribute__((address_space(1))) GX;
-    return (X*)reinterpret_cast<GX*>(v);
-}
-__device__ __forceinline__ int uniform_int(const int32_t* slot) { return __builtin_amdgcn_readfirstlane(*slot); }
-__device__ __forceinline__ int problem_of(const ProblemTable* t, int unit) {   // unit < first[kMaxGroup]
-    int p = 0;
-    while (unit >= uniform_int(&t->first[p + 1])) ++p;
-    return p;
-}
-
-// The row blocks a workgroup works on: `cur` now, `nxt` after it (both indices into the group's row blocks; at
-// or past `total`: none).  The one after `nxt` is drawn from the counter when a block is begun and read when
-// it ends, so that the counter's latency stays hidden and the block after the current one is always known
-// early enough to fetch its first chunk ahead.  One lane of the last wave draws (that wave walks short lists
-// and has time to wait for the counter); the value passes through LDS, two slots in turn, with the barriers of
-// the block in between.
-struct Tickets {
-    uint32_t* counter;                                                // null: one row block per workgroup, nothing to draw
-    int32_t*  slot;
-    int       cur, nxt, total, drawn;
-    __device__ __forceinline__ void draw(int tid) {
-        if (counter && tid == kThreadsGQ - kWave) slot[drawn & 1] = (int32_t)atomicAdd(counter, 1u);
-    }
-    __device__ __forceinline__ void advance() {                       // after a barrier that follows draw()
-        cur = nxt;
-        nxt = counter ? __builtin_amdgcn_readfirstlane(slot[drawn & 1]) : total;
-        ++drawn;
-    }
-};
-
-// Fetches the first chunk of the row block a workgroup goes on to when that block belongs to another problem.
-template <typename E, int RP>
-__device__ __forceinline__ void fetch_ahead(ChunkStager16<RP>& stg, const ProblemTable* tab, int unit, int tid, int wave) {
-    const int q = problem_of(tab, unit);
-    stg.fetch(static_cast<const E*>(uniform_ptr(&tab->G[q])), (int64_t)(unit - uniform_int(&tab->first[q])) * (8 * RP),
-              uniform_int(&tab->m[q]), uniform_int(&tab->n[q]), 0, tid, wave);
-}
-
-// When some row of P^T is cut into pieces, kernel B adds into S, which therefore starts at zero; the row blocks
-// of a problem share that work (block b of nblocks takes every nblocks-th run of 512 elements).
-__device__ __forceinline__ void zero_share_of_s(float* __restrict__ S, int r, int block, int nblocks, int tid) {
-    const int64_t total = (int64_t)r * r;
-    for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
-}
-
-// One workgroup walks row blocks of 8 RP rows, beginning in problem p (whose plan has one column per lane), for
-// as long as its tickets name blocks of one-column plans: the first chunk of the next block is fetched and
-// staged while the last chunk of the current one is consumed, the plan ring is refilled for it, and the
-// stores of T go out under the next block's work, so that the set-up and the tail of a block cost nothing but
-// for the first and the last one -- also when the next block belongs to the next problem of the group.  Chunk 0
-// of the first block has been fetched by the caller; on return chunk 0 of the block tk.cur (if any) has been.
+// One workgroup walks `nblk` consecutive blocks of 16 rows (several when the grid is big: the first
+// chunk of the next block is fetched and staged while the last chunk of the current one is
+// consumed, and the stores of T go out under the next block's work, so that the set-up and the
+// tail of a block cost nothing but for the first and the last one).
 template <typename D, int RP>
-__device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* smem, const ProblemTable* tab, int p, int r, int d,
-                                              int tid, int lane, int wave, Tickets& tk, PhaseClock& clk) {
-    typedef typename D::elem E;
+__device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
+                                              const uint8_t* __restrict__ plan, PlanHeaderPtr H,
+                                              float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
+                                              int tid, int lane, int wave) {
     constexpr int R = 8 * RP;                                         // rows of a row block
-    // the problem the walk is in
-    const E* __restrict__ G; const uint8_t* __restrict__ plan; PlanHeaderPtr H; float* __restrict__ T; float* __restrict__ S;
-    int m, n, first_p, end_p, nchunks; bool shared, split;
-    const LSP_CONST_AS uint32_t* seg; const u32x4* rp0; const uint16_t* __restrict__ perm; uint32_t mycol, first;
-    auto stream_start = [&](const uint8_t* pl, PlanHeaderPtr Hq) {
-        return reinterpret_cast<const u32x4*>(pl + Hq->off_q_rows) + (size_t)(Hq->q_stream_row[wave] >> 1) * kWave + lane;
-    };
-    auto enter = [&](int q) {                                         // the plan of problem q has been checked
-        G = static_cast<const E*>(uniform_ptr(&tab->G[q])); plan = uniform_ptr(&tab->plan[q]);
-        T = uniform_ptr(&tab->T[q]); S = uniform_ptr(&tab->S[q]);
-        m = uniform_int(&tab->m[q]); n = uniform_int(&tab->n[q]);
-        first_p = uniform_int(&tab->first[q]); end_p = uniform_int(&tab->first[q + 1]);
-        H = as_const<PlanHeader>(plan);
-        nchunks = H->nchunks; shared = H->q_any_shared != 0; split = H->p_any_split != 0;
-        seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
-        rp0 = stream_start(plan, H);
-        perm = reinterpret_cast<const uint16_t*>(plan + H->off_q_perm) + tid;
-        mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
-        first = perm[0];
-    };
-    enter(p);
+    const int nchunks = H->nchunks;
+    const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
+    const u32x4* rp0 = reinterpret_cast<const u32x4*>(plan + H->off_q_rows) + (size_t)(H->q_stream_row[wave] >> 1) * kWave + lane;
     const u32x4* rp = rp0;
+    const uint32_t mycol = as_const<uint16_t>(plan + H->off_q_vcol)[tid];
+    const bool shared = H->q_any_shared != 0;
+    const uint16_t* __restrict__ perm = reinterpret_cast<const uint16_t*>(plan + H->off_q_perm) + tid;
+    const uint32_t first = perm[0];
     uint32_t walked = first;                                          // virtual column whose list this thread walks
 
     // ring of kPrefetch batches of plan rows in fixed register slots (see gq_one_slot)
     u32x4 ring[kPrefetch][kBatchLoads];
-    auto ring_restart = [&](const u32x4* from) {
-        rp = from;
+    auto ring_restart = [&]() {
+        rp = rp0;
 #pragma unroll
         for (int k = 0; k < kPrefetch; ++k)
 #pragma unroll
             for (int q = 0; q < kBatchLoads; ++q) ring[k][q] = rp[(size_t)(k * kBatchLoads + q) * kWave];
         rp += (size_t)kPrefetch * kBatchLoads * kWave;
     };
-    ring_restart(rp0);
+    ring_restart();
 
     float acc[1][R];
 #pragma unroll
@@ -273,41 +178,30 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         rp += (size_t)kBatchLoads * kWave;
     };
 
-    clk.resume();
+    PhaseClock clk;                                                   // empty unless built for phase timing
     stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
     __syncthreads();
     clk.tick(kPhFirstStage);
     // Batch k of a chunk sits in ring slot (rot + k) % kPrefetch, where rot is what the chunks before left over:
     // the walk enters the unrolled slot sequence at slot rot instead of moving the ring's registers.
     static_assert(kPrefetch == 4, "the slot walk below is written for four slots");
-    int rot = 0, c = 0;
-    int64_t ib = (int64_t)(tk.cur - first_p) * R;                     // first row of the block
+    int rot = 0, c = 0, blk = 0;
+    const int units = nblk * nchunks;                                 // (row block, chunk) pairs, in order
     int nb_next = (int)(seg[0] / kSegBatch);                          // batches of this wave in the coming chunk
-    for (int u = 0; ; ++u) {                                          // (row block, chunk) pairs, in order
-        if (c == 0) {
-            tk.draw(tid);
-            if (split) zero_share_of_s(S, r, (int)(ib / R), end_p - first_p, tid);
-        }
+    for (int u = 0; u < units; ++u) {
         const bool last_chunk = c + 1 == nchunks;
-        const bool more_here = tk.nxt < end_p;                        // the block after this one belongs to this problem too
-        const bool leaving = last_chunk && !more_here && tk.nxt < tk.total;   // ... or to the next problem
         const uint32_t next = last_chunk ? (uint32_t)tid : (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ];
         const int nb = nb_next;
-        if (!last_chunk || more_here)
-            nb_next = (int)(seg[(last_chunk ? 0 : c + 1) * kWavesGQ] / kSegBatch);   // arrives while this chunk is walked
+        nb_next = (int)(seg[(last_chunk ? 0 : c + 1) * kWavesGQ] / kSegBatch);   // arrives while this chunk is walked
         clk.tick(kPhTop);
-        int q = p; PlanHeaderPtr Hq = H;                              // the problem of the next block
-        if (!last_chunk) {                                            // the next chunk lands while this one is consumed
-            stg.fetch(G, ib, m, n, c + 1, tid, wave);
-        } else if (more_here) {
-            stg.fetch(G, (int64_t)(tk.nxt - first_p) * R, m, n, 0, tid, wave);
-        } else if (leaving) {
-            q = problem_of(tab, tk.nxt);
-            stg.fetch(static_cast<const E*>(uniform_ptr(&tab->G[q])), (int64_t)(tk.nxt - uniform_int(&tab->first[q])) * R,
-                      uniform_int(&tab->m[q]), uniform_int(&tab->n[q]), 0, tid, wave);
-            Hq = as_const<PlanHeader>(uniform_ptr(&tab->plan[q]));
-        }
+        if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * R, m, n, last_chunk ? 0 : c + 1, tid, wave);
         buf = smem + (u & 1) * (RP * kPlaneStride);
+        const bool more = u + 1 < units;
+        // The next chunk is staged (into the buffer nobody reads now) in the middle of this one's
+        // work rather than at its end, where every wave would wait for it; only a block's last
+        // chunk with shared columns stages later, behind the merge that uses the same LDS.
+        const bool stage_early = more && !(last_chunk && shared);
         int left = nb;
         clk.tick(kPhFetch);
         switch (rot) {                                                // up to the ring's slot 0
@@ -321,13 +215,6 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
         }
         clk.tick(kPhFirst);
-        // does the walk go on into the next problem?  (its header has had the first batches to arrive)
-        const bool chain = leaving && plan_matches(Hq, uniform_int(&tab->m[q]), uniform_int(&tab->n[q]), r, d) && Hq->nslots == 1;
-        const bool more = !last_chunk || more_here || chain;
-        // The next chunk is staged (into the buffer nobody reads now) in the middle of this one's
-        // work rather than at its end, where every wave would wait for it; only a block's last
-        // chunk with shared columns stages later, behind the merge that uses the same LDS.
-        const bool stage_early = more && !(last_chunk && shared);
         if (stage_early) stg.stage(smem, (u + 1) & 1, tid);
         clk.tick(kPhStage);
         for (int g = groups - before; g > 0; --g) {
@@ -342,13 +229,11 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         clk.count(kPhNFirst, (unsigned)(4 * before)); clk.count(kPhNRest, (unsigned)(nb - 4 * before)); clk.count(kPhBatches, (unsigned)nb);
         // The sums move to the lanes that walk the columns in the next chunk; after the last chunk
         // of a block they go home (thread t: virtual column t) and out to T.
-        if (last_chunk && more) {                                     // the stream starts over (that of the next problem, maybe); in flight during the stores
-            ring_restart(chain ? stream_start(uniform_ptr(&tab->plan[q]), Hq) : rp0);
-            rot = 0;
-        }
+        if (last_chunk && more) { ring_restart(); rot = 0; }          // the stream starts over; in flight during the stores
         swap_owner<R>(smem + (u & 1) * (RP * kPlaneStride), acc[0], walked, next);
         clk.tick(kPhSwap);
         if (last_chunk) {
+            const int64_t ib = i0 + (int64_t)blk * R;
             if (shared) {
                 write_tile_shared<1, R>(smem, plan, H, T, acc, 1, ib, m, r, tid);   // uses the LDS of the first chunk buffer
                 if (more) {
@@ -363,22 +248,16 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
             }
         }
         if (last_chunk) {                                             // the block's sums are out
-            tk.advance();
-            if (!more) break;
-            if (chain) {
-                p = q;
-                enter(p);
-                nb_next = (int)(seg[0] / kSegBatch);
-            }
 #pragma unroll
             for (int t = 0; t < R; ++t) acc[0][t] = 0.0f;
-            c = 0; ib = (int64_t)(tk.cur - first_p) * R;
+            c = 0; ++blk;
             walked = first;
         } else {
             ++c;
             walked = next;
         }
     }
+    clk.store(wave, lane);
 }
 
 // Several columns per lane (r > 512, or columns used so unevenly that they were split), 16-bit
@@ -388,8 +267,8 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
 template <typename D, int NS, int RP>
 __device__ __forceinline__ void gq16_multi_slot(ChunkStager16<RP>& stg, uint8_t* smem, const typename D::elem* __restrict__ G,
                                                 const uint8_t* __restrict__ plan, PlanHeaderPtr H,
-                                                float* __restrict__ T, float* __restrict__ S, int m, int n, int r,
-                                                int tid, int lane, int wave, Tickets& tk, int first_p, int end_p, const ProblemTable* tab) {
+                                                float* __restrict__ T, int64_t i0, int nblk, int m, int n, int r,
+                                                int tid, int lane, int wave) {
     constexpr int R = 8 * RP;                                         // rows of a row block
     const int nchunks = H->nchunks, nslots = H->nslots;
     const auto* seg = as_const<uint32_t>(plan + H->off_q_seg) + wave;
@@ -451,22 +330,13 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16<RP>& stg, uint8_t*
 
     stg.stage(smem, 0, tid);                                          // chunk 0 of the first block (fetched by the caller)
     __syncthreads();
-    int rot = 0, c = 0;
-    int64_t ib = (int64_t)(tk.cur - first_p) * R;                     // first row of the block
-    for (int u = 0; ; ++u) {                                          // (row block, chunk) pairs, in order
-        if (c == 0) {
-            tk.draw(tid);
-            if (H->p_any_split) zero_share_of_s(S, r, (int)(ib / R), end_p - first_p, tid);
-        }
+    int rot = 0, c = 0, blk = 0;
+    const int units = nblk * nchunks;
+    for (int u = 0; u < units; ++u) {
         const bool last_chunk = c + 1 == nchunks;
-        const bool more_here = tk.nxt < end_p;                        // the block after this one belongs to this problem too
-        const bool more = !last_chunk || more_here;
-        if (!last_chunk)
-            stg.fetch(G, ib, m, n, c + 1, tid, wave);
-        else if (more_here)
-            stg.fetch(G, (int64_t)(tk.nxt - first_p) * R, m, n, 0, tid, wave);
-        else if (tk.nxt < tk.total)
-            fetch_ahead<typename D::elem, RP>(stg, tab, tk.nxt, tid, wave);
+        const bool more = u + 1 < units;
+        if (more)
+            stg.fetch(G, i0 + (int64_t)(last_chunk ? blk + 1 : blk) * R, m, n, last_chunk ? 0 : c + 1, tid, wave);
         buf = smem + (u & 1) * (RP * kPlaneStride);
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
@@ -482,7 +352,8 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16<RP>& stg, uint8_t*
                 if (rot > 2) step(ring[2], acc[s]);
             }
         }
-        if (last_chunk) {                                             // the block's sums per column are complete
+        if (last_chunk) {                                             // the block's 16 sums per column are complete
+            const int64_t ib = i0 + (int64_t)blk * R;
             if (more) { ring_restart(); rot = 0; }                    // the stream starts over; in flight during the stores
             if (shared) {
                 write_tile_shared<NS, R>(smem, plan, H, T, acc, nslots, ib, m, r, tid);   // uses the LDS of both chunk buffers
@@ -505,100 +376,58 @@ __device__ __forceinline__ void gq16_multi_slot(ChunkStager16<RP>& stg, uint8_t*
             for (int s = 0; s < NS; ++s)
 #pragma unroll
                 for (int t = 0; t < R; ++t) acc[s][t] = 0.0f;
-            c = 0;
+            c = 0; ++blk;
         } else {
             ++c;
         }
         if (more) stg.stage(smem, (u + 1) & 1, tid);                  // the other buffer: nobody reads it now
         __syncthreads();                                              // the next chunk is staged; this one is no longer read
-        if (last_chunk) {
-            tk.advance();
-            if (!more_here) break;
-            ib = (int64_t)(tk.cur - first_p) * R;
-        }
     }
 }
 
-// Kernel A for fp16 / bf16 with n % 8 == 0: R = 8 RP rows per row block.  `counter` (device memory, zero at the
-// start of the launch) is null when the launch has one workgroup per row block.
+// Kernel A for fp16 / bf16 with n % 8 == 0: R = 8 RP rows per row block.
 template <typename D, int RP>
-__global__ __launch_bounds__(kThreadsGQ, RP == 1 ? 4 : 1) void k_compress_gq16(const CompressGroup grp, int r, int d, uint32_t* counter) {
+__global__ __launch_bounds__(kThreadsGQ, RP == 1 ? 4 : 1) void k_compress_gq16(const CompressGroup grp, int r, int d, int blocks_per_wg) {
     constexpr int R = 8 * RP;
-    typedef typename D::elem E;
     extern __shared__ __align__(16) uint8_t smem[];
-    ProblemTable* tab = reinterpret_cast<ProblemTable*>(smem + 2 * RP * kPlaneStride);
+    const CompressProblem pr = group_pick(grp, (int)blockIdx.x, false);
+    const typename D::elem* __restrict__ G = static_cast<const typename D::elem*>(pr.G);
+    const uint8_t* __restrict__ plan = pr.plan;
+    float* __restrict__ T = pr.T;
+    float* __restrict__ S = pr.S;
+    const int m = pr.m, n = pr.n;
+    const int block = pr.block_gq, nblocks = pr.nblocks_gq;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (tid == 0) fill_table(grp, tab);
-    if (tid == kThreadsGQ - kWave) tab->ticket[0] = counter ? (int32_t)atomicAdd(counter, 2u) : (int32_t)blockIdx.x;
-    if (tid < 2 * RP) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    __syncthreads();
-    Tickets tk;
-    tk.counter = counter; tk.slot = tab->ticket; tk.total = grp.first_gq[grp.count]; tk.drawn = 1;
-    tk.cur = __builtin_amdgcn_readfirstlane(tab->ticket[0]);          // a workgroup's first two row blocks lie side by side
-    tk.nxt = counter ? tk.cur + 1 : tk.total;
-    if (tk.cur >= tk.total) return;
-    PhaseClock clk;                                                   // empty unless built for phase timing
+    const int64_t i0 = (int64_t)block * blocks_per_wg * R;
+    const int nblk = min(blocks_per_wg, (int)((m - i0 + R - 1) / R));   // row blocks of this workgroup
+
     ChunkStager16<RP> stg;
-    fetch_ahead<E, RP>(stg, tab, tk.cur, tid, wave);                  // in flight while the plan's header arrives
-    for (bool first = true; tk.cur < tk.total; first = false) {
-        const int p = problem_of(tab, tk.cur);
-        const E* __restrict__ G = static_cast<const E*>(uniform_ptr(&tab->G[p]));
-        const uint8_t* __restrict__ plan = uniform_ptr(&tab->plan[p]);
-        float* __restrict__ T = uniform_ptr(&tab->T[p]);
-        float* __restrict__ S = uniform_ptr(&tab->S[p]);
-        const int m = uniform_int(&tab->m[p]), n = uniform_int(&tab->n[p]);
-        const int first_p = uniform_int(&tab->first[p]), end_p = uniform_int(&tab->first[p + 1]);
-        if (!first) __syncthreads();                                  // the LDS of the problem before is no longer read
-        PlanHeaderPtr H = as_const<PlanHeader>(plan);
-        if (!plan_matches(H, m, n, r, d)) {                           // not a plan for this problem: its row blocks only mark S
-            while (tk.cur < end_p) {
-                tk.draw(tid);
-                poison_s(S, r, tk.cur - first_p, end_p - first_p, tid, kThreadsGQ);
-                __syncthreads();
-                tk.advance();
-            }
-            if (tk.cur < tk.total) fetch_ahead<E, RP>(stg, tab, tk.cur, tid, wave);
-        }
-        else if (H->nslots == 1) gq16_one_slot<D, RP>(stg, smem, tab, p, r, d, tid, lane, wave, tk, clk);
-        else if (H->nslots == 2) gq16_multi_slot<D, 2, RP>(stg, smem, G, plan, H, T, S, m, n, r, tid, lane, wave, tk, first_p, end_p, tab);
-        else                     gq16_multi_slot<D, kMaxSlots, RP>(stg, smem, G, plan, H, T, S, m, n, r, tid, lane, wave, tk, first_p, end_p, tab);
+    stg.fetch(G, i0, m, n, 0, tid, wave);                             // in flight while the plan's header arrives
+    PlanHeaderPtr H = as_const<PlanHeader>(plan);
+    if (!plan_matches(H, m, n, r, d)) {                               // not a plan for this problem
+        poison_s(S, r, block, nblocks, tid, kThreadsGQ);
+        return;
     }
-    clk.store(wave, lane);
+    if (H->p_any_split) {
+        const int64_t total = (int64_t)r * r;
+        for (int64_t k = (int64_t)block * kThreadsGQ + tid; k < total; k += (int64_t)nblocks * kThreadsGQ) S[k] = 0.0f;
+    }
+    if (tid < 2 * RP) *reinterpret_cast<f32x4*>(smem + tid * kPlaneStride + kChunk * 16) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (H->nslots == 1)      gq16_one_slot<D, RP>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else if (H->nslots == 2) gq16_multi_slot<D, 2, RP>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
+    else                     gq16_multi_slot<D, kMaxSlots, RP>(stg, smem, G, plan, H, T, i0, nblk, m, n, r, tid, lane, wave);
 }
 
-template <typename D> __global__ void k_zero_counter(uint32_t* counter) { if (threadIdx.x < 2) counter[threadIdx.x] = 0u; }
-
-// workgroups that stay on the device together: two per CU (what the LDS of a CU holds)
-static int gq16_resident_workgroups() {
-    constexpr int kMaxDevices = 64;
-    static std::atomic<int> cus[kMaxDevices];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 512;
-    int v = cus[dev].load(std::memory_order_relaxed);
-    if (v == 0) {
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        cus[dev].store(v, std::memory_order_relaxed);
-    }
-    return 2 * v;
-}
 
 template <typename D>
-static hipError_t launch_gq16(const CompressGroup& g, int32_t r, int32_t d, uint32_t* counter, hipStream_t st) {
+static hipError_t launch_gq16(const CompressGroup& g, int32_t r, int32_t d, int blocks_per_wg, hipStream_t st) {
     constexpr int RP = kRowsGQ16 / 8;
-    constexpr size_t lds = (size_t)2 * RP * kPlaneStride + sizeof(ProblemTable);   // two chunk buffers of RP 8-row planes, the table
+    constexpr size_t lds = (size_t)2 * RP * kPlaneStride;    // two chunk buffers of RP 8-row planes
     hipError_t e;
     if ((e = allow_dynamic_lds<k_compress_gq16<D, RP>>(lds)) != hipSuccess) return e;
-    static const int expmode = getenv("LSP_EXP") ? atoi(getenv("LSP_EXP")) : 0;
-    const int total = g.first_gq[g.count], resident = expmode == 1 ? (1 << 30) : expmode > 1 ? expmode : gq16_resident_workgroups();
-    if (total <= resident) {
-        hipLaunchKernelGGL((k_compress_gq16<D, RP>), dim3((unsigned)total), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d, (uint32_t*)nullptr);
-        return hipGetLastError();
-    }
-    hipLaunchKernelGGL(k_zero_counter<D>, dim3(1), dim3(64), 0, st, counter);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_compress_gq16<D, RP>), dim3((unsigned)resident), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d, counter);
+    hipLaunchKernelGGL((k_compress_gq16<D, RP>), dim3((unsigned)g.first_gq[g.count]), dim3(kThreadsGQ), lds, st, g, (int)r, (int)d, blocks_per_wg);
     return hipGetLastError();
 }
 

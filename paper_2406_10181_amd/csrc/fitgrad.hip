@@ -141,10 +141,10 @@ __global__ __launch_bounds__(kGradCols * kGradSlices) void k_grad_right(const fl
     }
 }
 
-// floats of workspace: T (m r, with the row-block counter of kernel A behind it) | S, C_P, C_Q, S1, X, D, M1, M2 (8 r^2) | Y (r n)
+// floats of workspace: T (m r) | S, C_P, C_Q, S1, X, D, M1, M2 (8 r^2) | Y (r n)
 size_t fitgrad_workspace_floats(int64_t m, int64_t n, int32_t r) {
     const size_t rr = (size_t)r * (size_t)r;
-    return t_region_bytes(m, r) / sizeof(float) + 8 * align_up(rr, 64) + align_up((size_t)r * (size_t)n, 64);
+    return align_up((size_t)m * r, 64) + 8 * align_up(rr, 64) + align_up((size_t)r * (size_t)n, 64);
 }
 
 template <typename D>
@@ -166,7 +166,7 @@ hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_i
                           float* gP, float* gQ, float* ws, lsp_dtype dtype, hipStream_t st) {
     const size_t rr = align_up((size_t)r * (size_t)r, 64);
     float* T = ws;
-    float* S = T + t_region_bytes(m, r) / sizeof(float);
+    float* S = T + align_up((size_t)m * r, 64);
     float* CP = S + rr; float* CQ = CP + rr; float* S1 = CQ + rr; float* X = S1 + rr;
     float* Dm = X + rr; float* M1 = Dm + rr; float* M2 = M1 + rr;
     float* Y = M2 + rr;

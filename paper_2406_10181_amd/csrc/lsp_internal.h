@@ -28,13 +28,6 @@ constexpr uint32_t kSharedColumn = 0x8000u;  // flag: the column is owned by sev
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// The intermediate T = G Q of a compress call: m x r floats, followed by 256 bytes whose first word is the
-// counter from which the workgroups of kernel A draw their row blocks.
-static inline size_t t_region_bytes(int64_t m, int32_t r) { return align_up((size_t)m * (size_t)r * sizeof(float), 256) + 256; }
-static inline uint32_t* t_region_counter(float* T, int64_t m, int32_t r) {
-    return reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(T) + align_up((size_t)m * (size_t)r * sizeof(float), 256));
-}
-
 // Remembers the raw HIP error for lsp_last_hip_error() and returns LSP_ERR_LAUNCH.
 int note_hip_error(hipError_t e);
 
@@ -136,7 +129,7 @@ struct CompressGroup {
     float*         T[kMaxGroup];
     float*         S[kMaxGroup];
     int32_t        m[kMaxGroup], n[kMaxGroup];
-    int32_t        first_gq[kMaxGroup + 1];      // row blocks of the T = G Q kernel
+    int32_t        first_gq[kMaxGroup + 1];      // workgroups of the T = G Q kernel
     int32_t        first_pt[kMaxGroup + 1];      // workgroups of the S = P^T T kernel
     int32_t        count;
 };
