@@ -73,10 +73,57 @@ def build(verbose: bool = True, save_temps: bool = False, out: str = LIB, define
     return out
 
 
+# Development builds with pieces of the two hot kernels left out (LSP_ABLATE bits, lsp_internal.h): name -> (bits, sources
+# to recompile); results of such a library are wrong by design, ablation.py only times it.
+ABLATIONS = {
+    "a_no_exchange": (0x001, ["compress_gq16_bf16.hip"]), "a_no_staging": (0x002, ["compress_gq16_bf16.hip"]),
+    "a_no_batches": (0x004, ["compress_gq16_bf16.hip"]), "a_no_gathers": (0x008, ["compress_gq16_bf16.hip"]),
+    "a_no_gathers_no_fmas": (0x018, ["compress_gq16_bf16.hip"]), "a_no_plan_stream": (0x020, ["compress_gq16_bf16.hip"]),
+    "a_no_bank_conflicts": (0x040, ["compress_gq16_bf16.hip"]), "a_no_t_store": (0x080, ["compress_gq16_bf16.hip"]),
+    "d_no_math": (0x100, ["decompress.hip"]), "d_no_q_loads": (0x200, ["decompress.hip"]), "d_no_u_build": (0x400, ["decompress.hip"]),
+    "d_stream_only": (0x700, ["decompress.hip"]), "d_no_bank_conflicts": (0x040, ["decompress.hip"]),
+}
+
+
+def ablation_lib(name: str) -> str:
+    return os.path.join(PKG, "ablations", f"liblsp_hip_{name}.so")
+
+
+def build_ablations(names=None, verbose: bool = False) -> None:
+    """Every variant recompiles only the source its switch lives in and links it with the objects of the normal build
+    (which must exist: run build() first)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    normal = os.path.join(OBJDIR, "liblsp_hip")
+    os.makedirs(os.path.dirname(ablation_lib("x")), exist_ok=True)
+
+    def one(name: str) -> None:
+        bits, srcs = ABLATIONS[name]
+        objs = []
+        for s in SOURCES:
+            base = os.path.splitext(s)[0]
+            if s in srcs:
+                obj = os.path.join(os.path.dirname(ablation_lib(name)), f"{name}_{base}.o")
+                cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, f"-DLSP_ABLATE={bits}",
+                                               "-x", "hip", "-c", os.path.join(CSRC, s), "-o", obj]
+                if verbose:
+                    print(" ".join(cmd), flush=True)
+                subprocess.check_call(cmd, stderr=subprocess.DEVNULL)
+                objs.append(obj)
+            else:
+                objs.append(os.path.join(normal, base + ".o"))
+        subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", ablation_lib(name)])
+
+    with concurrent.futures.ThreadPoolExecutor(max_workers=4) as pool:
+        list(pool.map(one, names or list(ABLATIONS)))
+
+
 PHASE_LIB = os.path.join(PKG, "liblsp_hip_phase.so")   # development build with per-phase cycle counters in kernel A (phase_timing.py)
 
 if __name__ == "__main__":
-    if "--phase-timing" in sys.argv:
+    if "--ablations" in sys.argv:
+        build(incremental=True)
+        build_ablations(verbose=True)
+    elif "--phase-timing" in sys.argv:
         build(out=PHASE_LIB, defines=("LSP_PHASE_TIMING",), incremental="--incremental" in sys.argv)
     else:
         build(save_temps="--save-temps" in sys.argv, incremental="--incremental" in sys.argv)

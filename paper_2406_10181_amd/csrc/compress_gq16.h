@@ -107,10 +107,22 @@ __device__ __forceinline__ void gather_pair16(const uint8_t* buf, const u32x4 e,
     for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int g = 0; g < RP; ++g)
-            x[h][g] = *reinterpret_cast<const u32x4*>(buf + (h ? e.z : e.x) + g * kPlaneStride);
+            if constexpr (kNoGathers) x[h][g] = e;
+            else if constexpr (kNoConflicts) {                        // inside the chunk only (the always-zero unit lies behind it)
+                const uint32_t off = h ? e.z : e.x;
+                x[h][g] = *reinterpret_cast<const u32x4*>(buf + (off < kChunk * 16u ? (off & ~0xF0u) | ((threadIdx.x & 15u) << 4) : off) + g * kPlaneStride);
+            }
+            else x[h][g] = *reinterpret_cast<const u32x4*>(buf + (h ? e.z : e.x) + g * kPlaneStride);
 }
 template <typename D, int RP>
 __device__ __forceinline__ void fma_pair16(const u32x4 e, const u32x4 (&x)[2][RP], float (&acc)[8 * RP]) {
+    if constexpr (kNoFmas) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int g = 0; g < RP; ++g) acc[g * 8 + h] = __uint_as_float(__float_as_uint(acc[g * 8 + h]) ^ x[h][g][0] ^ x[h][g][3]);
+        return;
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const float v = __uint_as_float(h ? e.w : e.y);
@@ -173,9 +185,14 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
             fma_pair16<D, RP>(slot[q], x[q & 1], acc[0]);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (kNoStream) {
 #pragma unroll
-        for (int q = 0; q < kBatchLoads; ++q) slot[q] = rp[(size_t)q * kWave];
-        rp += (size_t)kBatchLoads * kWave;
+            for (int q = 0; q < kBatchLoads; ++q) { slot[q].x = (slot[q].x + 272u) & 0x7FF0u; slot[q].z = (slot[q].z + 528u) & 0x7FF0u; }
+        } else {
+#pragma unroll
+            for (int q = 0; q < kBatchLoads; ++q) slot[q] = rp[(size_t)q * kWave];
+            rp += (size_t)kBatchLoads * kWave;
+        }
     };
 
     PhaseClock clk;                                                   // empty unless built for phase timing
@@ -191,7 +208,7 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
     for (int u = 0; u < units; ++u) {
         const bool last_chunk = c + 1 == nchunks;
         const uint32_t next = last_chunk ? (uint32_t)tid : (uint32_t)perm[(size_t)(c + 1) * kThreadsGQ];
-        const int nb = nb_next;
+        const int nb = kNoBatches ? 0 : nb_next;
         nb_next = (int)(seg[(last_chunk ? 0 : c + 1) * kWavesGQ] / kSegBatch);   // arrives while this chunk is walked
         clk.tick(kPhTop);
         if (u + 1 < units)                                            // next chunk, maybe of the next block: lands while this one is consumed
@@ -215,7 +232,7 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
         }
         clk.tick(kPhFirst);
-        if (stage_early) stg.stage(smem, (u + 1) & 1, tid);
+        if (stage_early && !kNoStaging) stg.stage(smem, (u + 1) & 1, tid);
         clk.tick(kPhStage);
         for (int g = groups - before; g > 0; --g) {
             step(ring[0]); step(ring[1]); step(ring[2]); step(ring[3]);
@@ -230,7 +247,8 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
         // The sums move to the lanes that walk the columns in the next chunk; after the last chunk
         // of a block they go home (thread t: virtual column t) and out to T.
         if (last_chunk && more) { ring_restart(); rot = 0; }          // the stream starts over; in flight during the stores
-        swap_owner<R>(smem + (u & 1) * (RP * kPlaneStride), acc[0], walked, next);
+        if constexpr (kNoExchange) __syncthreads();
+        else swap_owner<R>(smem + (u & 1) * (RP * kPlaneStride), acc[0], walked, next);
         clk.tick(kPhSwap);
         if (last_chunk) {
             const int64_t ib = i0 + (int64_t)blk * R;
@@ -242,9 +260,13 @@ __device__ __forceinline__ void gq16_one_slot(ChunkStager16<RP>& stg, uint8_t* s
                     __syncthreads();
                 }
             } else if (mycol != kNoColumn) {
+                if constexpr (kNoTStore) {
+                    if (acc[0][0] == 123.456f) T[0] = acc[0][1] + acc[0][2] + acc[0][3] + acc[0][4] + acc[0][5] + acc[0][6] + acc[0][7];
+                } else {
 #pragma unroll
-                for (int t = 0; t < R; ++t)
-                    if (ib + t < m) T[(ib + t) * (int64_t)r + mycol] = acc[0][t];
+                    for (int t = 0; t < R; ++t)
+                        if (ib + t < m) T[(ib + t) * (int64_t)r + mycol] = acc[0][t];
+                }
             }
         }
         if (last_chunk) {                                             // the block's sums are out

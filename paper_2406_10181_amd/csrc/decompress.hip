@@ -172,8 +172,13 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, 
         const f32x4* qvp = reinterpret_cast<const f32x4*>(Q_val + j0 * DD);
 #pragma unroll
         for (int k = 0; k < NE / 4; ++k) {
-            p.qi[k] = qip[k];
-            p.qv[k] = qvp[k];
+            if constexpr (kNoApplyQ) {
+                p.qi[k] = make_int4((int)(threadIdx.x + k) & 255, (int)(threadIdx.x * 3 + k) & 255, (int)(threadIdx.x * 5 + k) & 255, (int)(threadIdx.x * 7 + k) & 255);
+                p.qv[k] = f32x4{0.1f, 0.2f, 0.3f, 0.4f};
+            } else {
+                p.qi[k] = qip[k];
+                p.qv[k] = qvp[k];
+            }
         }
 #pragma unroll
         for (int t = 0; t < R; ++t) {
@@ -210,11 +215,14 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, 
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int c = 0; c < CPT; ++c) acc[t][c] = 0.0f;
+            if constexpr (kNoApplyMath) acc[0][0] = val_of(cur, 0) + __int_as_float((int)idx_of(cur, 0));
+            else
 #pragma unroll
             for (int c = 0; c < CPT; ++c)
 #pragma unroll
                 for (int k = 0; k < DD; ++k) {
-                    const f32x4 u = Us4[idx_of(cur, c * DD + k) + g * (PS / 16)];
+                    const uint32_t unit = kNoConflicts ? ((idx_of(cur, c * DD + k) & ~15u) | (threadIdx.x & 15u)) : idx_of(cur, c * DD + k);
+                    const f32x4 u = Us4[unit + g * (PS / 16)];
                     const float v = val_of(cur, c * DD + k);
                     acc[0][c] = fmaf(v, u.x, acc[0][c]);
                     acc[1][c] = fmaf(v, u.y, acc[1][c]);
@@ -261,7 +269,7 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, 
     };
 #pragma unroll
     for (int k = 0; k + 1 < kDepth; ++k) load_if(k, slot[k]);       // in flight while the U tile is built
-    build_u_tile_fast<RG, DD, PS, NT>(smem, pent, S, P_idx, P_val, i0, m, r);
+    if constexpr (!kNoApplyU) build_u_tile_fast<RG, DD, PS, NT>(smem, pent, S, P_idx, P_val, i0, m, r);
     __syncthreads();
     for (int p = 0; p < npass; p += kDepth) {
 #pragma unroll

@@ -28,6 +28,24 @@ constexpr uint32_t kSharedColumn = 0x8000u;  // flag: the column is owned by sev
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Development aid: -DLSP_ABLATE=<bits> builds a library in which pieces of the two hot kernels are left out, to see
+// what each costs (build.py --ablations, ablation.py).  Such a library computes WRONG results by design and is
+// never loaded by the binding; the normal build has LSP_ABLATE = 0 and all of these are false.
+#ifndef LSP_ABLATE
+#define LSP_ABLATE 0
+#endif
+constexpr bool kNoExchange  = (LSP_ABLATE & 0x001) != 0;   // kernel A: the sums stay with their lanes between chunks (one barrier instead)
+constexpr bool kNoStaging   = (LSP_ABLATE & 0x002) != 0;   // kernel A: no chunk is written to LDS (nor fetched: the loads are dead)
+constexpr bool kNoBatches   = (LSP_ABLATE & 0x004) != 0;   // kernel A: no plan row is walked
+constexpr bool kNoGathers   = (LSP_ABLATE & 0x008) != 0;   // kernel A: the plan entry itself stands in for the gathered unit
+constexpr bool kNoFmas      = (LSP_ABLATE & 0x010) != 0;   // kernel A: one exclusive-or per gathered unit instead of 16 + 16 instructions
+constexpr bool kNoStream    = (LSP_ABLATE & 0x020) != 0;   // kernel A: the plan ring is never refilled (stale entries, scrambled)
+constexpr bool kNoConflicts = (LSP_ABLATE & 0x040) != 0;   // both: lane k of every 16 gathers from bank quad k
+constexpr bool kNoTStore    = (LSP_ABLATE & 0x080) != 0;   // kernel A: T is not stored
+constexpr bool kNoApplyMath = (LSP_ABLATE & 0x100) != 0;   // apply kernel: no gathers of U, no FMAs
+constexpr bool kNoApplyQ    = (LSP_ABLATE & 0x200) != 0;   // apply kernel: the rows of Q are made up, not loaded
+constexpr bool kNoApplyU    = (LSP_ABLATE & 0x400) != 0;   // apply kernel: U = P S is not built
+
 // Remembers the raw HIP error for lsp_last_hip_error() and returns LSP_ERR_LAUNCH.
 int note_hip_error(hipError_t e);
 
