@@ -466,10 +466,10 @@ def other_configs(torch, syn, L, dev, stream):
 def dense_ablation(torch, syn, L, dev, stream):
     """Where does the sparse gather lose to a real contraction?  S = P^T G Q on config-4 shapes (bf16, r = 512):
     the library's sparse path (lsp_compress_planned) at d = 2, 4, 8, 16 entries per projector row, against
-    T = G Qd, S = Pd^T T with the projectors densified and rounded to bf16, run through the vendor GEMM
-    (torch.matmul: matrix cores).  The dense leg is a yardstick, not a product path: it is not behind the C ABI,
-    and bf16 projector values (8 significant bits) put it outside the 1e-3 parity bar, which the reported error
-    shows.  Buffers rotate so that G comes from HBM in both legs."""
+    T = G Qd, S = Pd^T T with the projectors densified and rounded to bf16, run on the matrix cores twice: by the
+    library's own kernels (lsp_compress_dense: v_mfma_f32_32x32x16_bf16) and, as a second yardstick, by the vendor
+    GEMM (torch.matmul).  bf16 projector values (8 significant bits) put the dense form outside the 1e-3 parity
+    bar, which the reported error shows.  Buffers rotate so that G comes from HBM in all legs."""
     r, code, nbuf, reps = 512, syn.DTYPE_CODE["bf16"], 8, 3
     rows = []
 
@@ -516,15 +516,25 @@ def dense_ablation(torch, syn, L, dev, stream):
             def dense(G):
                 out["S"] = torch.matmul(Pdt, torch.matmul(G, Qdb))
             t_dense = timed(dense, Gs)
+            Qdt = Qd.t().contiguous().to(torch.bfloat16)
+            dwb = L.lsp_compress_dense_workspace_bytes(m, n, r)
+            dws = torch.empty(dwb, dtype=torch.uint8, device=dev)
+            S_dense = torch.empty(r, r, device=dev, dtype=torch.float32)
+            t_own = timed(lambda G: L.lsp_compress_dense(G, Pdt, Qdt, m, n, r, S_dense, code, dws, dwb, stream), Gs)
+            flop = 2.0 * m * n * r + 2.0 * m * r * r
             ref = torch.matmul(Pd.t().double(), torch.matmul(Gs[-1].double(), Qd.double()))   # fp64, fp32 projector values
             scale = ref.abs().max().item()
-            rows.append({"m": m, "n": n, "d": d, "sparse_us": round(t_sparse, 1), "dense_bf16_gemm_us": round(t_dense, 1),
+            rows.append({"m": m, "n": n, "d": d, "sparse_us": round(t_sparse, 1), "dense_mfma_us": round(t_own, 1),
+                         "dense_mfma_TFLOP/s": round(flop / t_own / 1e6, 1), "dense_mfma_frac_of_2500": round(flop / t_own / 1e6 / 2500.0, 4),
+                         "dense_vendor_gemm_us": round(t_dense, 1),
                          "sparse_max_err_rel": float(f"{(S_sparse.double() - ref).abs().max().item() / scale:.2e}"),
-                         "dense_max_err_rel": float(f"{(out['S'].double() - ref).abs().max().item() / scale:.2e}")})
-            del plan, ws, Pd, Qd, Pdt, Qdb, ref
+                         "dense_mfma_max_err_rel": float(f"{(S_dense.double() - ref).abs().max().item() / scale:.2e}"),
+                         "dense_vendor_max_err_rel": float(f"{(out['S'].double() - ref).abs().max().item() / scale:.2e}")})
+            del plan, ws, Pd, Qd, Pdt, Qdb, Qdt, dws, ref
         del Gs
-    return {"ablation": "dense projectors (bf16, vendor GEMM) against the sparse compress path, r = 512, bf16 G, one call, "
-                        "one stream, G from HBM", "unit": "us per call", "rows": rows}
+    return {"ablation": "dense projectors (bf16; lsp_compress_dense on the matrix cores, and the vendor GEMM) against the sparse "
+                        "compress path, r = 512, bf16 G, one call, one stream, G from HBM", "unit": "us per call",
+            "roofline_dense": {"bound": "mfma", "peak": 2500.0, "unit": "TFLOP/s", "flop": "2 m n r + 2 m r^2"}, "rows": rows}
 
 
 def cpu_baseline(syn, r, d):

@@ -253,6 +253,25 @@ int lsp_projector_reorder(const int32_t* idx, const float* val, int64_t rows, in
                           int32_t* idx_out, float* val_out, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Dense-projector ablation of compress:  S := P^T G Q with DENSE projectors, on the matrix cores.
+ * Def. 1 makes the projectors (d, r)-sparse, and the calls above never multiply by the zeros.  This call
+ * is the yardstick for that choice: the same contraction with dense m x r and n x r projectors (what a
+ * subspace method without the sparsity would run), as two matrix-core products in the storage type with
+ * fp32 accumulation, T = G Q rounded to the storage type in between.  Its cost does not depend on d.
+ *
+ *   G          device, m*n elements of `dtype` (LSP_F16 or LSP_BF16; LSP_ERR_DTYPE otherwise), row-major
+ *   Pt, Qt     device, the TRANSPOSED dense projectors P^T [r][m] and Q^T [r][n], row-major, in `dtype`
+ *   S          device, r*r fp32, written
+ *   workspace  device scratch of at least lsp_compress_dense_workspace_bytes(m, n, r) bytes, 16-byte aligned
+ * Shapes: m a multiple of 128, n of 64, r of 128 (LSP_ERR_SHAPE otherwise; the size query then returns 0).
+ * Asynchronous, three kernels, no atomics (bit-reproducible); all pointers 16-byte aligned.
+ */
+size_t lsp_compress_dense_workspace_bytes(int64_t m, int64_t n, int32_t r);
+int lsp_compress_dense(const void* G, const void* Pt, const void* Qt,
+                       int64_t m, int64_t n, int32_t r, float* S, lsp_dtype dtype,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Estimation bias of the projector pair on a gradient (Def. 2):
  *     b(P, Q; G) = || P P^T G Q Q^T - G ||_F / || G ||_F ,
  * the quantity MaybeUpdate in Alg. 1 compares with its threshold alpha to decide whether the

@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     lsp_compress, lsp_compress_workspace_bytes, lsp_workspace_bytes,
     lsp_plan_bytes, lsp_plan_build, lsp_plan_build_host, lsp_plan_build_async, lsp_plan_build_workspace_bytes,
     lsp_compress_planned, lsp_compress_planned_workspace_bytes, lsp_compress_planned_static, lsp_static_scratch_bytes,
-    lsp_decompress_apply, lsp_compress_planned_grouped, lsp_decompress_apply_grouped,
+    lsp_decompress_apply, lsp_compress_planned_grouped, lsp_decompress_apply_grouped, lsp_compress_dense, lsp_compress_dense_workspace_bytes,
     lsp_estimation_bias, lsp_estimation_bias_workspace_bytes,
     lsp_reproject_state, lsp_reproject_state_workspace_bytes, lsp_projector_reorder_host, lsp_projector_reorder,
     lsp_compress_item, lsp_apply_item, compress_items, apply_items, lsp_validate_projector, lsp_strerror, lsp_version,

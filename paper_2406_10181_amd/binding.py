@@ -77,6 +77,10 @@ def lib() -> ctypes.CDLL:
         L.lsp_compress_planned_grouped.restype = ctypes.c_int
         L.lsp_decompress_apply_grouped.argtypes = [vp, i32, i32, i32, i32, vp]
         L.lsp_decompress_apply_grouped.restype = ctypes.c_int
+        L.lsp_compress_dense_workspace_bytes.argtypes = [i64, i64, i32]
+        L.lsp_compress_dense_workspace_bytes.restype = sz
+        L.lsp_compress_dense.argtypes = [vp, vp, vp, i64, i64, i32, vp, i32, vp, sz, vp]
+        L.lsp_compress_dense.restype = ctypes.c_int
         L.lsp_estimation_bias.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, ctypes.c_size_t, i32, vp]
         L.lsp_estimation_bias.restype = ctypes.c_int
         L.lsp_projector_reorder_host.argtypes = [vp, vp, i64, i32, i32, vp, vp]
@@ -307,6 +311,19 @@ def lsp_decompress_apply_grouped(items, count, r, d, dtype: int, stream=None, ch
                                             _stream(stream))
     if check:
         _check(rc, "lsp_decompress_apply_grouped")
+    return rc
+
+
+def lsp_compress_dense_workspace_bytes(m, n, r) -> int:
+    return int(lib().lsp_compress_dense_workspace_bytes(m, n, r))
+
+
+def lsp_compress_dense(G, Pt, Qt, m, n, r, S, dtype: int, workspace, workspace_bytes, stream=None, check: bool = True) -> int:
+    """Pt, Qt: the transposed dense projectors [r][m], [r][n] in the storage type of G."""
+    rc = lib().lsp_compress_dense(_ptr(G), _ptr(Pt), _ptr(Qt), m, n, r, _ptr(S), dtype, _ptr(workspace), workspace_bytes,
+                                  _stream(stream))
+    if check:
+        _check(rc, "lsp_compress_dense")
     return rc
 
 

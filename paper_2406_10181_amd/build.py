@@ -15,7 +15,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblsp_hip.so")
 OBJDIR = os.path.join(PKG, "_build")
 SOURCES = ["compress_gq16_bf16.hip", "compress_gq16_f16.hip", "compress_gq32.hip", "plan_device.hip", "decompress.hip",
-           "compress.hip", "api.cpp", "plan.cpp", "reproject.hip", "fitgrad.hip", "noalloc.hip", "probe.hip"]
+           "compress.hip", "api.cpp", "plan.cpp", "reproject.hip", "dense.hip", "fitgrad.hip", "noalloc.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -150,6 +150,24 @@ int lsp_plan_build_host(const int32_t* P_idx, const float* P_val, const int32_t*
     return lsp::build_plan_host(P_idx, P_val, Q_idx, Q_val, m, n, r, d, static_cast<uint8_t*>(plan_host));
 }
 
+size_t lsp_compress_dense_workspace_bytes(int64_t m, int64_t n, int32_t r) {
+    if (check_shape(m, n, r, 1) != LSP_OK || !lsp::dense_shape_ok(m, n, r)) return 0;
+    return lsp::dense_workspace_bytes(m, r);
+}
+
+int lsp_compress_dense(const void* G, const void* Pt, const void* Qt, int64_t m, int64_t n, int32_t r, float* S,
+                       lsp_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!G || !Pt || !Qt || !S) return LSP_ERR_NULL;
+    int rc = check_shape(m, n, r, 1);
+    if (rc != LSP_OK) return rc;
+    if (!lsp::dense_shape_ok(m, n, r)) return LSP_ERR_SHAPE;
+    if (dtype != LSP_F16 && dtype != LSP_BF16) return LSP_ERR_DTYPE;
+    if (!workspace || workspace_bytes < lsp::dense_workspace_bytes(m, r) || !aligned16(workspace)) return LSP_ERR_WORKSPACE;
+    if (!aligned16(G) || !aligned16(Pt) || !aligned16(Qt) || !aligned16(S)) return LSP_ERR_ALIGN;
+    hipError_t e = lsp::launch_compress_dense(G, Pt, Qt, m, n, r, S, static_cast<uint8_t*>(workspace), dtype, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LSP_OK : fail_launch(e);
+}
+
 int lsp_compress_planned_grouped(const lsp_compress_item* items, int32_t count, int32_t r, int32_t d,
                                  lsp_dtype dtype, void* stream) {
     if (!items) return LSP_ERR_NULL;

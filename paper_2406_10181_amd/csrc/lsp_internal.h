@@ -206,6 +206,12 @@ hipError_t launch_compress_raw(const void* G, const int32_t* P_idx, const float*
                                int64_t m, int64_t n, int32_t r, int32_t d,
                                float* S, lsp_dtype dtype, float* T, const int32_t* gate, hipStream_t st);
 hipError_t launch_decompress(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, hipStream_t st);
+// Dense-projector ablation of compress on the matrix cores (dense.hip): Pt = P^T [r][m], Qt = Q^T [r][n] in the
+// storage type of G (fp16 / bf16); workspace of dense_workspace_bytes(m, r); shapes must pass dense_shape_ok.
+bool       dense_shape_ok(int64_t m, int64_t n, int32_t r);
+size_t     dense_workspace_bytes(int64_t m, int32_t r);
+hipError_t launch_compress_dense(const void* G, const void* Pt, const void* Qt, int64_t m, int64_t n, int32_t r, float* S,
+                                 uint8_t* workspace, lsp_dtype dtype, hipStream_t st);
 // Estimation bias (Def. 2): `partial` holds bias_blocks(m, r) pairs of floats, `out` three floats.
 int64_t    bias_blocks(int64_t m, int32_t r);
 hipError_t launch_bias(ApplyGroup& g, int32_t r, int32_t d, lsp_dtype dtype, float* partial, float* out, hipStream_t st);

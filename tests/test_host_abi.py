@@ -358,3 +358,12 @@ def test_projector_reorder_keeps_the_matrix_and_spreads_the_banks(rows, r, d, di
     assert L.lsp_projector_reorder(0x1000, 0x1000, rows, r + 1, r, 0x2000, 0x3000, None, check=False) == -2
     bad = idx.copy(); bad[0, 0] = r
     assert L.lsp_projector_reorder_host(bad, val, rows, d, r, oi, ov, check=False) == -6
+
+
+def test_dense_compress_refuses_other_shapes_and_types():
+    fake = 4096
+    assert L.lsp_compress_dense_workspace_bytes(100, 64, 128) == 0
+    assert L.lsp_compress_dense(fake, fake, fake, 100, 64, 128, fake, 2, fake, 1 << 30, None, check=False) == -2
+    assert L.lsp_compress_dense(fake, fake, fake, 128, 64, 128, fake, 0, fake, 1 << 30, None, check=False) == -3
+    assert L.lsp_compress_dense(fake, fake, fake, 128, 64, 128, fake, 2, fake, 16, None, check=False) == -4
+    assert L.lsp_compress_dense(None, fake, fake, 128, 64, 128, fake, 2, fake, 1 << 30, None, check=False) == -1
