@@ -322,7 +322,7 @@ int lsp_projector_reorder(const int32_t* idx, const float* val, int64_t rows, in
 
 size_t lsp_reproject_state_workspace_bytes(int32_t r) {
     if (r <= 0 || r > LSP_MAX_R) return 0;
-    return lsp::align_up((size_t)3 * (size_t)r * (size_t)r * sizeof(float), 256);
+    return lsp::align_up((size_t)4 * (size_t)r * (size_t)r * sizeof(float), 256);   // A, B and two products in flight
 }
 
 int lsp_reproject_state(const int32_t* P_idx, const float* P_val, const int32_t* Pprev_idx, const float* Pprev_val,

@@ -13,6 +13,7 @@
 // row through the column-sorted copy of P in the plan, for Y.  The dense r x r products run in fp32 on the
 // matrix cores; the rest is gathers and fp32 dot products.  No m x n temporary exists.
 #include <cstring>
+#include <type_traits>
 
 #include "lsp_internal.h"
 
@@ -21,49 +22,82 @@ namespace lsp {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Y[a][j] = sum over the entries (i, v) of row a of P^T of v * G[i][j]: one workgroup per (piece of a row of
-// P^T, tile of columns); a thread owns VEC consecutive columns.  Rows cut into pieces (heavily skewed
-// projectors) add up with atomics on a Y that k_zero_if_split cleared.
-constexpr int kThreadsY = 128;
+// P^T, tile of 64 VEC columns); a lane owns VEC consecutive columns, and the four waves take a quarter of the
+// piece's entries each; their sums meet in LDS and are added in wave order.  Rows cut into pieces (heavily
+// skewed projectors) add up with atomics on a Y that k_zero_if_split cleared.
+// Every row of G is wanted by d rows of Y, so G goes from L2 to the CUs d times: that traffic (268 MB at
+// 4096 x 4096, d = 8, 16-bit) is what the kernel's time is made of, whatever the shape of the workgroups.  HBM
+// sees G once: workgroup b runs on XCD b % 8 (the dispatcher deals workgroups round-robin), and the grid is laid
+// out so that one XCD takes every row of Y for a column tile before its next tile, so a tile of G (m rows of
+// 64 VEC elements, 2 MB at m = 4096) stays in that XCD's L2 for its d visits.
+constexpr int kThreadsY = 256, kWavesY = kThreadsY / kWave, kXcds = 8;
 template <typename D, int VEC>
 __global__ __launch_bounds__(kThreadsY) void k_gather_rows(const typename D::elem* __restrict__ G, const uint8_t* __restrict__ plan,
-                                                          float* __restrict__ Y, int m, int n, int r, int d) {
+                                                          float* __restrict__ Y, int m, int n, int r, int d, int items, int tiles) {
+    __shared__ float part[kWavesY][kWave * VEC];
     PlanHeaderPtr H = as_const<PlanHeader>(plan);
     if (H->magic != kPlanMagic || H->m != m || H->n != n || H->r != r || H->d != d) return;
-    const int item = blockIdx.x;
-    if (item >= H->p_nitems) return;
+    const int seq = blockIdx.x / kXcds;                             // position in this XCD's sequence: items fastest
+    const int item = seq % items, tile = (seq / items) * kXcds + blockIdx.x % kXcds;
+    if (item >= H->p_nitems || tile >= tiles) return;
     const auto* itp = as_const<int32_t>(plan + H->off_p_item) + 4 * item;
     const RowItem it{itp[0], itp[1], itp[2], itp[3]};
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int e_begin = (int)((int64_t)it.len * wave / kWavesY), e_end = (int)((int64_t)it.len * (wave + 1) / kWavesY);
     const uint2* ent = reinterpret_cast<const uint2*>(plan + H->off_p_ent) + it.start;
-    const int64_t j0 = ((int64_t)blockIdx.y * kThreadsY + threadIdx.x) * VEC;
-    if (j0 >= n) return;
+    const int64_t tile0 = (int64_t)tile * kWave * VEC;
+    const int64_t j0 = tile0 + lane * VEC;
+    const bool live = j0 < n;                                       // n % VEC == 0: a lane's columns are all in or all out
     float acc[VEC];
 #pragma unroll
     for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
-    for (int e = 0; e < it.len; ++e) {
-        const uint2 en = ent[e];                                    // uniform over the workgroup
+    // a lane's piece of a row: 8 bytes of 16-bit storage or 16 bytes of fp32 (VEC == 4), else one element
+    using Piece = typename std::conditional<VEC == 1, typename D::elem, typename std::conditional<D::size == 2, uint2, f32x4>::type>::type;
+    auto load = [&](uint2 en) { return *reinterpret_cast<const Piece*>(G + (int64_t)en.x * n + j0); };
+    auto add = [&](uint2 en, Piece x) {                             // entries are added in their stored order
         const float v = __uint_as_float(en.y);
-        const typename D::elem* row = G + (int64_t)en.x * n + j0;
-        if constexpr (VEC == 8) {                                   // 16-bit storage, n % 8 == 0
-            const uint4 x = *reinterpret_cast<const uint4*>(row);
-            const uint32_t w[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                acc[2 * q]     = fmaf(v, widen<D>((uint16_t)(w[q] & 0xFFFFu)), acc[2 * q]);
-                acc[2 * q + 1] = fmaf(v, widen<D>((uint16_t)(w[q] >> 16)), acc[2 * q + 1]);
-            }
-        } else if constexpr (VEC == 4) {                            // fp32 storage, n % 4 == 0
-            const f32x4 x = *reinterpret_cast<const f32x4*>(row);
+        if constexpr (VEC == 1) {
+            acc[0] = fmaf(v, widen<D>(x), acc[0]);
+        } else if constexpr (D::size == 2) {
+            acc[0] = fmaf(v, widen<D>((uint16_t)(x.x & 0xFFFFu)), acc[0]); acc[1] = fmaf(v, widen<D>((uint16_t)(x.x >> 16)), acc[1]);
+            acc[2] = fmaf(v, widen<D>((uint16_t)(x.y & 0xFFFFu)), acc[2]); acc[3] = fmaf(v, widen<D>((uint16_t)(x.y >> 16)), acc[3]);
+        } else {
             acc[0] = fmaf(v, x.x, acc[0]); acc[1] = fmaf(v, x.y, acc[1]);
             acc[2] = fmaf(v, x.z, acc[2]); acc[3] = fmaf(v, x.w, acc[3]);
-        } else {
-            acc[0] = fmaf(v, widen<D>(row[0]), acc[0]);
+        }
+    };
+    if (live) {
+        // eight rows of G in flight per lane: a row piece is one load whose latency nothing else hides
+        constexpr int kInFlight = 8;
+        int e = e_begin;
+        for (; e + kInFlight <= e_end; e += kInFlight) {
+            uint2 en[kInFlight];                                    // uniform over the wave
+            Piece x[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) en[u] = ent[e + u];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) x[u] = load(en[u]);
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) add(en[u], x[u]);
+        }
+        for (; e < e_end; ++e) {
+            const uint2 en = ent[e];
+            add(en, load(en));
         }
     }
-    float* dst = Y + (int64_t)it.a * n + j0;
 #pragma unroll
-    for (int q = 0; q < VEC; ++q) {
-        if (it.atomic) atomicAdd(dst + q, acc[q]);
-        else dst[q] = acc[q];
+    for (int q = 0; q < VEC; ++q) part[wave][q * kWave + lane] = acc[q];     // column lane * VEC + q of the tile
+    __syncthreads();
+    for (int c = threadIdx.x; c < kWave * VEC; c += kThreadsY) {
+        const int64_t j = tile0 + c;
+        if (j >= n) break;
+        const int slot = (c % VEC) * kWave + c / VEC;
+        float sum = part[0][slot];
+#pragma unroll
+        for (int w = 1; w < kWavesY; ++w) sum += part[w][slot];
+        float* dst = Y + (int64_t)it.a * n + j;
+        if (it.atomic) atomicAdd(dst, sum);
+        else *dst = sum;
     }
 }
 
@@ -74,7 +108,8 @@ __global__ __launch_bounds__(256) void k_zero_if_split(const uint8_t* __restrict
 }
 
 // gP[i][k] = sum_k' P_val[i][k'] M1[P_idx[i][k']][a] + sum_b T[i][b] D[a][b],  a = P_idx[i][k]: one wave per
-// row i, the dot product over b spread over its lanes.
+// row i, the dot product over b spread over its lanes; lane k' < d also carries the k'-th term of the first
+// sum into the same lane reduction (d <= 64).  Four entries of the row at a time, so that their loads overlap.
 __global__ __launch_bounds__(256) void k_grad_left(const float* __restrict__ T, const float* __restrict__ Dm, const float* __restrict__ M1,
                                                    const int32_t* __restrict__ P_idx, const float* __restrict__ P_val,
                                                    int m, int r, int d, float* __restrict__ gP) {
@@ -82,33 +117,43 @@ __global__ __launch_bounds__(256) void k_grad_left(const float* __restrict__ T, 
     const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (i >= m) return;
     const float* Ti = T + i * r;
-    for (int k = 0; k < d; ++k) {
-        const int a = P_idx[i * d + k];
-        const float* Da = Dm + (int64_t)a * r;
-        float acc = 0.0f;
-        for (int b = lane; b < r; b += 64) acc = fmaf(Ti[b], Da[b], acc);
+    const bool mine = lane < d;
+    const float pv = mine ? P_val[i * d + lane] : 0.0f;
+    const int64_t prow = mine ? (int64_t)P_idx[i * d + lane] * r : 0;
+    for (int k0 = 0; k0 < d; k0 += 4) {
+        int a[4];
+        float acc[4];
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
-        if (lane == 0) {
-            float g = acc;
-            for (int k2 = 0; k2 < d; ++k2) g = fmaf(P_val[i * d + k2], M1[(int64_t)P_idx[i * d + k2] * r + a], g);
-            gP[i * d + k] = g;
+        for (int q = 0; q < 4; ++q) {
+            a[q] = P_idx[i * d + min(k0 + q, d - 1)];
+            acc[q] = mine ? pv * M1[prow + a[q]] : 0.0f;
+        }
+        for (int b = lane; b < r; b += 64) {
+            const float t = Ti[b];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = fmaf(t, Dm[(int64_t)a[q] * r + b], acc[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) acc[q] += __shfl_down(acc[q], off);
+            if (lane == 0 && k0 + q < d) gP[i * d + k0 + q] = acc[q];
         }
     }
 }
 
 // gQ[j][k] = sum_k' Q_val[j][k'] M2[Q_idx[j][k']][b] + sum_a Y[a][j] D[a][b],  b = Q_idx[j][k]: a workgroup takes
-// 16 columns j (the reads of Y are then contiguous) and cuts the sum over a into 16 interleaved slices, one per
-// group of 16 threads; the slices' sums meet in LDS and are added in slice order.  Eight entries of a row at a time.
-constexpr int kGradCols = 16, kGradSlices = 16;
+// 16 columns j (the reads of Y are then contiguous) and cuts the sum over a into 64 interleaved slices, one per
+// group of 16 threads (every term is a gather whose latency only more threads hide); the slices' sums meet in LDS
+// and are added in slice order.  Eight entries of a row at a time.
+constexpr int kGradCols = 16, kGradSlices = 64;
 __global__ __launch_bounds__(kGradCols * kGradSlices) void k_grad_right(const float* __restrict__ Y, const float* __restrict__ Dm, const float* __restrict__ M2,
                                                                       const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
                                                                       int n, int r, int d, float* __restrict__ gQ) {
-    __shared__ float part[kGradSlices][kGradCols][8];
+    __shared__ float part[kGradSlices][kGradCols * 8 + 1];
     const int jl = threadIdx.x % kGradCols, sl = threadIdx.x / kGradCols;
     const int64_t j = (int64_t)blockIdx.x * kGradCols + jl;
-    const bool live = j < n;
-    const int64_t jc = live ? j : (int64_t)n - 1;
+    const int64_t jc = j < n ? j : (int64_t)n - 1;
     for (int k0 = 0; k0 < d; k0 += 8) {
         int b[8];
         float acc[8];
@@ -117,6 +162,7 @@ __global__ __launch_bounds__(kGradCols * kGradSlices) void k_grad_right(const fl
             b[q] = k0 + q < d ? Q_idx[jc * d + k0 + q] : 0;
             acc[q] = 0.0f;
         }
+#pragma unroll 4
         for (int a = sl; a < r; a += kGradSlices) {
             const float y = Y[(int64_t)a * n + jc];
             const float* Da = Dm + (int64_t)a * r;
@@ -124,17 +170,17 @@ __global__ __launch_bounds__(kGradCols * kGradSlices) void k_grad_right(const fl
             for (int q = 0; q < 8; ++q) acc[q] = fmaf(y, Da[b[q]], acc[q]);
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) part[sl][jl][q] = acc[q];
+        for (int q = 0; q < 8; ++q) part[sl][jl * 8 + q] = acc[q];
         __syncthreads();
-        if (sl == 0 && live) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (k0 + q < d) {
-                    float g = 0.0f;
-                    for (int t = 0; t < kGradSlices; ++t) g += part[t][jl][q];
-                    for (int k2 = 0; k2 < d; ++k2) g = fmaf(Q_val[j * d + k2], M2[(int64_t)Q_idx[j * d + k2] * r + b[q]], g);
-                    gQ[j * d + k0 + q] = g;
-                }
+        if (threadIdx.x < kGradCols * 8) {                          // one thread per (column, entry) of the tile
+            const int oj = threadIdx.x / 8, q = threadIdx.x % 8;
+            const int64_t jo = (int64_t)blockIdx.x * kGradCols + oj;
+            if (jo < n && k0 + q < d) {
+                const int bo = Q_idx[jo * d + k0 + q];
+                float g = 0.0f;
+                for (int t = 0; t < kGradSlices; ++t) g += part[t][threadIdx.x];
+                for (int k2 = 0; k2 < d; ++k2) g = fmaf(Q_val[jo * d + k2], M2[(int64_t)Q_idx[jo * d + k2] * r + bo], g);
+                gQ[jo * d + k0 + q] = g;
             }
         }
         __syncthreads();
@@ -150,15 +196,19 @@ size_t fitgrad_workspace_floats(int64_t m, int64_t n, int32_t r) {
 template <typename D>
 static hipError_t launch_gather(const void* G, const uint8_t* plan, float* Y, int64_t m, int64_t n, int32_t r, int32_t d, hipStream_t st) {
     using E = typename D::elem;
-    const unsigned items = (unsigned)plan_max_items(m, r, d);
-    auto tiles = [&](int vec) { return (unsigned)((n + (int64_t)kThreadsY * vec - 1) / ((int64_t)kThreadsY * vec)); };
-    if (D::size == 2 && n % 8 == 0)
-        hipLaunchKernelGGL((k_gather_rows<D, 8>), dim3(items, tiles(8)), dim3(kThreadsY), 0, st, static_cast<const E*>(G), plan, Y, (int)m, (int)n, (int)r, (int)d);
-    else if (D::size == 4 && n % 4 == 0)
-        hipLaunchKernelGGL((k_gather_rows<D, 4>), dim3(items, tiles(4)), dim3(kThreadsY), 0, st, static_cast<const E*>(G), plan, Y, (int)m, (int)n, (int)r, (int)d);
-    else
-        hipLaunchKernelGGL((k_gather_rows<D, 1>), dim3(items, tiles(1)), dim3(kThreadsY), 0, st, static_cast<const E*>(G), plan, Y, (int)m, (int)n, (int)r, (int)d);
-    return hipGetLastError();
+    const int items = (int)plan_max_items(m, r, d);
+    auto launch = [&](auto vec) {
+        constexpr int VEC = decltype(vec)::value;
+        const int tiles = (int)((n + (int64_t)kWave * VEC - 1) / ((int64_t)kWave * VEC));
+        const int64_t grid = (int64_t)items * ((tiles + kXcds - 1) / kXcds) * kXcds;
+        if (grid > INT32_MAX) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((k_gather_rows<D, VEC>), dim3((unsigned)grid), dim3(kThreadsY), 0, st, static_cast<const E*>(G), plan, Y,
+                           (int)m, (int)n, (int)r, (int)d, items, tiles);
+        return hipGetLastError();
+    };
+    // four columns per lane when rows start on the piece's alignment (G itself is 16-byte aligned)
+    if (n % 4 == 0) return launch(std::integral_constant<int, 4>{});
+    return launch(std::integral_constant<int, 1>{});
 }
 
 hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_idx, const float* P_val,
@@ -181,12 +231,15 @@ hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_i
     if ((e = launch_zero(CP, (int64_t)(2 * rr), st)) != hipSuccess) return e;
     if ((e = launch_gram(P_idx, P_val, P_idx, P_val, m, d, r, CP, st)) != hipSuccess) return e;
     if ((e = launch_gram(Q_idx, Q_val, Q_idx, Q_val, n, d, r, CQ, st)) != hipSuccess) return e;
-    // the r x r chain
-    if ((e = launch_gemm_rr(S, CQ, S1, r, false, false, 0.0f, nullptr, st)) != hipSuccess) return e;     // S1 = S C_Q
-    if ((e = launch_gemm_rr(CP, S, X, r, false, false, 0.0f, nullptr, st)) != hipSuccess) return e;      // X  = C_P S
-    if ((e = launch_gemm_rr(CP, S1, Dm, r, false, false, -2.0f, S, st)) != hipSuccess) return e;         // D  = C_P S1 - 2 S
-    if ((e = launch_gemm_rr(S1, S, M1, r, false, true, 0.0f, nullptr, st)) != hipSuccess) return e;      // M1 = S1 S^T
-    if ((e = launch_gemm_rr(S, X, M2, r, true, false, 0.0f, nullptr, st)) != hipSuccess) return e;       // M2 = S^T X
+    // the r x r chain: two launches of independent products
+    GemmBatch first{}, second{};
+    first.p[0] = GemmProblem{S, CQ, S1, nullptr, 0.0f, 0};                                               // S1 = S C_Q
+    first.p[1] = GemmProblem{CP, S, X, nullptr, 0.0f, 0};                                                // X  = C_P S
+    second.p[0] = GemmProblem{CP, S1, Dm, S, -2.0f, 0};                                                  // D  = C_P S1 - 2 S
+    second.p[1] = GemmProblem{S1, S, M1, nullptr, 0.0f, kGemmTB};                                        // M1 = S1 S^T
+    second.p[2] = GemmProblem{S, X, M2, nullptr, 0.0f, kGemmTA};                                         // M2 = S^T X
+    if ((e = launch_gemm_rr_batch(first, 2, r, st)) != hipSuccess) return e;
+    if ((e = launch_gemm_rr_batch(second, 3, r, st)) != hipSuccess) return e;
     // Y = P^T G
     hipLaunchKernelGGL(k_zero_if_split, dim3(1024), dim3(256), 0, st, plan, Y, (int64_t)r * n);
     if ((e = hipGetLastError()) != hipSuccess) return e;

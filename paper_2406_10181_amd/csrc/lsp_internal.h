@@ -230,9 +230,14 @@ size_t     plan_build_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d
 hipError_t launch_plan_build(const int32_t* P_idx, const float* P_val, const int32_t* Q_idx, const float* Q_val,
                              int64_t m, int64_t n, int32_t r, int32_t d, uint8_t* plan, uint8_t* workspace,
                              int32_t* status_out, hipStream_t st);
-// C = op(A) op(B) + beta E on r x r fp32 matrices (matrix cores); ta / tb transpose an operand; E may be null.
-hipError_t launch_gemm_rr(const float* A, const float* B, float* C, int32_t r, bool ta, bool tb,
-                          float beta, const float* E, hipStream_t st);
+// C = op(A) op(B) + beta E on r x r fp32 matrices (matrix cores): up to kMaxGemmBatch independent products of
+// one size in a launch (no product may read what another of the same launch writes).  flags: transpose an
+// operand (not both), square an operand element by element; E may be null.
+constexpr int kMaxGemmBatch = 3;
+constexpr int kGemmTA = 1, kGemmTB = 2, kGemmSqA = 4, kGemmSqB = 8;
+struct GemmProblem { const float* A; const float* B; float* C; const float* E; float beta; int32_t flags; };
+struct GemmBatch { GemmProblem p[kMaxGemmBatch]; };
+hipError_t launch_gemm_rr_batch(const GemmBatch& batch, int count, int32_t r, hipStream_t st);
 // C += L^T R for two ELL matrices with the same number of rows (C must hold zeros or a running sum).
 hipError_t launch_gram(const int32_t* L_idx, const float* L_val, const int32_t* R_idx, const float* R_val,
                        int64_t rows, int32_t d, int32_t r, float* C, hipStream_t st);

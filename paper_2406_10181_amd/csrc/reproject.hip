@@ -6,7 +6,8 @@
 //      row i adds its d x d products val * val' at (idx, idx').  Scatter with fp32 atomics (a few
 //      hundred thousand of them on a 1 MB matrix that stays in L2).
 //   2. four dense r x r products in fp32 on the matrix cores (v_mfma_f32_32x32x2_f32): X = A M,
-//      M = X B, X = (A o A) V, V = X (B o B); the squares are taken while the tiles are staged.
+//      X2 = (A o A) V, then M = X B, V = X2 (B o B); the squares are taken while the tiles are staged,
+//      and the two independent products of each stage share a launch.
 // Runs once per change of projectors; nothing here is on the per-step path.
 #include "lsp_internal.h"
 
@@ -32,51 +33,67 @@ __global__ __launch_bounds__(256) void k_gram(const int32_t* __restrict__ L_idx,
     }
 }
 
-// C = op(A) op(B) + beta E, all r x r row-major fp32; op squares every element (SQ*) or transposes the
-// operand (T*) while its tiles are staged.
+// C = op(A) op(B) + beta E, all r x r row-major fp32; op squares every element (sqa, sqb) or transposes the
+// operand (ta, tb) while its tiles are staged.  A launch takes up to kMaxGemmBatch independent products of
+// one size (blockIdx.z picks one): a product alone is 256 small workgroups at r = 512, one per CU and each a
+// chain of load latencies, so independent products share the chip.
 // A workgroup of four waves makes a 32 x 32 tile of C (many small tiles: r is a few hundred, and
-// every CU should get one).  The K range goes by in 64-wide tiles staged through LDS; inside a
-// tile the four waves take 16 consecutive k each with v_mfma_f32_32x32x2_f32 -- lane l supplies
+// every CU should get one).  The K range goes by in 128-wide tiles staged through LDS; inside a
+// tile the four waves take 32 consecutive k each with v_mfma_f32_32x32x2_f32 -- lane l supplies
 // A[i = l % 32][k = l / 32] and B[k = l / 32][j = l % 32] and holds
 // C[8 (v / 4) + 4 (l / 32) + v % 4][l % 32] in accumulator register v -- and their four partial
 // tiles are added through LDS at the end, in wave order.
-constexpr int kTileMN = 32, kTileK = 64;
+constexpr int kTileMN = 32, kTileK = 128;
 constexpr int kTileElems = kTileMN * kTileK / 256;                  // elements of each tile a thread stages
-template <bool SQA, bool SQB, bool TA, bool TB>
-__global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, const float* __restrict__ B,
-                                                 float* __restrict__ C, int r, float beta, const float* __restrict__ E) {
+__global__ __launch_bounds__(256) void k_gemm_rr(const GemmBatch batch, int r) {
     __shared__ float As[kTileMN][kTileK + 1];
     __shared__ float Bs[kTileK][kTileMN + 1];
     __shared__ float Cs[4][16][64];
+    GemmProblem P = batch.p[0];
+#pragma unroll
+    for (int z = 1; z < kMaxGemmBatch; ++z)
+        if ((int)blockIdx.z == z) P = batch.p[z];
+    const float* __restrict__ A = P.A;
+    const float* __restrict__ B = P.B;
+    const bool ta = P.flags & kGemmTA, tb = P.flags & kGemmTB, sqa = P.flags & kGemmSqA, sqb = P.flags & kGemmSqB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row0 = blockIdx.y * kTileMN, col0 = blockIdx.x * kTileMN;
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    // the next pair of tiles is fetched into registers while the matrix cores work on the current one;
-    // consecutive threads read consecutive addresses whichever way the operand lies in memory
+    // A thread stages elements q = tid + 256 e of each tile; consecutive threads read consecutive addresses
+    // whichever way the operand lies in memory.  Element e sits at (row, k) = (ar + e dar, ak + e dak) of the
+    // A tile and at (k, col) = (bk + e dbk, bc + e dbc) of the B tile: one base and one step per operand.
+    const int ar = ta ? tid % kTileMN : tid / kTileK, ak = ta ? tid / kTileMN : tid % kTileK;
+    const int dar = ta ? 0 : 256 / kTileK, dak = ta ? 256 / kTileMN : 0;
+    const int bk = tb ? tid % kTileK : tid / kTileMN, bc = tb ? tid / kTileK : tid % kTileMN;
+    const int dbk = tb ? 0 : 256 / kTileMN, dbc = tb ? 256 / kTileK : 0;
+    const int a_off = ta ? ak * r + row0 + ar : (row0 + ar) * r + ak;      // r * r < 2^31
+    const int a_step = ta ? dak * r : dar * r, a_kstep = ta ? r : 1;
+    const int b_off = tb ? (col0 + bc) * r + bk : bk * r + col0 + bc;
+    const int b_step = tb ? dbc * r : dbk * r, b_kstep = tb ? 1 : r;
+    float* const as0 = &As[0][0] + ar * (kTileK + 1) + ak;
+    float* const bs0 = &Bs[0][0] + bk * (kTileMN + 1) + bc;
+    const int as_step = dar * (kTileK + 1) + dak, bs_step = dbk * (kTileMN + 1) + dbc;
+    // the next pair of tiles is fetched into registers while the matrix cores work on the current one
     float an[kTileElems], bn[kTileElems];
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int e = 0; e < kTileElems; ++e) {
-            const int q = tid + e * 256;
-            const int ar = TA ? q % kTileMN : q / kTileK, ak = TA ? q / kTileMN : q % kTileK;
-            const bool aok = row0 + ar < r && k0 + ak < r;
-            const float a = !aok ? 0.0f : TA ? A[(int64_t)(k0 + ak) * r + row0 + ar] : A[(int64_t)(row0 + ar) * r + k0 + ak];
-            an[e] = SQA ? a * a : a;
-            const int bk = TB ? q % kTileK : q / kTileMN, bc = TB ? q / kTileK : q % kTileMN;
-            const bool bok = k0 + bk < r && col0 + bc < r;
-            const float b = !bok ? 0.0f : TB ? B[(int64_t)(col0 + bc) * r + k0 + bk] : B[(int64_t)(k0 + bk) * r + col0 + bc];
-            bn[e] = SQB ? b * b : b;
+            const bool aok = row0 + ar + e * dar < r && k0 + ak + e * dak < r;
+            const float a = aok ? A[a_off + e * a_step + k0 * a_kstep] : 0.0f;
+            an[e] = sqa ? a * a : a;
+            const bool bok = k0 + bk + e * dbk < r && col0 + bc + e * dbc < r;
+            const float b = bok ? B[b_off + e * b_step + k0 * b_kstep] : 0.0f;
+            bn[e] = sqb ? b * b : b;
         }
     };
     fetch(0);
     for (int k0 = 0; k0 < r; k0 += kTileK) {
 #pragma unroll
         for (int e = 0; e < kTileElems; ++e) {
-            const int q = tid + e * 256;
-            As[TA ? q % kTileMN : q / kTileK][TA ? q / kTileMN : q % kTileK] = an[e];
-            Bs[TB ? q % kTileK : q / kTileMN][TB ? q / kTileK : q % kTileMN] = bn[e];
+            as0[e * as_step] = an[e];
+            bs0[e * bs_step] = bn[e];
         }
         __syncthreads();
         if (k0 + kTileK < r) fetch(k0 + kTileK);
@@ -96,8 +113,104 @@ __global__ __launch_bounds__(256) void k_gemm_rr(const float* __restrict__ A, co
             const int i = row0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             float sum = ((Cs[0][v][lane] + Cs[1][v][lane]) + Cs[2][v][lane]) + Cs[3][v][lane];
             if (i < r && j < r) {
-                if (E) sum = fmaf(beta, E[(int64_t)i * r + j], sum);
-                C[(int64_t)i * r + j] = sum;
+                if (P.E) sum = fmaf(P.beta, P.E[(int64_t)i * r + j], sum);
+                P.C[(int64_t)i * r + j] = sum;
+            }
+        }
+    }
+}
+
+// The same product for r % 4 == 0, which is what the training configurations use: everything moves in groups
+// of four floats.  Both tiles lie in LDS with k running along the rows (As[i][k], Bs[j][k], rows padded by 16
+// bytes); a thread fetches 4 + 4 groups of 16 bytes per K tile -- four consecutive k of one row where the operand
+// has k contiguous in memory (A as it is, B transposed: one 16-byte LDS store), else four consecutive rows of
+// one k (four 4-byte LDS stores).  Within 8 consecutive k the lanes of half h = l / 32 take k = 4 h .. 4 h + 3
+// with one 16-byte LDS load per operand, and the matrix instruction number s of the group multiplies element s of
+// both: it sums over k = s and k = 4 + s, and the four of them over all eight.
+constexpr int kTileRow4 = kTileK + 4;                               // floats per LDS row
+constexpr int kTileGroups = kTileMN * kTileK / 4 / 256;             // 16-byte groups of each tile a thread stages
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void k_gemm_rr4(const GemmBatch batch, int r) {
+    __shared__ __align__(16) float As[kTileMN * kTileRow4];
+    __shared__ __align__(16) float Bs[kTileMN * kTileRow4];
+    __shared__ float Cs[4][16][64];
+    GemmProblem P = batch.p[0];
+#pragma unroll
+    for (int z = 1; z < kMaxGemmBatch; ++z)
+        if ((int)blockIdx.z == z) P = batch.p[z];
+    const float* __restrict__ A = P.A;
+    const float* __restrict__ B = P.B;
+    const bool ta = P.flags & kGemmTA, tb = P.flags & kGemmTB, sqa = P.flags & kGemmSqA, sqb = P.flags & kGemmSqB;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row0 = blockIdx.y * kTileMN, col0 = blockIdx.x * kTileMN;
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    // Group q = tid + 256 e of a tile.  k contiguous in memory: row q / 32, k = 4 (q % 32) .. + 3 (rows step by 8
+    // with e).  Rows contiguous in memory: k = q / 8, rows 4 (q % 8) .. + 3 (k steps by 32 with e).
+    const bool a_kc = !ta, b_kc = tb;
+    const int a_mn = a_kc ? tid / 32 : 4 * (tid % 8), a_k = a_kc ? 4 * (tid % 32) : tid / 8;
+    const int b_mn = b_kc ? tid / 32 : 4 * (tid % 8), b_k = b_kc ? 4 * (tid % 32) : tid / 8;
+    const int a_off = a_kc ? (row0 + a_mn) * r + a_k : a_k * r + row0 + a_mn;    // r * r < 2^31
+    const int b_off = b_kc ? (col0 + b_mn) * r + b_k : b_k * r + col0 + b_mn;
+    const int a_step = (a_kc ? 8 : 32) * r, b_step = (b_kc ? 8 : 32) * r;
+    const int a_kstep = a_kc ? 1 : r, b_kstep = b_kc ? 1 : r;
+    float* const as0 = As + a_mn * kTileRow4 + a_k;
+    float* const bs0 = Bs + b_mn * kTileRow4 + b_k;
+    const int as_step = a_kc ? 8 * kTileRow4 : 32, bs_step = b_kc ? 8 * kTileRow4 : 32;
+    f32x4 an[kTileGroups], bn[kTileGroups];
+    const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int e = 0; e < kTileGroups; ++e) {
+            const bool aok = row0 + a_mn + (a_kc ? 8 * e : 0) < r && k0 + a_k + (a_kc ? 0 : 32 * e) < r;
+            const f32x4 a = aok ? *reinterpret_cast<const f32x4*>(A + a_off + e * a_step + k0 * a_kstep) : zero4;
+            an[e] = sqa ? a * a : a;
+            const bool bok = col0 + b_mn + (b_kc ? 8 * e : 0) < r && k0 + b_k + (b_kc ? 0 : 32 * e) < r;
+            const f32x4 b = bok ? *reinterpret_cast<const f32x4*>(B + b_off + e * b_step + k0 * b_kstep) : zero4;
+            bn[e] = sqb ? b * b : b;
+        }
+    };
+    fetch(0);
+    const float* ap = As + (lane & 31) * kTileRow4 + wave * (kTileK / 4) + 4 * (lane >> 5);
+    const float* bp = Bs + (lane & 31) * kTileRow4 + wave * (kTileK / 4) + 4 * (lane >> 5);
+    for (int k0 = 0; k0 < r; k0 += kTileK) {
+#pragma unroll
+        for (int e = 0; e < kTileGroups; ++e) {
+            if (a_kc) *reinterpret_cast<f32x4*>(as0 + e * as_step) = an[e];
+            else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) as0[e * as_step + s * kTileRow4] = an[e][s];
+            }
+            if (b_kc) *reinterpret_cast<f32x4*>(bs0 + e * bs_step) = bn[e];
+            else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) bs0[e * bs_step + s * kTileRow4] = bn[e][s];
+            }
+        }
+        __syncthreads();
+        if (k0 + kTileK < r) fetch(k0 + kTileK);
+#pragma unroll
+        for (int g = 0; g < kTileK / 4 / 8; ++g) {                  // a wave's quarter of the tile, 8 k at a time
+            const f32x4 a = *reinterpret_cast<const f32x4*>(ap + 8 * g);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(bp + 8 * g);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[s], acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) Cs[wave][v][lane] = acc[v];
+    __syncthreads();
+    if (wave == 0) {
+        const int j = col0 + (lane & 31);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = row0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            float sum = ((Cs[0][v][lane] + Cs[1][v][lane]) + Cs[2][v][lane]) + Cs[3][v][lane];
+            if (i < r && j < r) {
+                if (P.E) sum = fmaf(P.beta, P.E[(int64_t)i * r + j], sum);
+                P.C[(int64_t)i * r + j] = sum;
             }
         }
     }
@@ -116,13 +229,16 @@ hipError_t launch_gram(const int32_t* L_idx, const float* L_val, const int32_t* 
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_rr(const float* A, const float* B, float* C, int32_t r, bool ta, bool tb,
-                          float beta, const float* E, hipStream_t st) {
-    const dim3 grid((unsigned)((r + kTileMN - 1) / kTileMN), (unsigned)((r + kTileMN - 1) / kTileMN));
-    if (ta && tb) return hipErrorInvalidValue;                       // not needed anywhere
-    if (ta)      hipLaunchKernelGGL((k_gemm_rr<false, false, true, false>), grid, dim3(256), 0, st, A, B, C, (int)r, beta, E);
-    else if (tb) hipLaunchKernelGGL((k_gemm_rr<false, false, false, true>), grid, dim3(256), 0, st, A, B, C, (int)r, beta, E);
-    else         hipLaunchKernelGGL((k_gemm_rr<false, false, false, false>), grid, dim3(256), 0, st, A, B, C, (int)r, beta, E);
+hipError_t launch_gemm_rr_batch(const GemmBatch& batch, int count, int32_t r, hipStream_t st) {
+    if (count < 1 || count > kMaxGemmBatch) return hipErrorInvalidValue;
+    for (int z = 0; z < count; ++z)
+        if ((batch.p[z].flags & kGemmTA) && (batch.p[z].flags & kGemmTB)) return hipErrorInvalidValue;   // not needed anywhere
+    const dim3 grid((unsigned)((r + kTileMN - 1) / kTileMN), (unsigned)((r + kTileMN - 1) / kTileMN), (unsigned)count);
+    bool by16 = r % 4 == 0;                                          // the 16-byte path: whole groups, aligned operands
+    for (int z = 0; z < count; ++z)
+        by16 = by16 && reinterpret_cast<uintptr_t>(batch.p[z].A) % 16 == 0 && reinterpret_cast<uintptr_t>(batch.p[z].B) % 16 == 0;
+    if (by16) hipLaunchKernelGGL(k_gemm_rr4, grid, dim3(256), 0, st, batch, (int)r);
+    else      hipLaunchKernelGGL(k_gemm_rr, grid, dim3(256), 0, st, batch, (int)r);
     return hipGetLastError();
 }
 
@@ -137,15 +253,17 @@ hipError_t launch_reproject(const int32_t* P_idx, const float* P_val, const int3
     hipLaunchKernelGGL(k_zero, blocks_for(2 * rr), dim3(256), 0, st, A, 2 * rr);
     hipLaunchKernelGGL(k_gram, blocks_for(m * d * d), dim3(256), 0, st, P_idx, P_val, Pp_idx, Pp_val, m, (int)d, (int)r, A);
     hipLaunchKernelGGL(k_gram, blocks_for(n * d * d), dim3(256), 0, st, Qp_idx, Qp_val, Q_idx, Q_val, n, (int)d, (int)r, B);
-    const dim3 grid((unsigned)((r + kTileMN - 1) / kTileMN), (unsigned)((r + kTileMN - 1) / kTileMN));
-    const float* none = nullptr;
-    hipLaunchKernelGGL((k_gemm_rr<false, false, false, false>), grid, dim3(256), 0, st, A, M, X, (int)r, 0.0f, none);
-    hipLaunchKernelGGL((k_gemm_rr<false, false, false, false>), grid, dim3(256), 0, st, X, B, M, (int)r, 0.0f, none);
-    if (V) {
-        hipLaunchKernelGGL((k_gemm_rr<true, false, false, false>), grid, dim3(256), 0, st, A, V, X, (int)r, 0.0f, none);
-        hipLaunchKernelGGL((k_gemm_rr<false, true, false, false>), grid, dim3(256), 0, st, X, B, V, (int)r, 0.0f, none);
-    }
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // X = A M and X2 = (A o A) V in one launch, then M = X B and V = X2 (B o B) in another
+    float* X2 = workspace + 3 * rr;
+    GemmBatch left{}, right{};
+    left.p[0] = GemmProblem{A, M, X, nullptr, 0.0f, 0};
+    left.p[1] = GemmProblem{A, V, X2, nullptr, 0.0f, kGemmSqA};
+    right.p[0] = GemmProblem{X, B, M, nullptr, 0.0f, 0};
+    right.p[1] = GemmProblem{X2, B, V, nullptr, 0.0f, kGemmSqB};
+    if ((e = launch_gemm_rr_batch(left, V ? 2 : 1, r, st)) != hipSuccess) return e;
+    return launch_gemm_rr_batch(right, V ? 2 : 1, r, st);
 }
 
 }  // namespace lsp

@@ -49,6 +49,7 @@ def _check_gradient(pb, tol=GRAD_TOL):
     (64, 2048, 96, 4, "bf16", "zipf"),           # duplicates inside rows, shared columns
     (2000, 64, 4, 2, "f32", "uniform"),          # rows of P^T cut into pieces: the atomic path of the row gather
     (96, 1024, 1100, 2, "bf16", "uniform"),      # more subspace columns than lanes
+    (150, 264, 50, 3, "f32", "uniform"),         # r % 4 != 0: the element-wise path of the r x r products, all operand forms
 ])
 def test_bias_gradient_against_oracle(m, n, r, d, dtype, dist):
     _check_gradient(syn.make_problem("grad", m, n, r, d, dtype, seed=5100 + m + n, g_std=1.0, index_dist=dist))
