@@ -386,12 +386,12 @@ def main():
                             "frac_of_hbm_peak": round(bbytes / (ms_bias * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                             "avg_call_us": round(ms_bias * 1e3 / nlaunch, 2)},
         # once per change of projectors: 4 dense r x r x r products on the matrix cores (fp32) + 2 sparse-sparse ones
-        "reproject_state": {"kernel": "k_gram x2 + k_gemm_rr x4 (one lsp_reproject_state call, 4096 x 4096, r=512, d=8)",
+        "reproject_state": {"kernel": "k_gram (both pairs) + k_gemm_rr4 x2, two products each (one lsp_reproject_state call, 4096 x 4096, r=512, d=8)",
                             "us_per_call": round(ms_rep * 1e3, 1), "bound": "mfma", "dense_flop": 8 * r ** 3,
                             "TFLOP/s": round(8 * r ** 3 / (ms_rep * 1e-3) / 1e12, 2), "peak_fp32_TFLOP/s": 157.3},
         # one fitting iteration on a 4096 x 4096 matrix: values-only plan refresh + gradient of the bias loss (G is
         # streamed twice: 2 x 33.6 MB algorithmic)
-        "fitting_gradient": {"kernel": "k_plan_refresh + compress kernels + k_gram x2 + k_gemm_rr x5 + k_gather_rows + k_grad_left/right "
+        "fitting_gradient": {"kernel": "k_plan_refresh + compress kernels + k_gram + k_gemm_rr4 x2 (five products) + k_gather_rows + k_grad_left/right "
                                        "(lsp_plan_refresh_values + lsp_bias_gradient, 4096 x 4096, r=512, d=8)",
                              "us_per_iteration": round(ms_fit * 1e3, 1), "plan_refresh_us": round(ms_refresh * 1e3, 1),
                              "GB/s_on_two_reads_of_G": round(2 * 4096 * 4096 * sz / (ms_fit * 1e-3) / 1e9, 1)},

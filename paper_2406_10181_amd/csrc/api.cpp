@@ -353,7 +353,7 @@ int lsp_plan_refresh_values(void* plan, const float* P_val, const float* Q_val,
 
 size_t lsp_bias_gradient_workspace_bytes(int64_t m, int64_t n, int32_t r, int32_t d) {
     if (check_shape(m, n, r, d) != LSP_OK) return 0;
-    return lsp::align_up(lsp::fitgrad_workspace_floats(m, n, r) * sizeof(float), 256);
+    return lsp::align_up(lsp::fitgrad_workspace_floats(m, n, r, d) * sizeof(float), 256);
 }
 
 int lsp_bias_gradient(const void* G, const void* plan,

@@ -12,6 +12,7 @@
 // G is streamed twice: once by the compress kernels (T and S, as in every training step) and once, row by
 // row through the column-sorted copy of P in the plan, for Y.  The dense r x r products run in fp32 on the
 // matrix cores; the rest is gathers and fp32 dot products.  No m x n temporary exists.
+#include <algorithm>
 #include <cstring>
 #include <type_traits>
 
@@ -142,55 +143,58 @@ __global__ __launch_bounds__(256) void k_grad_left(const float* __restrict__ T, 
     }
 }
 
-// gQ[j][k] = sum_k' Q_val[j][k'] M2[Q_idx[j][k']][b] + sum_a Y[a][j] D[a][b],  b = Q_idx[j][k]: a workgroup takes
-// 16 columns j (the reads of Y are then contiguous) and cuts the sum over a into 64 interleaved slices, one per
-// group of 16 threads (every term is a gather whose latency only more threads hide); the slices' sums meet in LDS
-// and are added in slice order.  Eight entries of a row at a time.
-constexpr int kGradCols = 16, kGradSlices = 64;
-__global__ __launch_bounds__(kGradCols * kGradSlices) void k_grad_right(const float* __restrict__ Y, const float* __restrict__ Dm, const float* __restrict__ M2,
-                                                                      const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
-                                                                      int n, int r, int d, float* __restrict__ gQ) {
-    __shared__ float part[kGradSlices][kGradCols * 8 + 1];
-    const int jl = threadIdx.x % kGradCols, sl = threadIdx.x / kGradCols;
-    const int64_t j = (int64_t)blockIdx.x * kGradCols + jl;
-    const int64_t jc = j < n ? j : (int64_t)n - 1;
-    for (int k0 = 0; k0 < d; k0 += 8) {
-        int b[8];
-        float acc[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            b[q] = k0 + q < d ? Q_idx[jc * d + k0 + q] : 0;
-            acc[q] = 0.0f;
-        }
-#pragma unroll 4
-        for (int a = sl; a < r; a += kGradSlices) {
-            const float y = Y[(int64_t)a * n + jc];
-            const float* Da = Dm + (int64_t)a * r;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] = fmaf(y, Da[b[q]], acc[q]);
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) part[sl][jl * 8 + q] = acc[q];
-        __syncthreads();
-        if (threadIdx.x < kGradCols * 8) {                          // one thread per (column, entry) of the tile
-            const int oj = threadIdx.x / 8, q = threadIdx.x % 8;
-            const int64_t jo = (int64_t)blockIdx.x * kGradCols + oj;
-            if (jo < n && k0 + q < d) {
-                const int bo = Q_idx[jo * d + k0 + q];
-                float g = 0.0f;
-                for (int t = 0; t < kGradSlices; ++t) g += part[t][threadIdx.x];
-                for (int k2 = 0; k2 < d; ++k2) g = fmaf(Q_val[jo * d + k2], M2[(int64_t)Q_idx[jo * d + k2] * r + bo], g);
-                gQ[jo * d + k0 + q] = g;
+// gQ[j][k] = sum_k' Q_val[j][k'] M2[Q_idx[j][k']][b] + sum_a Y[a][j] D[a][b],  b = Q_idx[j][k].  The second sum
+// gathers one element of every row of D per (j, k): from memory that is one cache line per term.  So a workgroup
+// takes 128 columns j and a slice of the range of a, brings the rows of D of that slice (and the matching piece
+// of Y) through LDS a few rows at a time, and every thread gathers from LDS: thread (j, g) owns entry k = k0 + g
+// of column j, eight entries of a column at a time.  Each slice leaves its sums in a list of its own (the terms
+// of the first sum are dealt over the slices as well), and k_grad_right_finish adds the lists in slice order.
+constexpr int kGradCols = 128, kGradEnt = 8, kGradThreads = kGradCols * kGradEnt;
+constexpr int kGradLdsFloats = 8192;                                // rows of D staged at a time: kGradLdsFloats / r, at most 16
+constexpr int kGradMaxRows = 16, kGradMaxSlices = 16;
+__global__ __launch_bounds__(kGradThreads) void k_grad_right(const float* __restrict__ Y, const float* __restrict__ Dm, const float* __restrict__ M2,
+                                                           const int32_t* __restrict__ Q_idx, const float* __restrict__ Q_val,
+                                                           int n, int r, int d, int rows, int a_per_slice, float* __restrict__ part) {
+    __shared__ float Ds[kGradLdsFloats];
+    __shared__ float Ys[kGradMaxRows][kGradCols];
+    const int jl = threadIdx.x % kGradCols, g = threadIdx.x / kGradCols;
+    const int64_t j0 = (int64_t)blockIdx.x * kGradCols, j = j0 + jl;
+    const int a_begin = blockIdx.y * a_per_slice, a_end = min(r, a_begin + a_per_slice);
+    for (int k0 = 0; k0 < d; k0 += kGradEnt) {
+        const bool mine = j < n && k0 + g < d;
+        const int b = mine ? Q_idx[j * d + k0 + g] : 0;
+        float acc = 0.0f;
+        for (int a0 = a_begin; a0 < a_end; a0 += rows) {
+            const int here = min(rows, a_end - a0);
+            __syncthreads();                                        // the previous rows have been used
+            for (int q = threadIdx.x; q < here * r; q += kGradThreads) Ds[q] = Dm[(int64_t)a0 * r + q];
+            for (int q = threadIdx.x; q < here * kGradCols; q += kGradThreads) {
+                const int64_t jj = j0 + q % kGradCols;
+                Ys[q / kGradCols][q % kGradCols] = jj < n ? Y[(int64_t)(a0 + q / kGradCols) * n + jj] : 0.0f;
             }
+            __syncthreads();
+            for (int t = 0; t < here; ++t) acc = fmaf(Ys[t][jl], Ds[t * r + b], acc);
         }
-        __syncthreads();
+        if (mine) {
+            for (int k2 = blockIdx.y; k2 < d; k2 += gridDim.y)      // the terms of the first sum, dealt over the slices
+                acc = fmaf(Q_val[j * d + k2], M2[(int64_t)Q_idx[j * d + k2] * r + b], acc);
+            part[(int64_t)blockIdx.y * n * d + j * d + k0 + g] = acc;
+        }
     }
 }
 
-// floats of workspace: T (m r) | S, C_P, C_Q, S1, X, D, M1, M2 (8 r^2) | Y (r n)
-size_t fitgrad_workspace_floats(int64_t m, int64_t n, int32_t r) {
+__global__ __launch_bounds__(256) void k_grad_right_finish(const float* __restrict__ part, float* __restrict__ gQ, int64_t count, int slices) {
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < count; k += (int64_t)gridDim.x * 256) {
+        float s = part[k];
+        for (int q = 1; q < slices; ++q) s += part[(int64_t)q * count + k];
+        gQ[k] = s;
+    }
+}
+
+// floats of workspace: T (m r) | S, C_P, C_Q, S1, X, D, M1, M2 (8 r^2) | Y (r n) | the slices' lists of gQ
+size_t fitgrad_workspace_floats(int64_t m, int64_t n, int32_t r, int32_t d) {
     const size_t rr = (size_t)r * (size_t)r;
-    return align_up((size_t)m * r, 64) + 8 * align_up(rr, 64) + align_up((size_t)r * (size_t)n, 64);
+    return align_up((size_t)m * r, 64) + 8 * align_up(rr, 64) + align_up((size_t)r * (size_t)n, 64) + (size_t)kGradMaxSlices * (size_t)n * d;
 }
 
 template <typename D>
@@ -220,6 +224,7 @@ hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_i
     float* CP = S + rr; float* CQ = CP + rr; float* S1 = CQ + rr; float* X = S1 + rr;
     float* Dm = X + rr; float* M1 = Dm + rr; float* M2 = M1 + rr;
     float* Y = M2 + rr;
+    float* gq_part = Y + align_up((size_t)r * (size_t)n, 64);
     hipError_t e;
     // T = G Q and S = P^T T: the compress kernels (a plan of another problem leaves S full of NaN, which then
     // reaches every output)
@@ -227,10 +232,11 @@ hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_i
     memset(&g, 0, sizeof(g));
     g.count = 1; g.G[0] = G; g.plan[0] = plan; g.T[0] = T; g.S[0] = S; g.m[0] = (int32_t)m; g.n[0] = (int32_t)n;
     if ((e = launch_compress_planned(g, r, d, dtype, st)) != hipSuccess) return e;
-    // C_P = P^T P, C_Q = Q^T Q (adjacent: one clearing pass)
-    if ((e = launch_zero(CP, (int64_t)(2 * rr), st)) != hipSuccess) return e;
-    if ((e = launch_gram(P_idx, P_val, P_idx, P_val, m, d, r, CP, st)) != hipSuccess) return e;
-    if ((e = launch_gram(Q_idx, Q_val, Q_idx, Q_val, n, d, r, CQ, st)) != hipSuccess) return e;
+    // C_P = P^T P, C_Q = Q^T Q
+    GramBatch grams{};
+    grams.p[0] = GramPair{P_idx, P_val, P_idx, P_val, m, CP};
+    grams.p[1] = GramPair{Q_idx, Q_val, Q_idx, Q_val, n, CQ};
+    if ((e = launch_gram(grams, 2, d, r, st)) != hipSuccess) return e;
     // the r x r chain: two launches of independent products
     GemmBatch first{}, second{};
     first.p[0] = GemmProblem{S, CQ, S1, nullptr, 0.0f, 0};                                               // S1 = S C_Q
@@ -251,7 +257,17 @@ hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_i
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_grad_left, dim3((unsigned)((m + 3) / 4)), dim3(256), 0, st, T, Dm, M1, P_idx, P_val, (int)m, (int)r, (int)d, gP);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(k_grad_right, dim3((unsigned)((n + kGradCols - 1) / kGradCols)), dim3(kGradCols * kGradSlices), 0, st, Y, Dm, M2, Q_idx, Q_val, (int)n, (int)r, (int)d, gQ);
+    // enough slices of the range of a for two workgroups per CU, each a whole number of LDS loads
+    const int rows = std::max(1, std::min(kGradMaxRows, kGradLdsFloats / (int)r));
+    const int colblocks = (int)((n + kGradCols - 1) / kGradCols);
+    const int want = std::max(1, std::min({(512 + colblocks - 1) / colblocks, ((int)r + rows - 1) / rows, kGradMaxSlices}));
+    const int a_per_slice = (((int)r + want - 1) / want + rows - 1) / rows * rows;
+    const int slices = ((int)r + a_per_slice - 1) / a_per_slice;
+    hipLaunchKernelGGL(k_grad_right, dim3((unsigned)colblocks, (unsigned)slices), dim3(kGradThreads), 0, st, Y, Dm, M2, Q_idx, Q_val,
+                       (int)n, (int)r, (int)d, rows, a_per_slice, gq_part);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int64_t count = n * d;
+    hipLaunchKernelGGL(k_grad_right_finish, dim3((unsigned)std::min<int64_t>((count + 255) / 256, 2048)), dim3(256), 0, st, gq_part, gQ, count, slices);
     return hipGetLastError();
 }
 

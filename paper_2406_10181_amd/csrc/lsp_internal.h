@@ -238,12 +238,14 @@ constexpr int kGemmTA = 1, kGemmTB = 2, kGemmSqA = 4, kGemmSqB = 8;
 struct GemmProblem { const float* A; const float* B; float* C; const float* E; float beta; int32_t flags; };
 struct GemmBatch { GemmProblem p[kMaxGemmBatch]; };
 hipError_t launch_gemm_rr_batch(const GemmBatch& batch, int count, int32_t r, hipStream_t st);
-// C += L^T R for two ELL matrices with the same number of rows (C must hold zeros or a running sum).
-hipError_t launch_gram(const int32_t* L_idx, const float* L_val, const int32_t* R_idx, const float* R_val,
-                       int64_t rows, int32_t d, int32_t r, float* C, hipStream_t st);
+// C = L^T R (r x r, overwritten) for two ELL matrices with the same number of rows; one or two independent
+// pairs per launch.
+struct GramPair { const int32_t* L_idx; const float* L_val; const int32_t* R_idx; const float* R_val; int64_t rows; float* C; };
+struct GramBatch { GramPair p[2]; };
+hipError_t launch_gram(const GramBatch& batch, int count, int32_t d, int32_t r, hipStream_t st);
 hipError_t launch_zero(float* p, int64_t count, hipStream_t st);
 // Gradient of 1/2 ||P P^T G Q Q^T - G||_F^2 with respect to the stored projector values (fitgrad.hip).
-size_t     fitgrad_workspace_floats(int64_t m, int64_t n, int32_t r);
+size_t     fitgrad_workspace_floats(int64_t m, int64_t n, int32_t r, int32_t d);
 hipError_t launch_fitgrad(const void* G, const uint8_t* plan, const int32_t* P_idx, const float* P_val,
                           const int32_t* Q_idx, const float* Q_val, int64_t m, int64_t n, int32_t r, int32_t d,
                           float* gP, float* gQ, float* workspace, lsp_dtype dtype, hipStream_t st);

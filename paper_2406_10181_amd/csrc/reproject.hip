@@ -3,34 +3,103 @@
 //     M <- (P^T P_prev) M (Q_prev^T Q),      V <- (P^T P_prev)^2 V (Q_prev^T Q)^2,
 // the squares taken element by element.  Two steps:
 //   1. A = P^T P_prev and B = Q_prev^T Q, r x r: products of two ELL matrices with the same rows;
-//      row i adds its d x d products val * val' at (idx, idx').  Scatter with fp32 atomics (a few
-//      hundred thousand of them on a 1 MB matrix that stays in L2).
+//      row i adds its d x d products val * val' at (idx, idx'), with fp32 atomics in LDS on a block
+//      of rows of the result that a workgroup owns.
 //   2. four dense r x r products in fp32 on the matrix cores (v_mfma_f32_32x32x2_f32): X = A M,
 //      X2 = (A o A) V, then M = X B, V = X2 (B o B); the squares are taken while the tiles are staged,
 //      and the two independent products of each stage share a launch.
 // Runs once per change of projectors; nothing here is on the per-step path.
+#include <algorithm>
+
 #include "lsp_internal.h"
 
 namespace lsp {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-__global__ __launch_bounds__(256) void k_zero(float* __restrict__ p, int64_t count) {
-    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < count; k += (int64_t)gridDim.x * 256) p[k] = 0.0f;
+// C = L^T R for two ELL matrices with the same rows: C[L_idx[i][k]][R_idx[i][k']] += L_val[i][k] * R_val[i][k'].
+// Global fp32 atomics are slow here (they go past the per-XCD L2), so a workgroup owns a block of rows of C
+// in LDS.  It scans the column index of every entry (i, k) of L and queues, in LDS, those that fall in its
+// block; then one thread per (queued entry, k') adds the product with an LDS atomic; then the block is
+// written (C needs no clearing).  Scanning and adding are separate so that neither is a chain of dependent
+// loads.  An entry that finds the queue full is added by the thread that found it (correct, slow: only
+// heavily skewed projectors get there).  blockIdx.y picks one of two independent pairs.  Entries with an
+// index outside [0, r) are skipped.  The order of the LDS additions varies: results can differ in the last
+// bits from run to run.
+constexpr int kGramThreads = 1024, kGramAccFloats = 12288, kGramQueue = 4096, kGramInFlight = 8;
+__global__ __launch_bounds__(kGramThreads) void k_gram(const GramBatch batch, int d, int r, int block_rows) {
+    __shared__ float acc[kGramAccFloats];
+    __shared__ int queue[kGramQueue];
+    __shared__ int queued;
+    GramPair P = batch.p[0];
+    if (blockIdx.y == 1) P = batch.p[1];
+    const int a0 = blockIdx.x * block_rows, a1 = min(r, a0 + block_rows);
+    const int mine = (a1 - a0) * r;
+    const int lane = threadIdx.x & 63;
+    for (int q = threadIdx.x; q < mine; q += kGramThreads) acc[q] = 0.0f;
+    if (threadIdx.x == 0) queued = 0;
+    __syncthreads();
+    auto add_entry = [&](int t, int a, int k2) {
+        const float v = P.L_val[t];
+        const int row = t / d * d;
+        const int b = P.R_idx[row + k2];
+        const float x = P.R_val[row + k2];
+        if (v != 0.0f && (unsigned)b < (unsigned)r) atomicAdd(&acc[(a - a0) * r + b], v * x);
+    };
+    const int total = (int)(P.rows * d);                            // < 2^31, checked by the host
+    for (int t0 = 0; t0 < total; t0 += kGramThreads * kGramInFlight) {       // uniform trip count: the ballots need whole waves
+        int a[kGramInFlight];
+#pragma unroll
+        for (int u = 0; u < kGramInFlight; ++u) {
+            const int t = t0 + u * kGramThreads + (int)threadIdx.x;
+            a[u] = t < total ? P.L_idx[t] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kGramInFlight; ++u) {
+            const bool hit = a[u] >= a0 && a[u] < a1;
+            const uint64_t mask = __ballot(hit);
+            if (mask == 0) continue;
+            int base = 0;
+            if (lane == __ffsll((long long)mask) - 1) base = atomicAdd(&queued, __popcll(mask));
+            base = __shfl(base, __ffsll((long long)mask) - 1);
+            if (hit) {
+                const int t = t0 + u * kGramThreads + (int)threadIdx.x;
+                const int slot = base + __popcll(mask & ((1ull << lane) - 1));
+                if (slot < kGramQueue) queue[slot] = t;
+                else
+                    for (int k2 = 0; k2 < d; ++k2) add_entry(t, a[u], k2);
+            }
+        }
+    }
+    __syncthreads();
+    const int work = min(queued, kGramQueue) * d;
+    for (int w0 = threadIdx.x; w0 < work; w0 += kGramThreads * kGramInFlight) {
+        // every load of a batch is issued before the first addition: otherwise each item waits for its own
+        int t[kGramInFlight], a[kGramInFlight], b[kGramInFlight];
+        float v[kGramInFlight], x[kGramInFlight];
+#pragma unroll
+        for (int u = 0; u < kGramInFlight; ++u) {
+            const int w = w0 + u * kGramThreads;
+            t[u] = w < work ? queue[w / d] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kGramInFlight; ++u) {
+            const int tt = max(t[u], 0), k2 = (w0 + u * kGramThreads) % d;
+            a[u] = P.L_idx[tt];
+            v[u] = P.L_val[tt];
+            b[u] = P.R_idx[tt / d * d + k2];
+            x[u] = P.R_val[tt / d * d + k2];
+        }
+#pragma unroll
+        for (int u = 0; u < kGramInFlight; ++u)
+            if (t[u] >= 0 && v[u] != 0.0f && (unsigned)b[u] < (unsigned)r) atomicAdd(&acc[(a[u] - a0) * r + b[u]], v[u] * x[u]);
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < mine; q += kGramThreads) P.C[(int64_t)a0 * r + q] = acc[q];
 }
 
-// C[L_idx[i][k]][R_idx[i][k']] += L_val[i][k] * R_val[i][k']  for all rows i: C = L^T R.
-// One thread per (row, k, k').
-__global__ __launch_bounds__(256) void k_gram(const int32_t* __restrict__ L_idx, const float* __restrict__ L_val,
-                                              const int32_t* __restrict__ R_idx, const float* __restrict__ R_val,
-                                              int64_t rows, int d, int r, float* __restrict__ C) {
-    const int64_t total = rows * d * d;
-    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
-        const int64_t i = t / (d * d);
-        const int k = (int)(t - i * d * d) / d, k2 = (int)(t - i * d * d) % d;
-        const float v = L_val[i * d + k] * R_val[i * d + k2];
-        if (v != 0.0f) atomicAdd(&C[(int64_t)L_idx[i * d + k] * r + R_idx[i * d + k2]], v);
-    }
+__global__ __launch_bounds__(256) void k_zero(float* __restrict__ p, int64_t count) {
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < count; k += (int64_t)gridDim.x * 256) p[k] = 0.0f;
 }
 
 // C = op(A) op(B) + beta E, all r x r row-major fp32; op squares every element (sqa, sqb) or transposes the
@@ -223,9 +292,15 @@ hipError_t launch_zero(float* p, int64_t count, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_gram(const int32_t* L_idx, const float* L_val, const int32_t* R_idx, const float* R_val,
-                       int64_t rows, int32_t d, int32_t r, float* C, hipStream_t st) {
-    hipLaunchKernelGGL(k_gram, blocks_for(rows * d * d), dim3(256), 0, st, L_idx, L_val, R_idx, R_val, rows, (int)d, (int)r, C);
+hipError_t launch_gram(const GramBatch& batch, int count, int32_t d, int32_t r, hipStream_t st) {
+    if (count < 1 || count > 2 || r > kGramAccFloats) return hipErrorInvalidValue;
+    for (int z = 0; z < count; ++z)
+        if (batch.p[z].rows * d > INT32_MAX) return hipErrorInvalidValue;
+    // LDS fp32 atomics go at a few cycles each per CU, so the rows of C are spread over about one workgroup
+    // per CU rather than packed into as few as LDS allows (each workgroup scans all of L_idx either way)
+    const int block_rows = std::max(1, std::min(kGramAccFloats / (int)r, ((int)r * count + 255) / 256));
+    hipLaunchKernelGGL(k_gram, dim3((unsigned)((r + block_rows - 1) / block_rows), (unsigned)count), dim3(kGramThreads), 0, st,
+                       batch, (int)d, (int)r, block_rows);
     return hipGetLastError();
 }
 
@@ -250,10 +325,10 @@ hipError_t launch_reproject(const int32_t* P_idx, const float* P_val, const int3
     float* A = workspace;
     float* B = workspace + rr;
     float* X = workspace + 2 * rr;
-    hipLaunchKernelGGL(k_zero, blocks_for(2 * rr), dim3(256), 0, st, A, 2 * rr);
-    hipLaunchKernelGGL(k_gram, blocks_for(m * d * d), dim3(256), 0, st, P_idx, P_val, Pp_idx, Pp_val, m, (int)d, (int)r, A);
-    hipLaunchKernelGGL(k_gram, blocks_for(n * d * d), dim3(256), 0, st, Qp_idx, Qp_val, Q_idx, Q_val, n, (int)d, (int)r, B);
-    hipError_t e = hipGetLastError();
+    GramBatch grams{};
+    grams.p[0] = GramPair{P_idx, P_val, Pp_idx, Pp_val, m, A};
+    grams.p[1] = GramPair{Qp_idx, Qp_val, Q_idx, Q_val, n, B};
+    hipError_t e = launch_gram(grams, 2, d, r, st);
     if (e != hipSuccess) return e;
     // X = A M and X2 = (A o A) V in one launch, then M = X B and V = X2 (B o B) in another
     float* X2 = workspace + 3 * rr;
