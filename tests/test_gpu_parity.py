@@ -415,6 +415,32 @@ def test_reproject_state_against_oracle(m, n, r, d, dist, with_v):
     print(f"[ok]   reproject: M rel err {eM:.2e}", flush=True)
 
 
+def test_reproject_state_concentrated_columns():
+    """Every row of P and of P_prev has its first entry in column 0: one row block of P^T P_prev receives more
+    products than the workgroup's queue holds, so the rest takes the kernel's direct path."""
+    import torch
+    import paper_2406_10181_amd as L
+    m, n, r, d = 5000, 40, 32, 2
+    print(f"[case] reproject concentrated m={m} n={n} r={r} d={d}", flush=True)
+    rng = np.random.default_rng(6077)
+    prj = [syn.ell_projector(rows, r, d, rng, "uniform") for rows in (m, m, n, n)]
+    prj[0][0][:, 0] = 0
+    prj[1][0][:, 0] = 0
+    M = rng.standard_normal((r, r)).astype(np.float32)
+    V = (rng.standard_normal((r, r)) ** 2).astype(np.float32)
+    Mo, Vo = oracle.reproject_state(*prj[0], *prj[1], *prj[2], *prj[3], r, M, V)
+    dev = [torch.from_numpy(np.ascontiguousarray(x)).cuda() for pair in prj for x in pair]
+    Md, Vd = torch.from_numpy(M).cuda(), torch.from_numpy(V).cuda()
+    nb = L.lsp_reproject_state_workspace_bytes(r)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    L.lsp_reproject_state(*dev, m, n, r, d, Md, Vd, ws, nb, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    eM = np.abs(Md.cpu().numpy() - Mo).max() / np.abs(Mo).max()
+    eV = np.abs(Vd.cpu().numpy() - Vo).max() / np.abs(Vo).max()
+    print(f"[ok]   reproject concentrated: rel err M {eM:.2e} V {eV:.2e}", flush=True)
+    assert eM <= 2e-5 and eV <= 2e-5, (eM, eV)
+
+
 def test_reproject_state_exact_on_relabelled_projectors():
     """New projectors that relabel the old columns: P^T P_prev and Q_prev^T Q are permutation matrices and
     the moments are permuted, bit for bit."""
