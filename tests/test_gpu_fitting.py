@@ -50,6 +50,9 @@ def _check_gradient(pb, tol=GRAD_TOL):
     (2000, 64, 4, 2, "f32", "uniform"),          # rows of P^T cut into pieces: the atomic path of the row gather
     (96, 1024, 1100, 2, "bf16", "uniform"),      # more subspace columns than lanes
     (150, 264, 50, 3, "f32", "uniform"),         # r % 4 != 0: the element-wise path of the r x r products, all operand forms
+    (100, 520, 64, 16, "bf16", "uniform"),       # d = 16: two passes of eight entries on the right, four of four on the left
+    (90, 64, 8, 1, "f32", "distinct"),           # d = 1
+    (40, 8200, 32, 4, "f16", "uniform"),         # many column blocks, one slice of the subspace range each
 ])
 def test_bias_gradient_against_oracle(m, n, r, d, dtype, dist):
     _check_gradient(syn.make_problem("grad", m, n, r, d, dtype, seed=5100 + m + n, g_std=1.0, index_dist=dist))
