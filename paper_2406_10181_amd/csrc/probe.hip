@@ -8,7 +8,11 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;
-constexpr int kUnroll = 8;                                       // 16-byte vectors in flight per thread
+constexpr int kUnroll = 8;                                       // 16-byte vectors in flight per thread, read-only pass
+// The read-modify-write pass is sensitive to how much a workgroup reads before it writes: with 256 threads,
+// 1 / 2 / 4 / 6 / 8 / 16 vectors per thread reach 6.6 / 6.1 / 6.2 / 6.3 / 4.5 / 5.3 TB/s on 1 GiB.  The probe
+// reports the best plain pattern: one vector per thread, a 4 KB tile read and written back at once.
+constexpr int kUnrollRmw = 1;
 
 __global__ __launch_bounds__(kThreads) void k_probe_read(const f32x4* __restrict__ x, size_t nvec, float* __restrict__ out) {
     const size_t tile = (size_t)kThreads * kUnroll;
@@ -32,16 +36,16 @@ __global__ __launch_bounds__(kThreads) void k_probe_read(const f32x4* __restrict
 }
 
 __global__ __launch_bounds__(kThreads) void k_probe_rmw(f32x4* __restrict__ y, size_t nvec, float c) {
-    const size_t tile = (size_t)kThreads * kUnroll;
+    const size_t tile = (size_t)kThreads * kUnrollRmw;
     const size_t base = (size_t)blockIdx.x * tile + threadIdx.x;
-    f32x4 v[kUnroll];
+    f32x4 v[kUnrollRmw];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kUnrollRmw; ++u) {
         const size_t k = base + (size_t)u * kThreads;
         if (k < nvec) v[u] = __builtin_nontemporal_load(y + k);
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kUnrollRmw; ++u) {
         const size_t k = base + (size_t)u * kThreads;
         if (k < nvec) __builtin_nontemporal_store(v[u] - c, y + k);
     }
@@ -70,9 +74,9 @@ int lsp_hbm_probe_read(const void* buf, size_t bytes, void* workspace, size_t wo
 
 int lsp_hbm_probe_rmw(void* buf, size_t bytes, float c, void* stream) {
     if (!buf) return LSP_ERR_NULL;
-    if (bytes < 16 || bytes / 16 / ((size_t)kThreads * kUnroll) > 0x7FFFFFFFu) return LSP_ERR_SHAPE;
+    if (bytes < 16 || bytes / 16 / ((size_t)kThreads * kUnrollRmw) > 0x7FFFFFFFu) return LSP_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(buf) & 15u) return LSP_ERR_ALIGN;
-    const size_t nvec = bytes / 16, tile = (size_t)kThreads * kUnroll;
+    const size_t nvec = bytes / 16, tile = (size_t)kThreads * kUnrollRmw;
     hipLaunchKernelGGL(k_probe_rmw, dim3((unsigned)((nvec + tile - 1) / tile)), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
                        static_cast<f32x4*>(buf), nvec, c);
     const hipError_t e = hipGetLastError();
