@@ -146,12 +146,19 @@ __device__ __forceinline__ void build_u_tile_fast(uint8_t* smem, int2* pent, con
 // All loads of a pass (the thread's rows of Q and its R x CPT patch of W) are issued before the
 // gathers start, so one pass costs one HBM round trip; many waves per CU overlap the passes.
 template <typename D, int RG, int DD, int PS, int NT, int CPT, int kDepth, bool NORMS>
-__global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, float2* __restrict__ partial) {
+__global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, float2* __restrict__ partial, int split_from) {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int R = 4 * RG;
     constexpr int NE = CPT * DD;                                    // entries owned by a thread in one pass
     static_assert(NE % 4 == 0, "entries are loaded 4 at a time");
-    const int prob = group_find(grp.first, grp.count, (int)blockIdx.x);
+    // Row blocks from split_from on are shared by two workgroups, each with half of the passes (both build
+    // the tile of U): the last workgroups of a launch are then half as long, and the CUs finish closer together.
+    int bx = (int)blockIdx.x, half = 0, halves = 1;
+    if (bx >= split_from) {
+        const int t = bx - split_from;
+        bx = split_from + (t >> 1); half = t & 1; halves = 2;
+    }
+    const int prob = group_find(grp.first, grp.count, bx);
     typename D::elem* __restrict__ W = static_cast<typename D::elem*>(grp.W[prob]);
     const float* __restrict__ S = grp.S[prob];
     const int32_t* __restrict__ P_idx = grp.P_idx[prob];
@@ -159,7 +166,7 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, 
     const int32_t* __restrict__ Q_idx = grp.Q_idx[prob];
     const float* __restrict__ Q_val = grp.Q_val[prob];
     const int m = grp.m[prob], n = grp.n[prob];
-    const int block = (int)blockIdx.x - grp.first[prob];
+    const int block = bx - grp.first[prob];
     const int64_t i0 = (int64_t)block * R;
     int2* pent = reinterpret_cast<int2*>(smem + RG * PS);
     const f32x4* Us4 = reinterpret_cast<const f32x4*>(smem);
@@ -199,11 +206,13 @@ __global__ __launch_bounds__(NT) void k_decompress(const ApplyGroup grp, int r, 
     // (workgroups are dealt to the 8 XCDs round-robin): all workgroups read the same Q arrays, and
     // without the rotation they would all ask the same few L2 channels for the same lines at once.
     const int64_t step = (int64_t)NT * CPT;
-    const int npass = (int)((n + step - 1) / step);
-    const int rot = (int)((block / 8) % npass);
+    const int npass_all = (int)((n + step - 1) / step);
+    const int p_lo = half * ((npass_all + 1) / 2);
+    const int npass = halves == 1 ? npass_all : (half == 0 ? (npass_all + 1) / 2 : npass_all / 2);   // passes of this workgroup
+    const int rot = (int)((block / 8) % npass_all);
     auto pass_col = [&](int p) -> int64_t {
-        int q = p + rot;
-        if (q >= npass) q -= npass;
+        int q = p_lo + p + rot;
+        if (q >= npass_all) q -= npass_all;
         return (int64_t)q * step + (int64_t)threadIdx.x * CPT;
     };
     float num = 0.0f, den = 0.0f;                                   // NORMS: this thread's sums of squares
@@ -360,6 +369,12 @@ bool apply_group_uniform(const ApplyGroup& g, int32_t r, int32_t d) {
     return g.count == 1 || fast_shape(g.n[0], r, d);                // the generic kernel takes one problem at a time
 }
 
+// Row blocks at the end of a big launch of 32-row workgroups that are shared by two workgroups each: half a
+// round of the 256 CUs (measured on the seven matrices of a 6.7B-style layer: 0 / 96 / 128 / 160 / 192 / 256
+// blocks give 216 / 214 / 212 / 212 / 219 / 217 us per launch -- beyond that the second build of U costs more
+// than the shorter tail saves).
+constexpr int kTailSplitBlocks = 128;
+
 template <typename D, int RG, int PS, int NT, int CPT, int DEPTH, bool NORMS = false>
 static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st, float2* partial = nullptr) {
     using E = typename D::elem;
@@ -373,7 +388,11 @@ static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st, 
         }
     g.first[0] = 0;
     for (int p = 0; p < g.count; ++p) g.first[p + 1] = g.first[p] + (g.m[p] + RG * 4 - 1) / (RG * 4);
-    const unsigned grid = (unsigned)g.first[g.count];
+    const int row_blocks = g.first[g.count];
+    // big launches of 32-row workgroups: the last row blocks go to two workgroups each (see the kernel)
+    const int tail = (!NORMS && RG == 8) ? std::min(row_blocks, kTailSplitBlocks) : 0;
+    const int split_from = row_blocks - tail;
+    const unsigned grid = (unsigned)(row_blocks + tail);
     hipError_t e;
     // d = 16: a pass holds 32 (column, value) pairs per thread, so only one pass fits the registers
 #define LSP_LAUNCH_FAST(DDV)                                                                                   \
@@ -381,7 +400,7 @@ static hipError_t launch_d(ApplyGroup& g, int32_t r, int32_t d, hipStream_t st, 
         constexpr auto kern = k_decompress<D, RG, DDV, PS, NT, CPT, (DDV == 16 ? 1 : DEPTH), NORMS>;                  \
         constexpr size_t lds = (size_t)RG * PS + (size_t)RG * 4 * DDV * sizeof(int2);                          \
         if ((e = allow_dynamic_lds<kern>(lds)) != hipSuccess) return e;                                        \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, g, (int)r, partial);                           \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, g, (int)r, partial, split_from);               \
     } while (0)
     if (!fast_shape(g.n[0], r, d)) {
         constexpr auto kern = k_decompress_any<D, RG, NORMS>;

@@ -253,6 +253,14 @@ def test_big_grid_with_ragged_last_row_block():
     _full_check(pb, raw=False)
 
 
+def test_big_grid_with_an_odd_number_of_passes():
+    # 32-row apply workgroups of 512 threads take 1024 columns per pass: three passes here, and the last row
+    # blocks of the launch are shared by two workgroups with two passes and one
+    pb = syn.make_problem("big_odd", 16 * 1030 + 9, 3072, 512, 8, "bf16", seed=925)
+    _grouped_case([pb])
+    _full_check(pb, raw=False)
+
+
 @pytest.mark.parametrize("n,r,d,dist", [
     (1024, 1024, 2, "uniform"),       # two columns per lane, none shared
     (2048, 600, 4, "zipf"),           # hot columns split between lanes: several slots and the ordered merge
