@@ -396,6 +396,7 @@ def test_estimation_bias_is_reproducible_and_checks_arguments():
     (257, 131, 50, 3, "zipf", True),             # r not a multiple of the 64 x 64 tile, duplicates
     (128, 128, 16, 2, "distinct", False),        # first moment only
     (4096, 4096, 512, 8, "uniform", True),       # config-4 size
+    (200, 160, 1100, 4, "uniform", True),        # r past 1024 and not a multiple of the tiles of the r x r products
 ])
 def test_reproject_state_against_oracle(m, n, r, d, dist, with_v):
     import torch
